@@ -1,0 +1,451 @@
+"""Pins for the CPU oracles: each test fixes the oracle to something other than itself --
+values the paper prints, closed forms, invariants of the normalised adjacency, special
+graphs that reduce to textbook results, independent library routines (torch autograd,
+scipy.sparse, scipy.special), finite differences, brute force on tiny inputs.
+
+Citations are to arXiv 2110.02987 (sections / equations).  All tests here run on the CPU.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+import scipy.special
+import torch
+
+from oracle import gad_dense as T0
+from oracle import gad_csr as T1
+from paper_2110_02987_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _ids(n):
+    return np.arange(n, dtype=np.int64), np.zeros(0, dtype=np.int64)
+
+
+def _graph_from_pairs(pairs, n):
+    src = np.array([a for a, _ in pairs], dtype=np.int64)
+    dst = np.array([b for _, b in pairs], dtype=np.int64)
+    loc, halo = _ids(n)
+    return src, dst, n, loc, halo
+
+
+def _random_problem(n, m, dims, seed, n_halo=0, n_global=None, masked=True):
+    rng = np.random.default_rng(seed)
+    n_global = n_global or n
+    perm = rng.permutation(n_global).astype(np.int64)
+    src = perm[rng.integers(0, n_global, m)]
+    dst = perm[rng.integers(0, n_global, m)]
+    loc, halo = perm[: n - n_halo], perm[n - n_halo: n]
+    X = rng.standard_normal((n, dims[0]))
+    Ws = [rng.standard_normal((dims[l], dims[l + 1])) * 0.3 for l in range(len(dims) - 1)]
+    y = rng.integers(0, dims[-1], n).astype(np.int32)
+    mask = np.ones(n, dtype=np.uint8)
+    if masked:
+        mask[rng.random(n) < 0.3] = 0
+    return dict(src=src, dst=dst, n_global=n_global, local_ids=loc, halo_ids=halo), X, Ws, y, mask
+
+
+# --------------------------------------------------------------------------- zeta: the paper's worked example
+
+def _load_example():
+    rows = []
+    with open(os.path.join(GOLDEN, "zeta_example.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, edges, val = line.split()
+            pairs = [tuple(int(t) for t in e.split("-")) for e in edges.split(",")]
+            rows.append((name, pairs, float(val)))
+    return rows
+
+
+@pytest.mark.parametrize("tier", ["T0", "T1"])
+def test_zeta_worked_example(tier):
+    """Section 3.4.1, Example (Fig. 4): printed 3.75 > 3.61 > 3.59 with d(i,j) = 0.
+
+    The printed magnitudes need beta = 0.1 (the paper's 'normally beta = 1' gives them / 10;
+    a common factor on all zeta cancels in Eq. 15)."""
+    vals = {}
+    for name, pairs, printed in _load_example():
+        src, dst, n, loc, halo = _graph_from_pairs(pairs, 4)
+        V = np.ones((4, 3)) * 0.7                       # identical node vectors: d(i,j) = 0
+        if tier == "T0":
+            A = T0.adjacency_dense(src, dst, n, loc, halo)
+            z, spp, var, _ = T0.zeta(T0.degrees(A), V, beta=0.1)
+        else:
+            g = T1.build(src, dst, n, loc, halo)
+            z, spp, var, _ = T1.zeta(g, V, beta=0.1)
+        assert var == pytest.approx(0.0, abs=1e-30)
+        assert round(z, 2) == printed, (name, z)
+        vals[name] = z
+        z1 = (T0.zeta(T0.degrees(T0.adjacency_dense(src, dst, n, loc, halo)), V, beta=1.0)[0])
+        assert z1 == pytest.approx(z / 10.0, rel=1e-12)  # beta = 1: same ordering, a tenth of the size
+    assert vals["fig4a"] > vals["fig4c"] > vals["fig4b"]
+
+
+def test_zeta_example_discriminates_other_readings():
+    """The printed numbers rule out the neighbouring readings of p(v) and of the pair set."""
+    deg = np.array([3, 2, 2, 1], dtype=np.float64)
+    # degree counted with the self loop: p = (4,3,3,2)/12 -> 3.68, not 3.59
+    p = (deg + 1) / (deg + 1).sum()
+    assert round(10 * (1 - np.sum(p * p)) / 2, 2) == 3.68
+    # pairs restricted to edges (4-cycle): 4 * (1/4)^2 * 10 = 2.5, not 3.75
+    assert 10 * 4 * 0.25 * 0.25 == 2.5
+    # ordered pairs would double it: 7.5
+    assert round(10 * (1 - 4 * 0.0625), 2) == 7.5
+
+
+def test_pair_probability_sum_closed_form_and_property2():
+    """Numerator of Eq. 14: literal double sum == (1 - sum p^2)/2; Property 2: maximal for equal degrees."""
+    rng = np.random.default_rng(3)
+    for n in (2, 5, 37, 300):
+        deg = rng.integers(0, 50, n)
+        deg[0] = 1
+        p = deg / deg.sum()
+        brute = sum(p[i] * p[j] for i, j in itertools.combinations(range(n), 2))
+        assert T0.pair_probability_sum(deg) == pytest.approx(brute, rel=1e-12)
+        assert brute == pytest.approx((1 - np.sum(p * p)) / 2, rel=1e-12)
+        regular = T0.pair_probability_sum(np.full(n, 7))
+        assert regular == pytest.approx((1 - 1 / n) / 2, rel=1e-12)
+        assert regular >= T0.pair_probability_sum(deg) - 1e-15
+    # the proof's own family p = (1 +- t)/n: decreasing in |t|
+    n = 10
+    prev = None
+    for t in (0.0, 0.2, 0.5, 0.9):
+        pr = np.r_[np.full(n // 2, 1 + t), np.full(n // 2, 1 - t)]
+        v = T0.pair_probability_sum(pr * 1000)
+        assert prev is None or v < prev
+        prev = v
+    # large-n branch (closed form inside the oracle) against the literal sum on a prefix-scaled input
+    deg = rng.integers(1, 9, 3000)
+    p = deg / deg.sum()
+    assert T0.pair_probability_sum(deg) == pytest.approx((1 - (p * p).sum()) / 2, rel=1e-12)
+    csum = np.cumsum(p[::-1])[::-1]
+    assert T0.pair_probability_sum(deg) == pytest.approx(np.sum(p[:-1] * csum[1:]), rel=1e-10)
+
+
+def test_aggregate_distance_is_rms_pairwise_distance():
+    """sum_{i<j} ||v_i - v_j||^2 = n * sum_i r_i  =>  D = sqrt(2 var) is the RMS distance over all ordered pairs."""
+    rng = np.random.default_rng(5)
+    for n, F in ((2, 1), (17, 3), (400, 8)):
+        V = rng.standard_normal((n, F)) * 3 + 1.5
+        var, D, r = T0.aggregate_distance(V)
+        brute = 0.0
+        for i in range(n):
+            diff = V[i + 1:] - V[i]
+            brute += np.sum(diff * diff)
+        assert n * r.sum() == pytest.approx(brute, rel=1e-10)
+        assert D == pytest.approx(np.sqrt(2 * brute / (n * n)), rel=1e-10)
+        assert var == pytest.approx(V.var(axis=0).sum(), rel=1e-12)      # numpy's population variance, per dimension
+    V = np.tile(rng.standard_normal(6), (9, 1))
+    assert T0.aggregate_distance(V)[1] == pytest.approx(0.0, abs=1e-12)
+    # zeta with equal vectors = S_pp / beta ; zeta decreases when vectors spread out
+    deg = np.array([2, 2, 3, 1, 2, 2, 2, 1, 1])
+    assert T0.zeta(deg, V, beta=1.0)[0] == pytest.approx(T0.pair_probability_sum(deg), rel=1e-12)
+    assert T0.zeta(deg, V + rng.standard_normal(V.shape), 1.0)[0] < T0.zeta(deg, V, 1.0)[0]
+    assert T0.zeta(np.zeros(4, dtype=int), V[:4], 1.0)[0] == 0.0          # edgeless convention
+
+
+# --------------------------------------------------------------------------- graph build
+
+def test_csr_hand_example():
+    """Algorithm 1 (last step): g' = induced graph on v + v'.  Hand-built case with reversed and repeated
+    pairs, self pairs, pairs leaving the node set, and ids outside the global range."""
+    # global ids: local = [10, 3, 7], halo = [5, 0]  ->  rows 0..4
+    local = np.array([10, 3, 7], dtype=np.int64)
+    halo = np.array([5, 0], dtype=np.int64)
+    src = np.array([10, 3, 3, 7, 5, 0, 5, 8, 10, 2, 7, 99, -1], dtype=np.int64)
+    dst = np.array([3, 10, 3, 5, 7, 5, 0, 10, 8, 9, 7, 3, 10], dtype=np.int64)
+    # kept undirected edges: {10,3} = rows {0,1}; {7,5} = rows {2,3}; {0,5} = rows {4,3}
+    exp_rowptr = np.array([0, 2, 4, 6, 9, 11], dtype=np.int64)
+    exp_col = np.array([0, 1, 0, 1, 2, 3, 2, 3, 4, 3, 4], dtype=np.int32)
+    # T0 has no range guard on pairs: hand it the in-range pairs only (the others cannot be in the node set)
+    ok = (src >= 0) & (src < 12) & (dst >= 0) & (dst < 12)
+    A = T0.adjacency_dense(src[ok], dst[ok], 12, local, halo)
+    rp, ci = T0.csr_of(A)
+    assert np.array_equal(rp, exp_rowptr) and np.array_equal(ci, exp_col)
+    g = T1.build(src, dst, 12, local, halo)
+    assert np.array_equal(g.rowptr, exp_rowptr) and np.array_equal(g.colidx, exp_col)
+    assert g.colidx.dtype == np.int32 and g.rowptr.dtype == np.int64
+    assert np.array_equal(g.deg, [1, 1, 1, 2, 1])
+    assert np.array_equal(T0.degrees(A), [1, 1, 1, 2, 1])
+    np.testing.assert_array_equal(g.dinv, (1 / np.sqrt(np.array([2, 2, 2, 3, 2.0]))).astype(np.float32))
+
+
+def test_build_rejects_bad_ids():
+    src = np.array([0], dtype=np.int64)
+    for tier in (lambda *a: T1.build(*a), lambda *a: T0.adjacency_dense(*a)):
+        with pytest.raises(ValueError):
+            tier(src, src, 4, np.array([0, 1, 1], dtype=np.int64), np.zeros(0, dtype=np.int64))
+        with pytest.raises(ValueError):
+            tier(src, src, 4, np.array([0, 1], dtype=np.int64), np.array([1], dtype=np.int64))
+        with pytest.raises(ValueError):
+            tier(src, src, 4, np.array([0, 4], dtype=np.int64), np.zeros(0, dtype=np.int64))
+        with pytest.raises(ValueError):
+            tier(src, src, 4, np.array([-1], dtype=np.int64), np.zeros(0, dtype=np.int64))
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_csr_t1_matches_t0_and_scipy(seed):
+    gr, X, Ws, y, mask = _random_problem(300, 2500, (5, 4, 3), seed, n_halo=40, n_global=500)
+    A = T0.adjacency_dense(**gr)
+    rp, ci = T0.csr_of(A)
+    g = T1.build(**gr)
+    assert np.array_equal(g.rowptr, rp) and np.array_equal(g.colidx, ci)
+    # independent route: scipy COO -> CSR of the symmetrised, de-duplicated pattern
+    lut = np.full(gr["n_global"], -1)
+    lut[np.r_[gr["local_ids"], gr["halo_ids"]]] = np.arange(300)
+    r, c = lut[gr["src"]], lut[gr["dst"]]
+    k = (r >= 0) & (c >= 0)
+    M = sp.coo_matrix((np.ones(k.sum()), (r[k], c[k])), shape=(300, 300))
+    M = ((M + M.T + sp.eye(300)) > 0).tocsr()
+    M.sort_indices()
+    assert np.array_equal(M.indptr, g.rowptr) and np.array_equal(M.indices, g.colidx)
+    assert np.array_equal(g.deg, np.diff(g.rowptr) - 1)
+    # strictly ascending columns and one self loop per row
+    for i in range(300):
+        seg = g.colidx[g.rowptr[i]: g.rowptr[i + 1]]
+        assert np.all(np.diff(seg) > 0) and np.sum(seg == i) == 1
+
+
+# --------------------------------------------------------------------------- normalised adjacency (A~ of Eq. 7)
+
+def test_normalised_adjacency_hand_values():
+    """3-node path 0-1-2: d~ = (2,3,2)."""
+    A = T0.adjacency_dense(*_graph_from_pairs([(0, 1), (1, 2)], 3))
+    At = T0.normalized_adjacency(A)
+    exp = np.array([[1 / 2, 1 / np.sqrt(6), 0], [1 / np.sqrt(6), 1 / 3, 1 / np.sqrt(6)], [0, 1 / np.sqrt(6), 1 / 2]])
+    np.testing.assert_allclose(At, exp, rtol=1e-15)
+    g = T1.build(*_graph_from_pairs([(0, 1), (1, 2)], 3))
+    np.testing.assert_allclose(T1.spmm(g, np.eye(3)), exp, rtol=1e-15)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_normalised_adjacency_invariants(seed):
+    gr, *_ = _random_problem(200, 900, (3, 2), seed, n_halo=30, n_global=260)
+    A = T0.adjacency_dense(**gr)
+    At = T0.normalized_adjacency(A)
+    assert np.array_equal(A, A.T) and np.all(np.diag(A) == 0)
+    np.testing.assert_allclose(At, At.T, rtol=0, atol=0)
+    dt = 1.0 + A.sum(axis=1)
+    np.testing.assert_allclose(At @ np.sqrt(dt), np.sqrt(dt), rtol=1e-13)       # eigenvalue 1, eigenvector sqrt(d~)
+    ev = np.linalg.eigvalsh(At)
+    assert ev.max() <= 1 + 1e-12 and ev.min() > -1 + 1e-12                       # spectral radius <= 1
+    g = T1.build(**gr)
+    np.testing.assert_allclose(T1.spmm(g, np.sqrt(dt)[:, None])[:, 0], np.sqrt(dt), rtol=1e-13)
+    np.testing.assert_allclose(T1.spmm(g, np.eye(200)), At, rtol=1e-13, atol=1e-16)
+    Tm = np.random.default_rng(seed).standard_normal((200, 7))
+    Ms = sp.csr_matrix(At)
+    np.testing.assert_allclose(T1.spmm(g, Tm), Ms @ Tm, rtol=1e-12, atol=1e-14)
+    rows = np.array([0, 199, 57, 57, 3], dtype=np.int64)
+    np.testing.assert_allclose(T1.spmm_rows(g, Tm.astype(np.float32), rows),
+                               (At @ Tm.astype(np.float32).astype(np.float64))[rows], rtol=1e-12, atol=1e-14)
+
+
+def test_special_graphs():
+    n = 9
+    loc, halo = _ids(n)
+    none = np.zeros(0, dtype=np.int64)
+    # no edges: A~ = I, so the GCN is an MLP applied row by row
+    At = T0.normalized_adjacency(T0.adjacency_dense(none, none, n, loc, halo))
+    np.testing.assert_array_equal(At, np.eye(n))
+    # complete graph: A~ = (1/n) 1 1^T, aggregation = global mean
+    pairs = list(itertools.combinations(range(n), 2))
+    At = T0.normalized_adjacency(T0.adjacency_dense(*_graph_from_pairs(pairs, n)))
+    np.testing.assert_allclose(At, np.full((n, n), 1 / n), rtol=1e-15)
+    g = T1.build(*_graph_from_pairs(pairs, n))
+    X = np.random.default_rng(0).standard_normal((n, 4))
+    np.testing.assert_allclose(T1.spmm(g, X), np.tile(X.mean(axis=0), (n, 1)), rtol=1e-13)
+    # cycle (2-regular): A~ = (A + I) / 3
+    cyc = [(i, (i + 1) % n) for i in range(n)]
+    A = T0.adjacency_dense(*_graph_from_pairs(cyc, n))
+    np.testing.assert_allclose(T0.normalized_adjacency(A), (A + np.eye(n)) / 3, rtol=1e-15)
+
+
+# --------------------------------------------------------------------------- forward / loss / backward (Eq. 7-10)
+
+def _mlp_by_loops(X, Ws):
+    """Row-by-row MLP with python loops (what Eq. 8 reduces to when A~ = I)."""
+    out = []
+    for x in X:
+        h = list(x)
+        for l, W in enumerate(Ws):
+            h = [sum(h[k] * W[k][j] for k in range(len(h))) for j in range(W.shape[1])]
+            if l < len(Ws) - 1:
+                h = [max(v, 0.0) for v in h]
+        out.append(h)
+    return np.array(out)
+
+
+@pytest.mark.parametrize("tier", ["T0", "T1"])
+def test_edgeless_graph_is_mlp(tier):
+    rng = np.random.default_rng(1)
+    n, dims = 6, (4, 5, 3)
+    X = rng.standard_normal((n, dims[0]))
+    Ws = [rng.standard_normal((dims[l], dims[l + 1])) for l in range(2)]
+    y = rng.integers(0, 3, n).astype(np.int32)
+    mask = np.ones(n, dtype=np.uint8)
+    none = np.zeros(0, dtype=np.int64)
+    loc, halo = _ids(n)
+    if tier == "T0":
+        f = T0.forward(T0.normalized_adjacency(T0.adjacency_dense(none, none, n, loc, halo)), X, Ws, y, mask)
+    else:
+        f = T1.forward(T1.build(none, none, n, loc, halo), X, Ws, y, mask)
+    Z = _mlp_by_loops(X, Ws)
+    np.testing.assert_allclose(f["Z"], Z, rtol=1e-12, atol=1e-14)
+    loss = -sum(np.log(np.exp(Z[i, y[i]]) / np.exp(Z[i]).sum()) for i in range(n))
+    assert f["loss"] == pytest.approx(loss, rel=1e-12)
+
+
+def test_two_layer_structure_eq8():
+    """Eq. 8 written out literally for two layers."""
+    gr, X, Ws, y, mask = _random_problem(40, 120, (6, 5, 4), 7)
+    At = T0.normalized_adjacency(T0.adjacency_dense(**gr))
+    f = T0.forward(At, X, Ws, y, mask)
+    Z = At @ np.maximum(At @ X @ Ws[0], 0) @ Ws[1]
+    np.testing.assert_allclose(f["Z"], Z, rtol=1e-13)
+    np.testing.assert_allclose(f["yhat"], scipy.special.softmax(Z, axis=1), rtol=1e-12)
+    # association (A~ H) W == A~ (H W)
+    np.testing.assert_allclose(f["P"][0], At @ (X @ Ws[0]), rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("c_mode", ["sum", "mean"])
+def test_loss_properties(c_mode):
+    gr, X, Ws, y, mask = _random_problem(60, 200, (5, 6, 7), 11)
+    c = 1.0 if c_mode == "sum" else 1.0 / mask.sum()
+    At = T0.normalized_adjacency(T0.adjacency_dense(**gr))
+    C = 7
+    f0 = T0.forward(At, X, [np.zeros_like(w) for w in Ws], y, mask, c)
+    assert f0["loss"] == pytest.approx(c * mask.sum() * np.log(C), rel=1e-13)     # uniform prediction
+    f = T0.forward(At, X, Ws, y, mask, c)
+    ref = torch.nn.functional.cross_entropy(torch.tensor(f["Z"])[mask.astype(bool)],
+                                            torch.tensor(y[mask.astype(bool)]).long(), reduction="sum").item()
+    assert f["loss"] == pytest.approx(c * ref, rel=1e-12)                          # library softmax-CE
+    lse = scipy.special.logsumexp(f["Z"], axis=1)
+    assert f["loss"] == pytest.approx(c * np.sum((lse - f["Z"][np.arange(60), y])[mask == 1]), rel=1e-12)
+    dW, Gs = T0.backward(At, Ws, f, y, mask, c)
+    np.testing.assert_allclose(Gs[-1].sum(axis=1), 0, atol=1e-15)                  # rows of yhat - onehot sum to 0
+    assert np.all(Gs[-1][mask == 0] == 0)                                          # masked nodes carry no loss
+    y2 = y.copy()
+    y2[mask == 0] = (y2[mask == 0] + 1) % C
+    assert T0.forward(At, X, Ws, y2, mask, c)["loss"] == f["loss"]
+
+
+@pytest.mark.parametrize("tier", ["T0", "T1"])
+@pytest.mark.parametrize("dims", [(5, 4, 3), (4, 6, 5, 3), (3, 7, 4, 5, 2)])
+def test_gradients_finite_differences_and_autograd(tier, dims):
+    """dW of Eq. 7-10 against (a) central finite differences of the oracle's own loss and
+    (b) torch's reverse-mode autograd through an independently written dense forward."""
+    gr, X, Ws, y, mask = _random_problem(50, 160, dims, 21 + len(dims), n_halo=8, n_global=70)
+    c = 0.37
+    A = T0.adjacency_dense(**gr)
+    At = T0.normalized_adjacency(A)
+    if tier == "T0":
+        fwd = lambda W: T0.forward(At, X, W, y, mask, c)
+        dW, _ = T0.backward(At, Ws, fwd(Ws), y, mask, c)
+    else:
+        g = T1.build(**gr)
+        fwd = lambda W: T1.forward(g, X, W, y, mask, c)
+        dW, _ = T1.backward(g, Ws, fwd(Ws), y, mask, c)
+    rng = np.random.default_rng(0)
+    h = 1e-5
+    for l, W in enumerate(Ws):
+        for _ in range(32):
+            i, j = rng.integers(0, W.shape[0]), rng.integers(0, W.shape[1])
+            Wp = [w.copy() for w in Ws]
+            Wm = [w.copy() for w in Ws]
+            Wp[l][i, j] += h
+            Wm[l][i, j] -= h
+            fd = (fwd(Wp)["loss"] - fwd(Wm)["loss"]) / (2 * h)
+            assert dW[l][i, j] == pytest.approx(fd, rel=2e-6, abs=1e-9), (l, i, j)
+    # autograd through torch (float64)
+    tA = torch.tensor(At)
+    tW = [torch.tensor(w, requires_grad=True) for w in Ws]
+    H = torch.tensor(X)
+    for l, w in enumerate(tW):
+        H = tA @ H @ w
+        if l < len(tW) - 1:
+            H = torch.relu(H)
+    m = torch.tensor(mask.astype(bool))
+    loss = c * torch.nn.functional.cross_entropy(H[m], torch.tensor(y).long()[m], reduction="sum")
+    loss.backward()
+    assert fwd(Ws)["loss"] == pytest.approx(loss.item(), rel=1e-12)
+    for l in range(len(Ws)):
+        np.testing.assert_allclose(dW[l], tW[l].grad.numpy(), rtol=1e-9, atol=1e-12)
+
+
+def test_t1_matches_t0_on_tiny_workload():
+    """The first synthetic workload (4,096 nodes, 2-layer 128-64-16) end to end, T1 against the dense definition."""
+    cfg = wl.CONFIGS["tiny"]
+    gr = wl.make_graph(cfg)
+    X = wl.make_features(cfg.n, cfg.dims[0])
+    Ws = wl.make_weights(cfg.dims)
+    y = wl.make_labels(cfg.n, cfg.dims[-1])
+    mask = wl.make_mask(cfg)
+    c = 1.0 / mask.sum()
+    A = T0.adjacency_dense(**gr)
+    At = T0.normalized_adjacency(A)
+    g = T1.build(**gr)
+    rp, ci = T0.csr_of(A)
+    assert np.array_equal(rp, g.rowptr) and np.array_equal(ci, g.colidx)
+    assert abs(g.nnz - 36_864) < 400            # ~ n * (avg degree 8 + self loop)
+    f0 = T0.forward(At, X, Ws, y, mask, c)
+    f1 = T1.forward(g, X, Ws, y, mask, c)
+    np.testing.assert_allclose(f1["Z"], f0["Z"], rtol=1e-10, atol=1e-12)
+    assert f1["loss"] == pytest.approx(f0["loss"], rel=1e-12)
+    d0, _ = T0.backward(At, Ws, f0, y, mask, c)
+    d1, _ = T1.backward(g, Ws, f1, y, mask, c)
+    for a, b in zip(d1, d0):
+        np.testing.assert_allclose(a, b, rtol=1e-9, atol=1e-14)
+    z0 = T0.zeta(T0.degrees(A), X, 1.0)
+    z1 = T1.zeta(g, X, 1.0)
+    for a, b in zip(z1[:3], z0[:3]):
+        assert a == pytest.approx(b, rel=1e-12)
+    np.testing.assert_allclose(z1[3], z0[3], rtol=1e-12)
+
+
+# --------------------------------------------------------------------------- consensus (Eq. 11, Eq. 15)
+
+@pytest.mark.parametrize("mod", [T0, T1])
+def test_weighted_consensus_pins(mod):
+    rng = np.random.default_rng(2)
+    bufs = [rng.standard_normal(1000) for _ in range(5)]
+    z = rng.random(5) + 0.1
+    out = mod.weighted_consensus(bufs, z)
+    # literal Eq. 15 element by element
+    for e in (0, 17, 999):
+        assert out[e] == pytest.approx(sum(z[i] * bufs[i][e] for i in range(5)) / z.sum(), rel=1e-13)
+    np.testing.assert_allclose(mod.weighted_consensus(bufs, np.full(5, 3.3)), T0.plain_consensus(bufs), rtol=1e-13)
+    np.testing.assert_allclose(T0.plain_consensus(bufs), np.mean(bufs, axis=0), rtol=1e-13)   # Eq. 11
+    np.testing.assert_array_equal(mod.weighted_consensus(bufs[:1], [0.4]), bufs[0])            # K = 1
+    np.testing.assert_allclose(mod.weighted_consensus([bufs[0]] * 4, z[:4]), bufs[0], rtol=1e-14)
+    perm = [3, 0, 4, 1, 2]
+    np.testing.assert_allclose(mod.weighted_consensus([bufs[i] for i in perm], z[perm]), out, rtol=1e-13)
+    np.testing.assert_allclose(mod.weighted_consensus(bufs, 7 * z), out, rtol=1e-13)           # scale of zeta cancels
+    np.testing.assert_allclose(mod.weighted_consensus([np.ones(3)] * 5, z), 1.0, rtol=1e-15)  # weights sum to 1
+    for bad in ([0, 0, 0, 0, 0], [1, -1, 1, 1, 1], [1, np.nan, 1, 1, 1], [1, np.inf, 1, 1, 1]):
+        with pytest.raises(ValueError):
+            mod.weighted_consensus(bufs, bad)
+
+
+# --------------------------------------------------------------------------- input generators
+
+def test_workload_shapes():
+    cfg = wl.CONFIGS["reddit_part"]
+    assert cfg.n == 69_000 and cfg.dims == (602, 256, 41) and cfg.n_params == 602 * 256 + 256 * 41
+    assert wl.CONFIGS["products_part"].n_params == 103_168
+    g = wl.make_graph(wl.CONFIGS["products_small"])
+    ids = np.r_[g["local_ids"], g["halo_ids"]]
+    assert np.unique(ids).size == ids.size and ids.max() < g["n_global"]
+    inset = np.isin(g["src"], ids) & np.isin(g["dst"], ids)
+    assert 0.85 < inset.mean() < 0.95                       # ~10 % of the pairs leave the node set
+    g2 = wl.make_graph(wl.CONFIGS["products_small"])
+    assert np.array_equal(g["src"], g2["src"]) and np.array_equal(g["halo_ids"], g2["halo_ids"])
+    x = np.array([1.0, 1.00390625, 1.01171875, -3.3], dtype=np.float32)
+    b = wl.to_bf16_rne(x)
+    assert np.array_equal(wl.bf16_to_f32(b), torch.tensor(x).to(torch.bfloat16).float().numpy())
+    W = wl.make_weights((100, 256))
+    assert np.abs(W[0]).max() <= np.sqrt(6 / 356) and W[0].dtype == np.float32
