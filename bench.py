@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the GAD per-processor hot path on one MI355X.
+
+One "step" = one pass of the per-iteration hot path over one augmented subgraph resident in HBM:
+gcn_forward + gcn_backward (full batch: one pass = one epoch of that subgraph), subgraph_variance on the
+per-node gradients, and the K-way weighted_consensus of parameter copies.  The CSR build (a load-time
+step) is timed separately and reported as `build_ms`.
+
+Prints ONE JSON line (see README for the fields).  `value` = layer-edges per second:
+n_layers * nnz(A+I) / (forward + backward time), i.e. the per-layer edge rate of a full fwd+bwd.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="products_part")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-reps", type=int, default=20, help="standalone launches of the dominant kernel")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs one augmented subgraph on ONE GPU; the only cross-GPU step of the method "
+              "(the weighted all-reduce of Eq. 15) is not part of it. Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2110_02987_amd import gad, workloads as wl
+
+    cfg = wl.CONFIGS[args.workload]
+    dims, L = list(cfg.dims), cfg.n_layers
+    torch.cuda.set_device(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    # ---- inputs (synthetic, seeded), resident in HBM before anything is timed
+    gr = wl.make_graph(cfg)
+    X = wl.make_features(cfg.n, dims[0])
+    Ws = wl.make_weights(dims)
+    y = wl.make_labels(cfg.n, dims[-1])
+    mask = wl.make_mask(cfg)
+    c = 1.0 / float(mask.sum())
+    src, dst = dev(gr["src"]), dev(gr["dst"])
+    loc, halo = dev(gr["local_ids"]), dev(gr["halo_ids"])
+    Xd, Wd, yd, md = dev(X), [dev(w) for w in Ws], dev(y), dev(mask)
+    K = max(cfg.consensus_k, 1)
+    copies = [dev(p) for p in wl.make_param_copies(dims, K)]
+    torch.cuda.synchronize()
+
+    t0 = time.perf_counter()
+    g = gad.build_subgraph(src, dst, gr["n_global"], loc, halo)
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - t0) * 1e3
+    del src, dst
+
+    ws = gad.alloc_workspace(g, dims)
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    dW = [torch.empty_like(w) for w in Wd]
+    G_last = torch.empty((g.n, dims[-1]), device="cuda")
+    G_out = [None] * (L - 1) + [G_last]
+    out3 = torch.zeros(3, dtype=torch.float64, device="cuda")
+    consensus = torch.empty(cfg.n_params, device="cuda")
+    zetas = [1.0 + 0.1 * k for k in range(K)]
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(record=None):
+        e = [ev() for _ in range(4)] if record is not None else None
+        if e: e[0].record()
+        gad.gcn_forward(g, Xd, dims, Wd, yd, md, c, ws, None, loss)
+        if e: e[1].record()
+        gad.gcn_backward(g, Xd, dims, Wd, ws, dW, G_out)
+        if e: e[2].record()
+        gad.subgraph_variance(g, G_last, 1.0, out3)
+        gad.weighted_consensus(copies, zetas, consensus)
+        if e:
+            e[3].record()
+            record.append(e)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    rec = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(rec)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in rec]))
+    bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in rec]))
+    tail_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in rec]))
+    epoch_ms = fwd_ms + bwd_ms
+    value = L * g.nnz / (epoch_ms * 1e-3)
+
+    # ---- dominant kernel: the SpMM at each width the step uses, timed alone with events on the launch stream
+    widths = []
+    for l in range(L):
+        w = dims[l] if dims[l] <= dims[l + 1] else dims[l + 1]
+        widths.append(w)                                   # forward
+        if not (l == 0 and dims[l] <= dims[l + 1]):
+            widths.append(w)                               # backward (layer 1 needs none when it aggregates first)
+    spmm = {}
+    for w in sorted(set(widths)):
+        ld = (w + 15) // 16 * 16
+        T = torch.randn((g.n, ld), device="cuda")
+        O = torch.empty_like(T)
+        for _ in range(3):
+            gad.spmm(g, T, O, w)
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(args.kernel_reps):
+            gad.spmm(g, T, O, w)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / args.kernel_reps
+        compulsory = 4 * g.nnz + 12 * g.n + 2 * g.n * w * 4
+        gather = g.nnz * (4 + w * 4) + g.n * (12 + w * 4)
+        spmm[w] = dict(ms=ms, launches_per_step=widths.count(w), edges_per_s=g.nnz / (ms * 1e-3),
+                       compulsory_GBps=compulsory / ms * 1e-6, gather_model_GBps=gather / ms * 1e-6,
+                       compulsory_bytes=compulsory, gather_model_bytes=gather)
+        del T, O
+    dom = max(spmm, key=lambda w: spmm[w]["ms"] * spmm[w]["launches_per_step"])
+    roofline = dict(bound="hbm", kernel=f"spmm_rows width {dom} f32", achieved=spmm[dom]["compulsory_GBps"],
+                    peak=HBM_PEAK_GBPS, unit="GB/s", frac=spmm[dom]["compulsory_GBps"] / HBM_PEAK_GBPS,
+                    traffic=None, avg_launch_ms=spmm[dom]["ms"], model="compulsory: 4*nnz + 12*n + 2*n*w*4 bytes",
+                    gather_model_GBps=spmm[dom]["gather_model_GBps"],
+                    gather_model_frac=spmm[dom]["gather_model_GBps"] / HBM_PEAK_GBPS)
+    tr = os.path.join(ROOT, "profiles", f"spmm_traffic_{cfg.name}.json")
+    if os.path.exists(tr):          # HBM bytes per launch from rocprofv3 --pmc runs (see profiles/)
+        t = json.load(open(tr)).get(str(dom))
+        if t:
+            roofline["traffic"] = t["hbm_bytes_per_launch"]
+            roofline["measured_hbm_frac"] = t["hbm_bytes_per_launch"] / (spmm[dom]["ms"] * 1e-3) / (HBM_PEAK_GBPS * 1e9)
+
+    out = dict(metric="GCN fwd+bwd edges/s per layer and epoch ms per subgraph; SpMM % of HBM peak",
+               value=value, unit="edges/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step,
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32", data="synthetic",
+               config=dict(workload=f"{cfg.name}: n={g.n} ({cfg.n_local} local + {cfg.n_halo} halo), nnz={g.nnz}, "
+                                    f"GCN {'-'.join(map(str, dims))}, consensus K={K}",
+                           n=g.n, nnz=g.nnz, dims=dims),
+               epoch_ms=epoch_ms, forward_ms=fwd_ms, backward_ms=bwd_ms, variance_consensus_ms=tail_ms,
+               build_ms=build_ms, spmm={str(k): v for k, v in spmm.items()}, roofline=roofline)
+
+    # ---- the oracle, as it stands, on the host cores (reported baseline, not a target)
+    if not args.no_cpu_baseline:
+        from oracle import gad_csr as T1
+        t0 = time.perf_counter()
+        ref = T1.build(**gr)
+        cpu_build = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        f = T1.forward(ref, X, Ws, y, mask, c)
+        T1.backward(ref, Ws, f, y, mask, c)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = dict(value=L * ref.nnz / cpu_s, unit="edges/s", cores=int(T1.lib().t1_num_threads()),
+                                   kind="oracle", sample=f"one full forward+backward of the same workload "
+                                   f"({cpu_s:.1f} s; CSR build {cpu_build:.1f} s not included), float64",
+                                   epoch_ms=cpu_s * 1e3)
+        out["loss_gpu"], out["loss_oracle"] = float(loss.item()), f["loss"]
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

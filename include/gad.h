@@ -1,0 +1,163 @@
+/* libgad -- C ABI of the MI355X (gfx950) hot path of GAD's per-processor GCN training step.
+ *
+ * Paper: "Distributed Optimization of Graph Convolutional Network using Subgraph Variance"
+ * (arXiv 2110.02987).  One processor holds one augmented subgraph g' = (v + v', e + e')
+ * (Algorithm 1, last step; Algorithm 2, Require) and runs, per iteration, the forward
+ * propagation of Eq. 7/8, the loss and gradient of Eq. 9/10 (Algorithm 2, the two steps inside
+ * the per-processor loop), and then takes part in the weighted global consensus of Eq. 15 with
+ * the variance-based importance zeta of Eq. 14.
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer unless its comment says "host".
+ *  - Matrices are row-major.  "ld" is the leading dimension in elements.
+ *  - The caller owns every buffer it passes in, including the workspace.  The library owns only
+ *    gad_graph objects (create / destroy pair) and scratch memory that lives inside one call.
+ *  - All calls enqueue work on `hip_stream` (a hipStream_t, NULL = default stream) and return
+ *    without synchronising, except gad_build_subgraph, which synchronises the stream.
+ *  - Every function returns a gad_status.  Arguments are validated on the host before any kernel
+ *    is launched; nothing is launched when the status is an argument error.  gad_last_error()
+ *    returns a thread-local, statically stored message for the last failure on this thread.
+ *  - Node order is part of the contract: row k < n_local is local_ids[k]; row n_local + j is
+ *    halo_ids[j].  No internal reordering is visible through the interface.
+ */
+#ifndef GAD_H_
+#define GAD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gad_graph gad_graph; /* opaque: device CSR of A + I, degrees, d~^-1/2, SpMM schedule */
+
+typedef enum {
+  GAD_F32 = 0, /* float32 storage, float32 accumulation */
+  GAD_BF16 = 1 /* bfloat16 storage of features / activations, float32 accumulation, float32 weights */
+} gad_dtype;
+
+typedef enum {
+  GAD_OK = 0,
+  GAD_ERR_NULL = -1,        /* a required pointer is NULL */
+  GAD_ERR_SHAPE = -2,       /* negative / zero / inconsistent sizes */
+  GAD_ERR_ID_RANGE = -3,    /* a local or halo id lies outside [0, n_global) */
+  GAD_ERR_ID_DUP = -4,      /* an id occurs twice within or across local_ids and halo_ids */
+  GAD_ERR_WORKSPACE = -5,   /* workspace too small or misaligned (needs 256-byte alignment) */
+  GAD_ERR_WEIGHTS = -6,     /* consensus weights: negative, non-finite, or summing to zero */
+  GAD_ERR_HIP = -7,         /* a HIP runtime call failed (message in gad_last_error) */
+  GAD_ERR_UNSUPPORTED = -8, /* valid request outside what this build implements */
+  GAD_ERR_STATE = -9        /* backward called on a workspace that holds no matching forward */
+} gad_status;
+
+const char* gad_last_error(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * 1. Augmented-subgraph CSR and normalisation.
+ *
+ * Builds g' = (v + v', e + e') (Algorithm 1, last step; Algorithm 2, Require) as the CSR of A + I,
+ * where A is the adjacency of the induced simple undirected graph on local ++ halo nodes, and the
+ * normalisation of A~ in Eq. 7, read as A~ = D~^-1/2 (A + I) D~^-1/2 with D~ = diag(1 + deg), the
+ * degrees being those inside g'.
+ *
+ *   src, dst      [n_edges_in] int64, global ids of the endpoint pairs.  A pair is kept iff both
+ *                 ends are in local ++ halo and differ; direction and multiplicity are ignored.
+ *                 Pairs with an end outside [0, n_global) are dropped like any pair leaving g'.
+ *   local_ids     [n_local] int64, halo_ids [n_halo] int64: distinct ids in [0, n_global).
+ *   out           host pointer; receives the new graph.  Destroy with gad_graph_destroy.
+ *
+ * Result (bit-exact, deterministic): rowptr int64[n+1], colidx int32[nnz] with strictly ascending
+ * columns per row and exactly one self loop per row; deg int32[n] (self loop not counted);
+ * dinv float32[n] = (1 + deg)^-1/2 evaluated in float64 and rounded once.
+ * Errors: NULL pointers (src/dst may be NULL iff n_edges_in = 0, halo_ids iff n_halo = 0),
+ * n_local + n_halo = 0 or > 2^31 - 2, 2 * n_edges_in + n >= 2^31, ids out of range, duplicate ids.
+ * Synchronises hip_stream (sizes must be read back to allocate the CSR). */
+int gad_build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges_in, int64_t n_global,
+                       const int64_t* local_ids, int64_t n_local, const int64_t* halo_ids, int64_t n_halo,
+                       void* hip_stream, gad_graph** out);
+
+/* Sizes and borrowed device pointers of a graph; any output pointer may be NULL. */
+int gad_graph_info(const gad_graph* g, int64_t* n, int64_t* n_local, int64_t* nnz, const int64_t** rowptr,
+                   const int32_t** colidx, const int32_t** deg, const float** dinv);
+
+int gad_graph_destroy(gad_graph* g);
+
+/* ---------------------------------------------------------------------------------------------
+ * 2./3. Forward and backward propagation (Section 3.3; Algorithm 2, forward and backward steps).
+ *
+ * Model: H_0 = X;  P_l = A~ H_{l-1} W_l (Eq. 7);  H_l = ReLU(P_l) for l < L;  Z = P_L (Eq. 8: no bias,
+ * no activation after the last layer);  y^ = softmax(Z).  Loss (Eq. 9 read as softmax cross-entropy):
+ *   loss = loss_scale * sum_{i : mask_i != 0} ( log sum_c exp Z_ic - Z_{i, labels_i} ).
+ * Backward (Eq. 10 through the softmax):  G_L = loss_scale * mask_i * (y^ - onehot(labels)),
+ *   dW_l = (A~ H_{l-1})^T G_l,   G_{l-1} = (A~ G_l W_l^T) * [P_{l-1} > 0]   (ReLU'(0) = 0).
+ * Per layer the library evaluates A~ (H W) or (A~ H) W, whichever has the narrower sparse product.
+ *
+ *   X          [n x dims[0]] features, leading dimension dims[0]; float32, or bfloat16 for GAD_BF16.
+ *   dims       host, int32[L+1]: F_0 .. F_L (F_L = number of classes); 1 <= L <= 16, 1 <= F <= 4096.
+ *   W          host array of L device pointers; W[l] is float32 [dims[l] x dims[l+1]], ld dims[l+1].
+ *   labels     int32[n] in [0, F_L); mask uint8[n] (NULL = all ones).
+ *   workspace  device, 256-byte aligned, at least gad_gcn_workspace_bytes(); keeps the activations
+ *              between forward and backward.  Its contents are private to the library.
+ *   logits_out float32 [n x F_L] (ld F_L) or NULL;  loss_out device double[1] or NULL.
+ *   dW         host array of L device pointers; dW[l] is float32 [dims[l] x dims[l+1]], overwritten.
+ *   G_out      NULL, or a host array of L device pointers, each NULL or float32 [n x dims[l+1]] (ld dims[l+1])
+ *              that receives the per-node gradient G_{l+1} = dLoss/dP_{l+1} (e.g. as node vectors for
+ *              gad_subgraph_variance).
+ *
+ * gad_gcn_backward must follow a gad_gcn_forward on the same graph, workspace, L, dims and dtype
+ * (else GAD_ERR_STATE); X and W must still hold the values the forward saw.  Rows whose label is
+ * outside [0, F_L) contribute nothing (treated as masked). */
+int gad_gcn_workspace_bytes(const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, size_t* bytes);
+
+int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
+                    const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
+                    void* workspace, size_t workspace_bytes, float* logits_out, double* loss_out,
+                    void* hip_stream);
+
+int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
+                     const float* const* W, void* workspace, size_t workspace_bytes, float* const* dW,
+                     float* const* G_out, void* hip_stream);
+
+/* Copies a saved activation of the last forward on `workspace` into out (float32 [n x dims[layer]], ld
+ * dims[layer]):  layer in [1, L-1] gives H_layer = ReLU(P_layer), layer = L gives the logits Z.
+ * GAD_ERR_STATE if the workspace holds no forward matching (g, L, dims, dtype). */
+int gad_gcn_activation(const gad_graph* g, const void* workspace, size_t workspace_bytes, int L,
+                       const int32_t* dims, gad_dtype dtype, int layer, float* out, void* hip_stream);
+
+/* The normalised sparse product on its own (the A~ H of Eq. 7):  out = A~ T.
+ *   T, out   [n x width] row-major with leading dimensions ldt, ldo (>= width); float32 or bfloat16.
+ * out must not alias T.  Exposed so that the dominant kernel can be tested and timed directly. */
+int gad_spmm(const gad_graph* g, const void* T, int64_t ldt, void* out, int64_t ldo, int32_t width,
+             gad_dtype dtype, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * 4. Variance-based subgraph importance (Section 3.4.1, Eq. 14 and its worked example).
+ *
+ *   zeta = S_pp / (D + beta),  S_pp = sum_{i<j} p_i p_j,  p_i = deg_i / sum_k deg_k (deg without the
+ *   self loop, all unordered pairs: fixed by the worked example),  D = sqrt(2 var),
+ *   var = (1/n) sum_i ||v_i - mean(v)||^2 (squared deviations summed over the F dimensions), i.e. D is
+ *   the root-mean-square Euclidean distance over all node pairs.  sum deg and sum deg^2 are exact
+ *   64-bit integers.  An edgeless subgraph has S_pp = zeta = 0.
+ *
+ *   V            [n x F] node vectors (features, an activation, or per-node gradients), ld = F.
+ *   out3         device double[3]: zeta, S_pp, var.
+ *   per_node_out float32[n] = ||v_i - mean(v)||^2, or NULL.
+ * Errors: beta <= 0 or non-finite, F < 1. */
+int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta,
+                          double* out3, float* per_node_out, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * 5. Weighted global consensus (Section 3.4.2, Eq. 15; Eq. 11 is the case of equal zeta).
+ *
+ *   out[e] = sum_k (zeta_k / sum_j zeta_j) * bufs[k][e],  weights formed in float64.
+ *
+ *   bufs   host array of K device pointers to float32[n_elems];  zeta host double[K];  1 <= K <= 128.
+ *   out    float32[n_elems]; may alias any bufs[k].
+ * Errors: K out of range, any zeta_k negative or non-finite, sum zeta = 0 (GAD_ERR_WEIGHTS). */
+int gad_weighted_consensus(const float* const* bufs, int K, const double* zeta, int64_t n_elems, float* out,
+                           void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GAD_H_ */

@@ -122,8 +122,12 @@ def forward(g: Graph, X, Ws, labels, mask, c=1.0):
     return dict(Z=Z, loss=float(loss), H=H, P=P, AH=AH, yhat=yhat)
 
 
-def backward(g: Graph, Ws, fwd, labels, mask, c=1.0):
-    """dW_l = (A~ H_{l-1})^T G_l ;  G_{l-1} = (A~ G_l W_l^T) * [P_{l-1} > 0]."""
+def backward(g: Graph, Ws, fwd, labels, mask, c=1.0, relu_on=None):
+    """dW_l = (A~ H_{l-1})^T G_l ;  G_{l-1} = (A~ G_l W_l^T) * [P_{l-1} > 0].
+
+    relu_on: optional list of boolean arrays (one per hidden layer) replacing the decisions [P_l > 0].
+    A caller comparing against float32 arithmetic uses it to take the decisions in that precision for
+    the entries whose |P_l| lies below float32 rounding (ReLU'(0) = 0 otherwise)."""
     L = len(Ws)
     n, K = fwd["Z"].shape
     G = fwd["yhat"].copy()
@@ -135,7 +139,8 @@ def backward(g: Graph, Ws, fwd, labels, mask, c=1.0):
         Gs[l] = G
         dW[l] = fwd["AH"][l].T @ G
         if l > 0:
-            G = (spmm(g, G) @ np.asarray(Ws[l], dtype=np.float64).T) * (fwd["P"][l - 1] > 0)
+            on = fwd["P"][l - 1] > 0 if relu_on is None else relu_on[l - 1]
+            G = (spmm(g, G) @ np.asarray(Ws[l], dtype=np.float64).T) * on
     return dW, Gs
 
 

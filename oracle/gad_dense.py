@@ -114,8 +114,11 @@ def forward(At, X, Ws, labels, mask, c=1.0):
     return dict(Z=Z, loss=float(loss), H=H, P=P, yhat=yhat)
 
 
-def backward(At, Ws, fwd, labels, mask, c=1.0):
-    """Chain rule of Eq. 7-10.  Returns (dW list, G list with G[l] = dLoss/dP_{l+1})."""
+def backward(At, Ws, fwd, labels, mask, c=1.0, relu_on=None):
+    """Chain rule of Eq. 7-10.  Returns (dW list, G list with G[l] = dLoss/dP_{l+1}).
+
+    relu_on: optional list of boolean arrays (one per hidden layer) replacing the decisions [P_l > 0];
+    used by callers that must take the decisions with |P_l| below float32 rounding in float32."""
     L = len(Ws)
     n, C = fwd["Z"].shape
     onehot = np.zeros((n, C))
@@ -127,7 +130,8 @@ def backward(At, Ws, fwd, labels, mask, c=1.0):
         Gs[l] = G
         dW[l] = (At @ fwd["H"][l]).T @ G
         if l > 0:
-            G = (At.T @ G @ np.asarray(Ws[l], dtype=np.float64).T) * (fwd["P"][l - 1] > 0)
+            on = fwd["P"][l - 1] > 0 if relu_on is None else relu_on[l - 1]
+            G = (At.T @ G @ np.asarray(Ws[l], dtype=np.float64).T) * on
     return dW, Gs
 
 

@@ -1,0 +1,341 @@
+// C ABI of libgad: argument validation, workspace planning and the order of kernels in the forward and
+// backward passes of the per-processor GCN step (arXiv 2110.02987, Section 3.3, Eq. 7-10; Algorithm 2).
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+
+#include <mutex>
+#include <unordered_map>
+#include <vector>
+
+#include "gad_internal.h"
+
+namespace gad {
+
+static thread_local char g_error[512] = "";
+
+int set_error(int status, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+  return status;
+}
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+inline int64_t pad_ld(int w) { return round_up(w, 16); }
+
+// Where everything lives inside the caller's workspace (offsets in bytes).
+struct Plan {
+  int L = 0;
+  int dims[kMaxLayers + 1];
+  bool agg_first[kMaxLayers];      // layer l computes (A~ H) W  (true)  or  A~ (H W)  (false)
+  size_t agg[kMaxLayers];          // M_l = A~ H_l, kept for dW_l     (agg_first layers)      [n x pad(dims[l])]
+  size_t act[kMaxLayers + 1];      // H_l for 1 <= l < L (post-ReLU), act[L] = Z               [n x pad(dims[l])]
+  size_t g_a = 0, g_b = 0, tmp = 0;  // [n x max_ld] each
+  size_t wt = 0;                   // W^T scratch
+  size_t tn = 0;                   // slab partials of the weight-gradient GEMM
+  size_t sm = 0;                   // softmax block partials (doubles)
+  size_t total = 0;
+  int64_t max_ld = 0;
+};
+
+int make_plan(const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, Plan* p) {
+  if (!g || !dims) return set_error(GAD_ERR_NULL, "graph or dims is NULL");
+  if (L < 1 || L > kMaxLayers) return set_error(GAD_ERR_SHAPE, "L = %d outside [1, %d]", L, kMaxLayers);
+  for (int l = 0; l <= L; ++l)
+    if (dims[l] < 1 || dims[l] > kMaxWidth)
+      return set_error(GAD_ERR_SHAPE, "dims[%d] = %d outside [1, %d]", l, dims[l], kMaxWidth);
+  if (dtype != GAD_F32) return set_error(GAD_ERR_UNSUPPORTED, "only GAD_F32 is implemented for the GCN step");
+  p->L = L;
+  const size_t n = (size_t)g->n;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += (bytes + kAlign - 1) / kAlign * kAlign;
+    return o;
+  };
+  p->max_ld = 0;
+  size_t max_w = 0, max_tn = 0;
+  for (int l = 0; l <= L; ++l) p->dims[l] = dims[l];
+  for (int l = 1; l <= L; ++l)
+    if (pad_ld(dims[l]) > p->max_ld) p->max_ld = pad_ld(dims[l]);
+  for (int l = 0; l < L; ++l) {
+    p->agg_first[l] = dims[l] <= dims[l + 1];
+    p->agg[l] = p->agg_first[l] ? take(n * pad_ld(dims[l]) * sizeof(float)) : 0;
+    p->act[l + 1] = take(n * pad_ld(dims[l + 1]) * sizeof(float));
+    if (p->agg_first[l] && pad_ld(dims[l]) > p->max_ld) p->max_ld = pad_ld(dims[l]);
+    const size_t w = (size_t)dims[l] * dims[l + 1];
+    if (w > max_w) max_w = w;
+    const size_t t = gemm_tn_partial_floats(g->n, dims[l], dims[l + 1]);
+    if (t > max_tn) max_tn = t;
+  }
+  p->act[0] = 0;
+  p->g_a = take(n * p->max_ld * sizeof(float));
+  p->g_b = take(n * p->max_ld * sizeof(float));
+  p->tmp = take(n * p->max_ld * sizeof(float));
+  p->wt = take(max_w * sizeof(float));
+  p->tn = take(max_tn * sizeof(float));
+  p->sm = take(softmax_partial_doubles(g->n) * sizeof(double));
+  p->total = off;
+  return GAD_OK;
+}
+
+// Which forward a workspace currently holds (host-side bookkeeping; the workspace itself is device memory).
+struct Saved {
+  const gad_graph* g;
+  int L;
+  std::vector<int32_t> dims;
+  gad_dtype dtype;
+  const void* X;
+};
+std::mutex g_saved_mu;
+std::unordered_map<const void*, Saved> g_saved;
+
+int check_common(const gad_graph* g, const void* X, int L, const int32_t* dims, const float* const* W, void* ws,
+                 size_t ws_bytes, const Plan& p) {
+  if (!X || !W || !ws) return set_error(GAD_ERR_NULL, "X, W or workspace is NULL");
+  for (int l = 0; l < L; ++l)
+    if (!W[l]) return set_error(GAD_ERR_NULL, "W[%d] is NULL", l);
+  if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0)
+    return set_error(GAD_ERR_WORKSPACE, "workspace is not %zu-byte aligned", kAlign);
+  if (ws_bytes < p.total)
+    return set_error(GAD_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, p.total);
+  (void)g;
+  (void)dims;
+  return GAD_OK;
+}
+
+// True iff `ws` holds a forward of exactly this problem (X = nullptr: any features).
+bool forward_saved(const gad_graph* g, const void* ws, int L, const int32_t* dims, gad_dtype dtype, const void* X) {
+  std::lock_guard<std::mutex> lk(g_saved_mu);
+  auto it = g_saved.find(ws);
+  bool ok = it != g_saved.end() && it->second.g == g && it->second.L == L && it->second.dtype == dtype &&
+            (X == nullptr || it->second.X == X);
+  if (ok)
+    for (int l = 0; l <= L; ++l) ok = ok && it->second.dims[l] == dims[l];
+  return ok;
+}
+
+inline float* at(void* ws, size_t off) { return reinterpret_cast<float*>(static_cast<char*>(ws) + off); }
+
+}  // namespace
+}  // namespace gad
+
+using namespace gad;
+
+extern "C" {
+
+const char* gad_last_error(void) { return g_error; }
+
+int gad_build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges_in, int64_t n_global,
+                       const int64_t* local_ids, int64_t n_local, const int64_t* halo_ids, int64_t n_halo,
+                       void* hip_stream, gad_graph** out) {
+  if (!out) return set_error(GAD_ERR_NULL, "out is NULL");
+  *out = nullptr;
+  if (n_edges_in < 0 || n_local < 0 || n_halo < 0 || n_global < 1)
+    return set_error(GAD_ERR_SHAPE, "negative size or n_global < 1");
+  const int64_t n = n_local + n_halo;
+  if (n < 1) return set_error(GAD_ERR_SHAPE, "the subgraph has no nodes");
+  if (n > 2147483646ll) return set_error(GAD_ERR_SHAPE, "n = %lld exceeds 2^31 - 2", (long long)n);
+  if (2 * n_edges_in + n >= 2147483648ll)
+    return set_error(GAD_ERR_SHAPE, "2 * n_edges_in + n = %lld does not fit 31 bits", (long long)(2 * n_edges_in + n));
+  if (n_global >= 2147483648ll) return set_error(GAD_ERR_SHAPE, "n_global does not fit 31 bits");
+  if ((n_edges_in > 0 && (!src || !dst)) || (n_local > 0 && !local_ids) || (n_halo > 0 && !halo_ids))
+    return set_error(GAD_ERR_NULL, "a required array is NULL");
+  return build_subgraph(src, dst, n_edges_in, n_global, local_ids, n_local, halo_ids, n_halo,
+                        static_cast<hipStream_t>(hip_stream), out);
+}
+
+int gad_graph_info(const gad_graph* g, int64_t* n, int64_t* n_local, int64_t* nnz, const int64_t** rowptr,
+                   const int32_t** colidx, const int32_t** deg, const float** dinv) {
+  if (!g) return set_error(GAD_ERR_NULL, "graph is NULL");
+  if (n) *n = g->n;
+  if (n_local) *n_local = g->n_local;
+  if (nnz) *nnz = g->nnz;
+  if (rowptr) *rowptr = g->rowptr;
+  if (colidx) *colidx = g->colidx;
+  if (deg) *deg = g->deg;
+  if (dinv) *dinv = g->dinv;
+  return GAD_OK;
+}
+
+int gad_graph_destroy(gad_graph* g) {
+  if (!g) return GAD_OK;
+  void* ptrs[] = {g->rowptr,    g->colidx,      g->deg,     g->dinv,       g->long_row, g->long_first,
+                  g->chunk_row, g->chunk_begin, g->partial, g->red_scratch};
+  int st = GAD_OK;
+  for (void* p : ptrs)
+    if (p && hipFree(p) != hipSuccess) st = set_error(GAD_ERR_HIP, "hipFree failed in gad_graph_destroy");
+  {
+    std::lock_guard<std::mutex> lk(g_saved_mu);
+    for (auto it = g_saved.begin(); it != g_saved.end();)
+      it = it->second.g == g ? g_saved.erase(it) : ++it;
+  }
+  delete g;
+  return st;
+}
+
+int gad_gcn_workspace_bytes(const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, size_t* bytes) {
+  if (!bytes) return set_error(GAD_ERR_NULL, "bytes is NULL");
+  Plan p;
+  int st = make_plan(g, L, dims, dtype, &p);
+  if (st != GAD_OK) return st;
+  *bytes = p.total;
+  return GAD_OK;
+}
+
+int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
+                    const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
+                    void* workspace, size_t workspace_bytes, float* logits_out, double* loss_out, void* hip_stream) {
+  Plan p;
+  int st = make_plan(g, L, dims, dtype, &p);
+  if (st != GAD_OK) return st;
+  st = check_common(g, X, L, dims, W, workspace, workspace_bytes, p);
+  if (st != GAD_OK) return st;
+  if (!labels) return set_error(GAD_ERR_NULL, "labels is NULL");
+  if (!isfinite(loss_scale)) return set_error(GAD_ERR_SHAPE, "loss_scale is not finite");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int64_t n = g->n;
+
+  const float* h = static_cast<const float*>(X);
+  int64_t ldh = dims[0];
+  for (int l = 0; l < L; ++l) {
+    const bool last = l == L - 1;
+    const int epi = last ? EPI_NONE : EPI_RELU;
+    float* dst = at(workspace, p.act[l + 1]);
+    const int64_t ldd = pad_ld(dims[l + 1]);
+    if (p.agg_first[l]) {
+      float* m = at(workspace, p.agg[l]);
+      const int64_t ldm = pad_ld(dims[l]);
+      if ((st = spmm_f32(g, h, ldh, m, ldm, dims[l], EPI_NONE, nullptr, 0, s)) != GAD_OK) return st;
+      if ((st = gemm_nn_f32(m, ldm, W[l], dims[l + 1], dst, ldd, n, dims[l + 1], dims[l], epi, nullptr, 0, s)) != GAD_OK)
+        return st;
+    } else {
+      float* t = at(workspace, p.tmp);
+      if ((st = gemm_nn_f32(h, ldh, W[l], dims[l + 1], t, ldd, n, dims[l + 1], dims[l], EPI_NONE, nullptr, 0, s)) !=
+          GAD_OK)
+        return st;
+      if ((st = spmm_f32(g, t, ldd, dst, ldd, dims[l + 1], epi, nullptr, 0, s)) != GAD_OK) return st;
+    }
+    h = dst;
+    ldh = ldd;
+  }
+  const int C = dims[L];
+  const int64_t ldz = pad_ld(C);
+  st = softmax_xent_f32(h, ldz, labels, mask, loss_scale, n, C, at(workspace, p.g_a), ldz,
+                        reinterpret_cast<double*>(at(workspace, p.sm)), loss_out, s);
+  if (st != GAD_OK) return st;
+  if (logits_out && (st = copy_rows_f32(h, ldz, logits_out, C, n, C, s)) != GAD_OK) return st;
+  {
+    std::lock_guard<std::mutex> lk(g_saved_mu);
+    g_saved[workspace] = Saved{g, L, std::vector<int32_t>(dims, dims + L + 1), dtype, X};
+  }
+  return GAD_OK;
+}
+
+int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
+                     const float* const* W, void* workspace, size_t workspace_bytes, float* const* dW,
+                     float* const* G_out, void* hip_stream) {
+  Plan p;
+  int st = make_plan(g, L, dims, dtype, &p);
+  if (st != GAD_OK) return st;
+  st = check_common(g, X, L, dims, W, workspace, workspace_bytes, p);
+  if (st != GAD_OK) return st;
+  if (!dW) return set_error(GAD_ERR_NULL, "dW is NULL");
+  for (int l = 0; l < L; ++l)
+    if (!dW[l]) return set_error(GAD_ERR_NULL, "dW[%d] is NULL", l);
+  if (!forward_saved(g, workspace, L, dims, dtype, X))
+    return set_error(GAD_ERR_STATE, "workspace holds no forward pass matching this graph / model / X");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int64_t n = g->n;
+  float* gcur = at(workspace, p.g_a);
+  float* gnext = at(workspace, p.g_b);
+  float* tmp = at(workspace, p.tmp);
+  float* wt = at(workspace, p.wt);
+  float* tn = at(workspace, p.tn);
+  for (int l = L - 1; l >= 0; --l) {
+    const int fin = dims[l], fout = dims[l + 1];
+    const int64_t ldg = pad_ld(fout);        // G_l, S_l
+    const int64_t ldi = pad_ld(fin);         // dM, G_{l-1}, H_l
+    const float* hin = l == 0 ? static_cast<const float*>(X) : at(workspace, p.act[l]);
+    const int64_t ldhin = l == 0 ? dims[0] : ldi;
+    if (G_out && G_out[l] && (st = copy_rows_f32(gcur, ldg, G_out[l], fout, n, fout, s)) != GAD_OK) return st;
+    if (p.agg_first[l]) {
+      if ((st = gemm_tn_f32(at(workspace, p.agg[l]), ldi, gcur, ldg, dW[l], fout, n, fin, fout, tn, s)) != GAD_OK)
+        return st;
+      if (l > 0) {
+        if ((st = transpose_f32(W[l], fin, fout, wt, s)) != GAD_OK) return st;
+        if ((st = gemm_nn_f32(gcur, ldg, wt, fin, tmp, ldi, n, fin, fout, EPI_NONE, nullptr, 0, s)) != GAD_OK) return st;
+        if ((st = spmm_f32(g, tmp, ldi, gnext, ldi, fin, EPI_MASK, hin, ldhin, s)) != GAD_OK) return st;
+      }
+    } else {
+      if ((st = spmm_f32(g, gcur, ldg, tmp, ldg, fout, EPI_NONE, nullptr, 0, s)) != GAD_OK) return st;
+      if ((st = gemm_tn_f32(hin, ldhin, tmp, ldg, dW[l], fout, n, fin, fout, tn, s)) != GAD_OK) return st;
+      if (l > 0) {
+        if ((st = transpose_f32(W[l], fin, fout, wt, s)) != GAD_OK) return st;
+        if ((st = gemm_nn_f32(tmp, ldg, wt, fin, gnext, ldi, n, fin, fout, EPI_MASK, hin, ldhin, s)) != GAD_OK)
+          return st;
+      }
+    }
+    float* t = gcur;
+    gcur = gnext;
+    gnext = t;
+  }
+  return GAD_OK;
+}
+
+int gad_gcn_activation(const gad_graph* g, const void* workspace, size_t workspace_bytes, int L,
+                       const int32_t* dims, gad_dtype dtype, int layer, float* out, void* hip_stream) {
+  Plan p;
+  int st = make_plan(g, L, dims, dtype, &p);
+  if (st != GAD_OK) return st;
+  if (!workspace || !out) return set_error(GAD_ERR_NULL, "workspace or out is NULL");
+  if (workspace_bytes < p.total) return set_error(GAD_ERR_WORKSPACE, "workspace smaller than the plan");
+  if (layer < 1 || layer > L) return set_error(GAD_ERR_SHAPE, "layer = %d outside [1, %d]", layer, L);
+  if (!forward_saved(g, workspace, L, dims, dtype, nullptr))
+    return set_error(GAD_ERR_STATE, "workspace holds no forward pass matching this graph / model");
+  return copy_rows_f32(at(const_cast<void*>(workspace), p.act[layer]), pad_ld(dims[layer]), out, dims[layer], g->n,
+                       dims[layer], static_cast<hipStream_t>(hip_stream));
+}
+
+int gad_spmm(const gad_graph* g, const void* T, int64_t ldt, void* out, int64_t ldo, int32_t width, gad_dtype dtype,
+             void* hip_stream) {
+  if (!g || !T || !out) return set_error(GAD_ERR_NULL, "graph, T or out is NULL");
+  if (width < 1 || ldt < width || ldo < width) return set_error(GAD_ERR_SHAPE, "width < 1 or a leading dimension < width");
+  if (T == out) return set_error(GAD_ERR_SHAPE, "out must not alias T");
+  if (dtype != GAD_F32) return set_error(GAD_ERR_UNSUPPORTED, "only GAD_F32 is implemented for gad_spmm");
+  return spmm_f32(g, static_cast<const float*>(T), ldt, static_cast<float*>(out), ldo, width, EPI_NONE, nullptr, 0,
+                  static_cast<hipStream_t>(hip_stream));
+}
+
+int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta, double* out3,
+                          float* per_node_out, void* hip_stream) {
+  if (!g || !V || !out3) return set_error(GAD_ERR_NULL, "graph, V or out3 is NULL");
+  if (F < 1 || F > kMaxWidth) return set_error(GAD_ERR_SHAPE, "F = %d outside [1, %d]", F, kMaxWidth);
+  if (!(beta > 0.0) || !isfinite(beta)) return set_error(GAD_ERR_SHAPE, "beta must be positive and finite");
+  if (dtype != GAD_F32 && dtype != GAD_BF16) return set_error(GAD_ERR_UNSUPPORTED, "unknown dtype");
+  return subgraph_variance(g, V, F, dtype, beta, out3, per_node_out, static_cast<hipStream_t>(hip_stream));
+}
+
+int gad_weighted_consensus(const float* const* bufs, int K, const double* zeta, int64_t n_elems, float* out,
+                           void* hip_stream) {
+  if (!bufs || !zeta || !out) return set_error(GAD_ERR_NULL, "bufs, zeta or out is NULL");
+  if (K < 1 || K > kMaxConsensus) return set_error(GAD_ERR_SHAPE, "K = %d outside [1, %d]", K, kMaxConsensus);
+  if (n_elems < 0) return set_error(GAD_ERR_SHAPE, "n_elems is negative");
+  double sum = 0.0;
+  for (int k = 0; k < K; ++k) {
+    if (!bufs[k]) return set_error(GAD_ERR_NULL, "bufs[%d] is NULL", k);
+    if (!isfinite(zeta[k]) || zeta[k] < 0.0) return set_error(GAD_ERR_WEIGHTS, "zeta[%d] is negative or not finite", k);
+    sum += zeta[k];
+  }
+  if (!(sum > 0.0) || !isfinite(sum)) return set_error(GAD_ERR_WEIGHTS, "the weights sum to zero (or overflow)");
+  double w[kMaxConsensus];
+  for (int k = 0; k < K; ++k) w[k] = zeta[k] / sum;
+  return weighted_consensus(bufs, K, w, n_elems, out, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

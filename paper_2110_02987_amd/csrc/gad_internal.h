@@ -1,0 +1,94 @@
+// Internal declarations shared by the HIP translation units of libgad (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "gad.h"
+
+namespace gad {
+
+constexpr int kWave = 64;
+
+// ---- error plumbing -----------------------------------------------------------------------
+int set_error(int status, const char* fmt, ...);   // formats into the thread-local message, returns status
+
+#define GAD_HIP(expr)                                                                        \
+  do {                                                                                       \
+    hipError_t _e = (expr);                                                                  \
+    if (_e != hipSuccess)                                                                    \
+      return gad::set_error(GAD_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e), __FILE__, __LINE__); \
+  } while (0)
+
+#define GAD_LAUNCH_CHECK() GAD_HIP(hipGetLastError())
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+// ---- SpMM epilogues -----------------------------------------------------------------------
+enum Epilogue : int {
+  EPI_NONE = 0,
+  EPI_RELU = 1,   // out = max(out, 0)
+  EPI_MASK = 2,   // out = aux > 0 ? out : 0   (aux has the layout of out)
+};
+
+// Rows longer than this many non-zeros are split into chunks of this size; each chunk is summed by
+// one wave into a partial row and the partials of a row are added in chunk order.
+constexpr int kLongRow = 1024;
+// Widest slab of columns one SpMM launch handles for long rows (floats per partial row).
+constexpr int kPartialWidth = 512;
+constexpr int kMaxWidth = 4096;      // widest feature / hidden dimension accepted
+constexpr int kMaxLayers = 16;
+constexpr int kMaxConsensus = 128;   // most buffers one consensus call averages
+constexpr int kVarBlocks = 512;      // row slabs of the column-sum pass of the variance reduction
+
+}  // namespace gad
+
+struct gad_graph {
+  int64_t n = 0, n_local = 0, nnz = 0;
+  int64_t* rowptr = nullptr;   // [n+1]
+  int32_t* colidx = nullptr;   // [nnz]
+  int32_t* deg = nullptr;      // [n]
+  float* dinv = nullptr;       // [n]
+  // long-row schedule (rows with more than kLongRow non-zeros)
+  int32_t n_long = 0;          // number of long rows
+  int32_t n_chunks = 0;        // total number of chunks over all long rows
+  int32_t* long_row = nullptr;       // [n_long] row id
+  int32_t* long_first = nullptr;     // [n_long] first chunk slot of the row
+  int32_t* chunk_row = nullptr;      // [n_chunks] row id of the chunk
+  int32_t* chunk_begin = nullptr;    // [n_chunks] offset of the chunk inside its row
+  float* partial = nullptr;          // [n_chunks x kPartialWidth] scratch for chunk sums; shared by all calls on this graph
+  int64_t partial_elems = 0;
+  double* red_scratch = nullptr;     // variance_scratch_doubles(n) doubles; shared by all calls on this graph
+  int device = 0;
+};
+
+namespace gad {
+
+// ---- kernels' host entry points (each enqueues on `s` and returns a gad_status) -------------
+int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int64_t n_global, const int64_t* local_ids,
+                   int64_t n_local, const int64_t* halo_ids, int64_t n_halo, hipStream_t s, gad_graph** out);
+int spmm_f32(const gad_graph* g, const float* T, int64_t ldt, float* out, int64_t ldo, int width, int epilogue,
+             const float* aux, int64_t ldaux, hipStream_t s);
+
+// C[M x N] (ldc) = A[M x K] (lda) * B[K x N] (ldb), with the SpMM epilogues applied to C.
+int gemm_nn_f32(const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t M, int N,
+                int K, int epilogue, const float* aux, int64_t ldaux, hipStream_t s);
+// C[K x N] (ldc) = A[M x K]^T * G[M x N]; `partials` must hold gemm_tn_partial_floats(M, K, N) floats.
+size_t gemm_tn_partial_floats(int64_t M, int K, int N);
+int gemm_tn_f32(const float* A, int64_t lda, const float* G, int64_t ldg, float* C, int64_t ldc, int64_t M, int K,
+                int N, float* partials, hipStream_t s);
+int transpose_f32(const float* in, int rows, int cols, float* out, hipStream_t s);   // out[cols x rows]
+
+// Z [n x C] (ldz) -> G [n x C] (ldg), loss (double, device).  block_partials: ceil(n/64) doubles.
+size_t softmax_partial_doubles(int64_t n);
+int softmax_xent_f32(const float* Z, int64_t ldz, const int32_t* labels, const uint8_t* mask, float scale, int64_t n,
+                     int C, float* G, int64_t ldg, double* block_partials, double* loss_out, hipStream_t s);
+size_t variance_scratch_doubles(int64_t n);
+int subgraph_variance(const gad_graph* g, const void* V, int F, gad_dtype dtype, double beta, double* out3,
+                      float* per_node, hipStream_t s);
+int weighted_consensus(const float* const* bufs, int K, const double* w, int64_t n, float* out, hipStream_t s);
+int copy_rows_f32(const float* in, int64_t ldi, float* out, int64_t ldo, int64_t n, int width, hipStream_t s);
+
+}  // namespace gad

@@ -1,0 +1,278 @@
+// Dense contractions of the GCN step on the gfx950 matrix cores (float32 MFMA 32x32x2):
+//   NN:  C[M x N] = A[M x K] B[K x N]          -- the feature transform H W of Eq. 7 and the
+//                                                  input-gradient product S W^T (B = W^T)
+//   TN:  C[K x N] = A[M x K]^T G[M x N]        -- the weight gradient dW = (A~ H)^T G, a reduction
+//                                                  over the M = n nodes, split over M in slabs whose
+//                                                  partial products are added in slab order.
+// (arXiv 2110.02987, Section 3.3: Eq. 7 forward; backward step of Algorithm 2.)
+//
+// Block tile 128 x 128, four wave64s in a 2 x 2 arrangement, each wave a 64 x 64 sub-tile made of
+// 2 x 2 MFMA 32x32 accumulators.  Both operands are staged through LDS with the reduction index
+// leading (As[kk][i], Bs[kk][j]) so that a fragment read is 64 consecutive floats; the next tile is
+// fetched from global memory into registers while the current one is multiplied (double-buffered LDS).
+#include "gad_internal.h"
+
+namespace gad {
+namespace {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int LDS_LD = BM + 4;   // row stride of As / Bs in floats (16-byte aligned rows)
+
+struct Tile {
+  float a[BK][LDS_LD];
+  float b[BK][LDS_LD];
+};
+
+// acc[tm][tn] += As[:, 64*wm + 32*tm .. ]^T Bs[:, 64*wn + 32*tn ..]
+__device__ __forceinline__ void mma_tile(const Tile& t, int wm, int wn, v16f (&acc)[2][2]) {
+  const int lane = threadIdx.x & 63;
+  const int i = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int k0 = 0; k0 < BK; k0 += 2) {
+    float a[2], b[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      a[q] = t.a[k0 + half][wm * 64 + q * 32 + i];
+      b[q] = t.b[k0 + half][wn * 64 + q * 32 + i];
+    }
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < 2; ++tn)
+        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+  }
+}
+
+// Element (row, col) of accumulator register r of a 32x32 MFMA result held by `lane`.
+__device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
+// ---- loaders: 8 consecutive floats per thread, zero-filled outside the matrix -----------------
+// "row-major, reduction index contiguous" (A of NN): thread -> (row = t/2, k-segment = (t%2)*8)
+__device__ __forceinline__ void load8(const float* __restrict__ base, int64_t ld, int64_t row, int64_t n_rows, int col,
+                                      int n_cols, bool vec_ok, float (&r)[8]) {
+  if (row < n_rows && vec_ok && col + 8 <= n_cols) {
+    const float4* p = reinterpret_cast<const float4*>(base + row * ld + col);
+    const float4 x = p[0], y = p[1];
+    r[0] = x.x; r[1] = x.y; r[2] = x.z; r[3] = x.w;
+    r[4] = y.x; r[5] = y.y; r[6] = y.z; r[7] = y.w;
+  } else {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) r[q] = (row < n_rows && col + q < n_cols) ? base[row * ld + col + q] : 0.f;
+  }
+}
+
+__device__ __forceinline__ void store_direct(float (*dst)[LDS_LD], int kk, int seg, const float (&r)[8]) {
+  *reinterpret_cast<float4*>(&dst[kk][seg]) = make_float4(r[0], r[1], r[2], r[3]);
+  *reinterpret_cast<float4*>(&dst[kk][seg + 4]) = make_float4(r[4], r[5], r[6], r[7]);
+}
+
+__device__ __forceinline__ void store_transposed(float (*dst)[LDS_LD], int i, int kseg, const float (&r)[8]) {
+#pragma unroll
+  for (int q = 0; q < 8; ++q) dst[kseg + q][i] = r[q];
+}
+
+template <int EPI>
+__device__ __forceinline__ void store_acc(const v16f (&acc)[2][2], float* __restrict__ C, int64_t ldc, int64_t row0,
+                                          int col0, int64_t M, int N, int wm, int wn, const float* __restrict__ aux,
+                                          int64_t ldaux) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn) {
+      const int col = col0 + wn * 64 + tn * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t row = row0 + wm * 64 + tm * 32 + acc_row(r, lane);
+        if (row < M && col < N) {
+          float v = acc[tm][tn][r];
+          if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
+          if (EPI == EPI_MASK) v = aux[row * ldaux + col] > 0.f ? v : 0.f;
+          C[row * ldc + col] = v;
+        }
+      }
+    }
+}
+
+// ---- NN ----------------------------------------------------------------------------------------
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ A, int64_t lda,
+                                                      const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
+                                                      int64_t ldc, int64_t M, int N, int K, bool a_vec, bool b_vec,
+                                                      const float* __restrict__ aux, int64_t ldaux) {
+  __shared__ Tile tiles[2];
+  const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
+  const int64_t row0 = (int64_t)blockIdx.x * BM;
+  const int col0 = blockIdx.y * BN;
+  // A: thread -> row t/2, k segment (t%2)*8;  B: thread -> k row t/16, column segment (t%16)*8
+  const int a_i = t >> 1, a_k = (t & 1) * 8;
+  const int b_k = t >> 4, b_j = (t & 15) * 8;
+  v16f acc[2][2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
+
+  float ra[8], rb[8];
+  load8(A, lda, row0 + a_i, M, a_k, K, a_vec, ra);
+  load8(B, ldb, b_k, K, col0 + b_j, N, b_vec, rb);
+  store_transposed(tiles[0].a, a_i, a_k, ra);
+  store_direct(tiles[0].b, b_k, b_j, rb);
+  __syncthreads();
+  const int n_kt = (K + BK - 1) / BK;
+  for (int kt = 0; kt < n_kt; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < n_kt) {
+      const int k1 = (kt + 1) * BK;
+      load8(A, lda, row0 + a_i, M, k1 + a_k, K, a_vec, ra);
+      load8(B, ldb, k1 + b_k, K, col0 + b_j, N, b_vec, rb);
+    }
+    mma_tile(tiles[cur], wm, wn, acc);
+    if (kt + 1 < n_kt) {
+      store_transposed(tiles[cur ^ 1].a, a_i, a_k, ra);
+      store_direct(tiles[cur ^ 1].b, b_k, b_j, rb);
+    }
+    __syncthreads();
+  }
+  store_acc<EPI>(acc, C, ldc, row0, col0, M, N, wm, wn, aux, ldaux);
+}
+
+// ---- TN ----------------------------------------------------------------------------------------
+// grid: x = output tile (tiles_k * tiles_n), y = slab of M.  Writes P[slab][K x N] (ld N).
+__global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ A, int64_t lda,
+                                                      const float* __restrict__ G, int64_t ldg, float* __restrict__ P,
+                                                      int64_t M, int K, int N, int64_t slab_rows, int tiles_n,
+                                                      bool a_vec, bool g_vec) {
+  __shared__ Tile tiles[2];
+  const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
+  const int k0 = (blockIdx.x / tiles_n) * BM;   // output row block (columns of A)
+  const int n0 = (blockIdx.x % tiles_n) * BN;   // output column block (columns of G)
+  const int64_t m_begin = (int64_t)blockIdx.y * slab_rows;
+  const int64_t m_end = m_begin + slab_rows < M ? m_begin + slab_rows : M;
+  const int l_m = t >> 4, l_c = (t & 15) * 8;   // thread -> reduction row t/16, column segment (t%16)*8
+  v16f acc[2][2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
+
+  float ra[8], rb[8];
+  load8(A, lda, m_begin + l_m, m_end, k0 + l_c, K, a_vec, ra);
+  load8(G, ldg, m_begin + l_m, m_end, n0 + l_c, N, g_vec, rb);
+  store_direct(tiles[0].a, l_m, l_c, ra);
+  store_direct(tiles[0].b, l_m, l_c, rb);
+  __syncthreads();
+  const int64_t n_mt = (m_end - m_begin + BK - 1) / BK;
+  for (int64_t mt = 0; mt < n_mt; ++mt) {
+    const int cur = (int)(mt & 1);
+    if (mt + 1 < n_mt) {
+      const int64_t m1 = m_begin + (mt + 1) * BK + l_m;
+      load8(A, lda, m1, m_end, k0 + l_c, K, a_vec, ra);
+      load8(G, ldg, m1, m_end, n0 + l_c, N, g_vec, rb);
+    }
+    mma_tile(tiles[cur], wm, wn, acc);
+    if (mt + 1 < n_mt) {
+      store_direct(tiles[cur ^ 1].a, l_m, l_c, ra);
+      store_direct(tiles[cur ^ 1].b, l_m, l_c, rb);
+    }
+    __syncthreads();
+  }
+  float* Pslab = P + (int64_t)blockIdx.y * K * N;
+  store_acc<EPI_NONE>(acc, Pslab, N, k0, n0, K, N, wm, wn, nullptr, 0);
+}
+
+__global__ void reduce_slabs(const float* __restrict__ P, int n_slabs, int64_t elems, int N, float* __restrict__ C,
+                             int64_t ldc) {
+  const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (e >= elems) return;
+  double s = 0.0;
+  for (int q = 0; q < n_slabs; ++q) s += (double)P[(int64_t)q * elems + e];
+  C[(e / N) * ldc + (e % N)] = (float)s;
+}
+
+__global__ void transpose_kernel(const float* __restrict__ in, int rows, int cols, float* __restrict__ out) {
+  __shared__ float tile[32][33];
+  const int x = blockIdx.x * 32 + threadIdx.x, y0 = blockIdx.y * 32;
+  for (int dy = threadIdx.y; dy < 32; dy += blockDim.y)
+    if (x < cols && y0 + dy < rows) tile[dy][threadIdx.x] = in[(int64_t)(y0 + dy) * cols + x];
+  __syncthreads();
+  const int ox = blockIdx.y * 32 + threadIdx.x, oy0 = blockIdx.x * 32;
+  for (int dy = threadIdx.y; dy < 32; dy += blockDim.y)
+    if (ox < rows && oy0 + dy < cols) out[(int64_t)(oy0 + dy) * rows + ox] = tile[threadIdx.x][dy];
+}
+
+bool vec_ok(const float* p, int64_t ld) { return (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(p) & 15u) == 0); }
+
+void tn_split(int64_t M, int K, int N, int* n_slabs, int64_t* slab_rows) {
+  const int64_t tiles = ceil_div(K, BM) * ceil_div(N, BN);
+  int64_t want = ceil_div(2048, tiles);               // ~8 blocks per CU over the whole grid
+  const int64_t max_slabs = ceil_div(M, 512);         // at least 512 reduction rows per slab
+  if (want > max_slabs) want = max_slabs;
+  if (want < 1) want = 1;
+  *slab_rows = round_up(ceil_div(M, want), BK);
+  *n_slabs = (int)ceil_div(M, *slab_rows);
+}
+
+}  // namespace
+
+int gemm_nn_f32(const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t M, int N,
+                int K, int epi, const float* aux, int64_t ldaux, hipStream_t s) {
+  if (M == 0 || N == 0) return GAD_OK;
+  const dim3 grid((unsigned)ceil_div(M, BM), (unsigned)ceil_div(N, BN));
+  const bool av = vec_ok(A, lda), bv = vec_ok(B, ldb);
+  switch (epi) {
+    case EPI_NONE:
+      gemm_nn_kernel<EPI_NONE><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, aux, ldaux);
+      break;
+    case EPI_RELU:
+      gemm_nn_kernel<EPI_RELU><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, aux, ldaux);
+      break;
+    case EPI_MASK:
+      gemm_nn_kernel<EPI_MASK><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, aux, ldaux);
+      break;
+    default:
+      return set_error(GAD_ERR_UNSUPPORTED, "unknown epilogue %d", epi);
+  }
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
+}
+
+size_t gemm_tn_partial_floats(int64_t M, int K, int N) {
+  int n_slabs;
+  int64_t slab_rows;
+  tn_split(M, K, N, &n_slabs, &slab_rows);
+  return (size_t)n_slabs * (size_t)K * (size_t)N;
+}
+
+int gemm_tn_f32(const float* A, int64_t lda, const float* G, int64_t ldg, float* C, int64_t ldc, int64_t M, int K,
+                int N, float* partials, hipStream_t s) {
+  if (K == 0 || N == 0) return GAD_OK;
+  int n_slabs;
+  int64_t slab_rows;
+  tn_split(M, K, N, &n_slabs, &slab_rows);
+  const int tiles_n = (int)ceil_div(N, BN);
+  const dim3 grid((unsigned)(ceil_div(K, BM) * tiles_n), (unsigned)n_slabs);
+  gemm_tn_kernel<<<grid, 256, 0, s>>>(A, lda, G, ldg, partials, M, K, N, slab_rows, tiles_n, vec_ok(A, lda),
+                                      vec_ok(G, ldg));
+  GAD_LAUNCH_CHECK();
+  const int64_t elems = (int64_t)K * N;
+  reduce_slabs<<<(unsigned)ceil_div(elems, 256), 256, 0, s>>>(partials, n_slabs, elems, N, C, ldc);
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
+}
+
+int transpose_f32(const float* in, int rows, int cols, float* out, hipStream_t s) {
+  if (rows == 0 || cols == 0) return GAD_OK;
+  transpose_kernel<<<dim3((unsigned)ceil_div(cols, 32), (unsigned)ceil_div(rows, 32)), dim3(32, 8), 0, s>>>(in, rows,
+                                                                                                            cols, out);
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
+}
+
+}  // namespace gad

@@ -1,0 +1,210 @@
+// GAD-Optimizer reductions (arXiv 2110.02987, Section 3.4):
+//   * variance-based subgraph importance zeta(g'), Eq. 14 and its worked example:
+//       zeta = S_pp / (D + beta),  S_pp = sum_{i<j} p_i p_j = (S1^2 - S2) / (2 S1^2) with
+//       S1 = sum deg, S2 = sum deg^2 (exact 64-bit integers),  D = sqrt(2 var),
+//       var = (1/n) sum_i ||v_i - mean(v)||^2;
+//   * weighted global consensus, Eq. 15 (Eq. 11 when all zeta are equal):
+//       out = sum_k (zeta_k / sum_j zeta_j) B_k.
+// All floating-point reductions are float64 and ordered (per thread, per block, then over blocks), so
+// results are reproducible from run to run; the integer sums use 64-bit atomics, which are exact.
+#include <math.h>
+
+#include "gad_internal.h"
+
+namespace gad {
+namespace {
+
+template <typename T>
+__device__ __forceinline__ float to_float(T v);
+template <>
+__device__ __forceinline__ float to_float<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ float to_float<uint16_t>(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }  // bfloat16
+
+// Column sums of V[rows x F] over this block's slab of rows -> part[block][F].
+// Thread t owns column (t % CW) of row lane (t / CW); CW columns are covered per sweep.
+template <typename T, int CW>
+__global__ __launch_bounds__(256) void column_sums(const T* __restrict__ V, int64_t n, int F, int64_t slab,
+                                                   double* __restrict__ part) {
+  constexpr int RL = 256 / CW;
+  __shared__ double sm[256];
+  const int cl = threadIdx.x % CW, rl = threadIdx.x / CW;
+  const int64_t r0 = (int64_t)blockIdx.x * slab;
+  const int64_t r1 = r0 + slab < n ? r0 + slab : n;
+  for (int c0 = 0; c0 < F; c0 += CW) {
+    const int c = c0 + cl;
+    double s = 0.0;
+    if (c < F)
+      for (int64_t r = r0 + rl; r < r1; r += RL) s += (double)to_float<T>(V[r * F + c]);
+    sm[threadIdx.x] = s;
+    __syncthreads();
+    if (rl == 0 && c < F) {
+      double tot = 0.0;
+      for (int k = 0; k < RL; ++k) tot += sm[k * CW + cl];
+      part[(int64_t)blockIdx.x * F + c] = tot;
+    }
+    __syncthreads();
+  }
+}
+
+__global__ void column_means(const double* __restrict__ part, int n_blocks, int F, int64_t n,
+                             double* __restrict__ mean) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= F) return;
+  double s = 0.0;
+  for (int b = 0; b < n_blocks; ++b) s += part[(int64_t)b * F + c];
+  mean[c] = s / (double)n;
+}
+
+// r_i = ||v_i - mean||^2 (16-lane group per row), block sums of r_i, and the integer degree sums.
+template <typename T>
+__global__ __launch_bounds__(256) void deviations(const T* __restrict__ V, int64_t n, int F,
+                                                  const double* __restrict__ mean, const int32_t* __restrict__ deg,
+                                                  float* __restrict__ per_node, double* __restrict__ block_r,
+                                                  unsigned long long* __restrict__ deg_sums) {
+  __shared__ double sm_r[16];
+  const int grp = threadIdx.x >> 4, l = threadIdx.x & 15;
+  const int64_t i = (int64_t)blockIdx.x * 16 + grp;
+  double r = 0.0;
+  if (i < n) {
+    for (int c = l; c < F; c += 16) {
+      const double d = (double)to_float<T>(V[i * F + c]) - mean[c];
+      r += d * d;
+    }
+  }
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) r += __shfl_xor(r, o, 64);
+  if (l == 0) {
+    sm_r[grp] = i < n ? r : 0.0;
+    if (i < n && per_node) per_node[i] = (float)r;
+  }
+  // degree sums: thread t < 16 takes row blockIdx*16 + t
+  unsigned long long d1 = 0, d2 = 0;
+  if (threadIdx.x < 16) {
+    const int64_t j = (int64_t)blockIdx.x * 16 + threadIdx.x;
+    if (j < n) {
+      const unsigned long long d = (unsigned long long)deg[j];
+      d1 = d;
+      d2 = d * d;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double s = 0.0;
+    for (int k = 0; k < 16; ++k) s += sm_r[k];
+    block_r[blockIdx.x] = s;
+  }
+  if (threadIdx.x < 64) {   // first wave holds all 16 degree lanes
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) {
+      d1 += __shfl_xor(d1, o, 64);
+      d2 += __shfl_xor(d2, o, 64);
+    }
+    if (threadIdx.x == 0) {
+      atomicAdd(&deg_sums[0], d1);
+      atomicAdd(&deg_sums[1], d2);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void finalize_zeta(const double* __restrict__ block_r, int64_t n_blocks, int64_t n,
+                                                     const unsigned long long* __restrict__ deg_sums, double beta,
+                                                     double* __restrict__ out3) {
+  __shared__ double sm[256];
+  double s = 0.0;
+  for (int64_t k = threadIdx.x; k < n_blocks; k += 256) s += block_r[k];
+  sm[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double var = sm[0] / (double)n;
+    const unsigned long long s1 = deg_sums[0], s2 = deg_sums[1];
+    double spp = 0.0;
+    if (s1 != 0) {
+      const double sq = (double)s1 * (double)s1;
+      spp = 0.5 * (1.0 - (double)s2 / sq);
+    }
+    out3[0] = spp / (sqrt(2.0 * var) + beta);
+    out3[1] = spp;
+    out3[2] = var;
+  }
+}
+
+__global__ void zero_u64(unsigned long long* p, int count) {
+  if ((int)threadIdx.x < count) p[threadIdx.x] = 0ull;
+}
+
+struct ConsensusArgs {
+  const float* buf[kMaxConsensus];
+  double w[kMaxConsensus];
+};
+
+// `out` may alias any of the inputs: every element is read from all buffers before it is written.
+__global__ __launch_bounds__(256) void consensus_kernel(ConsensusArgs a, int K, int64_t n, float* out) {
+  const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (e >= n) return;
+  double s = 0.0;
+  for (int k = 0; k < K; ++k) s += a.w[k] * (double)a.buf[k][e];
+  out[e] = (float)s;
+}
+
+template <typename T>
+int variance_t(const gad_graph* g, const T* V, int F, double beta, double* out3, float* per_node, hipStream_t s) {
+  const int64_t n = g->n;
+  // scratch layout (doubles): part[kVarBlocks x F] | mean[F] | block_r[ceil(n/16)] ; then 2 uint64
+  int n_blocks = (int)(n < kVarBlocks ? n : kVarBlocks);
+  const int64_t slab = ceil_div(n, n_blocks);
+  n_blocks = (int)ceil_div(n, slab);
+  double* part = g->red_scratch;
+  double* mean = part + (int64_t)kVarBlocks * F;
+  double* block_r = mean + F;
+  const int64_t r_blocks = ceil_div(n, 16);
+  unsigned long long* deg_sums = reinterpret_cast<unsigned long long*>(block_r + r_blocks);
+  zero_u64<<<1, 64, 0, s>>>(deg_sums, 2);
+  GAD_LAUNCH_CHECK();
+  if (F <= 32) column_sums<T, 32><<<n_blocks, 256, 0, s>>>(V, n, F, slab, part);
+  else if (F <= 64) column_sums<T, 64><<<n_blocks, 256, 0, s>>>(V, n, F, slab, part);
+  else if (F <= 128) column_sums<T, 128><<<n_blocks, 256, 0, s>>>(V, n, F, slab, part);
+  else column_sums<T, 256><<<n_blocks, 256, 0, s>>>(V, n, F, slab, part);
+  GAD_LAUNCH_CHECK();
+  column_means<<<(unsigned)ceil_div(F, 256), 256, 0, s>>>(part, n_blocks, F, n, mean);
+  GAD_LAUNCH_CHECK();
+  deviations<T><<<(unsigned)r_blocks, 256, 0, s>>>(V, n, F, mean, g->deg, per_node, block_r, deg_sums);
+  GAD_LAUNCH_CHECK();
+  finalize_zeta<<<1, 256, 0, s>>>(block_r, r_blocks, n, deg_sums, beta, out3);
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
+}
+
+}  // namespace
+
+size_t variance_scratch_doubles(int64_t n) {
+  return (size_t)kVarBlocks * kMaxWidth + kMaxWidth + (size_t)ceil_div(n, 16) + 4;
+}
+
+int subgraph_variance(const gad_graph* g, const void* V, int F, gad_dtype dtype, double beta, double* out3,
+                      float* per_node, hipStream_t s) {
+  if (dtype == GAD_F32) return variance_t<float>(g, static_cast<const float*>(V), F, beta, out3, per_node, s);
+  return variance_t<uint16_t>(g, static_cast<const uint16_t*>(V), F, beta, out3, per_node, s);
+}
+
+int weighted_consensus(const float* const* bufs, int K, const double* w, int64_t n, float* out, hipStream_t s) {
+  if (n == 0) return GAD_OK;
+  ConsensusArgs a;
+  for (int k = 0; k < K; ++k) {
+    a.buf[k] = bufs[k];
+    a.w[k] = w[k];
+  }
+  for (int k = K; k < kMaxConsensus; ++k) {
+    a.buf[k] = nullptr;
+    a.w[k] = 0.0;
+  }
+  consensus_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(a, K, n, out);
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
+}
+
+}  // namespace gad

@@ -1,0 +1,214 @@
+// Normalised sparse aggregation  out = A~ T,  A~ = D~^-1/2 (A + I) D~^-1/2  (the A~ H of Eq. 7,
+// arXiv 2110.02987; also the backward product A~^T G = A~ G since A~ is symmetric).
+//
+// out_i = dinv_i * sum_{j in row i} dinv_j * T_j.  One wave64 owns one row.  The wave is cut into
+// 64/LPR groups of LPR lanes; a group gathers one neighbour row at a time, each lane holding V
+// consecutive columns (V = 4: 16-byte loads), so a gathered row is read as one contiguous burst.
+// Groups walk the neighbour list interleaved and are combined with wave shuffles at the end.
+// Only the 4-byte column index is read per edge; dinv_j comes from a 4n-byte array that stays in L2.
+// Rows longer than kLongRow are cut into chunks, one wave per chunk, whose raw sums go to a partial
+// buffer and are added in chunk order by a second kernel (deterministic, no floating-point atomics).
+#include "gad_internal.h"
+
+namespace gad {
+namespace {
+
+template <int V>
+struct Vec;
+template <>
+struct Vec<1> {
+  float v[1];
+};
+template <>
+struct Vec<4> {
+  float v[4];
+};
+
+template <int V>
+__device__ __forceinline__ void load_vec(const float* p, float (&r)[V]) {
+  if constexpr (V == 4) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    r[0] = t.x; r[1] = t.y; r[2] = t.z; r[3] = t.w;
+  } else {
+    r[0] = p[0];
+  }
+}
+
+// Sum over the neighbour positions [begin, end) of dinv_j * T_j for this lane's V columns starting at
+// column c (if `active`), combined over the wave's groups.  All lanes return the combined value.
+template <int LPR, int V>
+__device__ __forceinline__ void gather_sum(const int32_t* __restrict__ colidx, const float* __restrict__ dinv,
+                                           const float* __restrict__ T, int64_t ldt, int64_t begin, int64_t end,
+                                           int c, bool active, float (&acc)[V]) {
+  constexpr int G = 64 / LPR;
+  const int lane = threadIdx.x & 63;
+  const int grp = lane / LPR;
+#pragma unroll
+  for (int k = 0; k < V; ++k) acc[k] = 0.f;
+  int64_t p = begin + grp;
+  // four neighbours in flight per group
+  for (; p + 3 * G < end; p += 4 * G) {
+    const int32_t j0 = colidx[p], j1 = colidx[p + G], j2 = colidx[p + 2 * G], j3 = colidx[p + 3 * G];
+    const float d0 = dinv[j0], d1 = dinv[j1], d2 = dinv[j2], d3 = dinv[j3];
+    if (active) {
+      float t0[V], t1[V], t2[V], t3[V];
+      load_vec<V>(T + (int64_t)j0 * ldt + c, t0);
+      load_vec<V>(T + (int64_t)j1 * ldt + c, t1);
+      load_vec<V>(T + (int64_t)j2 * ldt + c, t2);
+      load_vec<V>(T + (int64_t)j3 * ldt + c, t3);
+#pragma unroll
+      for (int k = 0; k < V; ++k) {
+        acc[k] = fmaf(d0, t0[k], acc[k]);
+        acc[k] = fmaf(d1, t1[k], acc[k]);
+        acc[k] = fmaf(d2, t2[k], acc[k]);
+        acc[k] = fmaf(d3, t3[k], acc[k]);
+      }
+    }
+  }
+  for (; p < end; p += G) {
+    const int32_t j = colidx[p];
+    const float d = dinv[j];
+    if (active) {
+      float t[V];
+      load_vec<V>(T + (int64_t)j * ldt + c, t);
+#pragma unroll
+      for (int k = 0; k < V; ++k) acc[k] = fmaf(d, t[k], acc[k]);
+    }
+  }
+#pragma unroll
+  for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+    for (int k = 0; k < V; ++k) acc[k] += __shfl_xor(acc[k], off, 64);
+  }
+}
+
+template <int V>
+__device__ __forceinline__ void store_row(float* __restrict__ out, int64_t ldo, int64_t i, int c, int width,
+                                          float scale, const float (&acc)[V], int epi, const float* __restrict__ aux,
+                                          int64_t ldaux) {
+#pragma unroll
+  for (int k = 0; k < V; ++k) {
+    if (c + k < width) {
+      float v = scale * acc[k];
+      if (epi == EPI_RELU) v = fmaxf(v, 0.f);
+      if (epi == EPI_MASK) v = aux[i * ldaux + c + k] > 0.f ? v : 0.f;
+      out[i * ldo + c + k] = v;
+    }
+  }
+}
+
+// grid.x: 4 rows per block (one per wave); grid.y: column slab of LPR*V columns.
+template <int LPR, int V>
+__global__ __launch_bounds__(256) void spmm_rows(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                                                 const float* __restrict__ dinv, const float* __restrict__ T,
+                                                 int64_t ldt, float* __restrict__ out, int64_t ldo, int width,
+                                                 int64_t n, int epi, const float* __restrict__ aux, int64_t ldaux) {
+  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= n) return;
+  const int64_t begin = rowptr[i], end = rowptr[i + 1];
+  if (end - begin > kLongRow) return;   // handled by spmm_chunks + spmm_long_reduce
+  const int lane = threadIdx.x & 63;
+  const int c = blockIdx.y * (LPR * V) + (lane % LPR) * V;
+  const bool active = c < width;
+  float acc[V];
+  gather_sum<LPR, V>(colidx, dinv, T, ldt, begin, end, c, active, acc);
+  if (active && lane < LPR) store_row<V>(out, ldo, i, c, width, dinv[i], acc, epi, aux, ldaux);
+}
+
+// One wave per chunk of a long row; columns [col0, col0 + slabs * LPR * V) go to partial[chunk][c - col0].
+template <int LPR, int V>
+__global__ __launch_bounds__(256) void spmm_chunks(const int64_t* __restrict__ rowptr,
+                                                   const int32_t* __restrict__ colidx, const float* __restrict__ dinv,
+                                                   const float* __restrict__ T, int64_t ldt, int width, int col0,
+                                                   const int32_t* __restrict__ chunk_row,
+                                                   const int32_t* __restrict__ chunk_begin, int n_chunks,
+                                                   float* __restrict__ partial) {
+  const int ch = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (ch >= n_chunks) return;
+  const int64_t i = chunk_row[ch];
+  const int64_t begin = rowptr[i] + chunk_begin[ch];
+  const int64_t row_end = rowptr[i + 1];
+  const int64_t end = begin + kLongRow < row_end ? begin + kLongRow : row_end;
+  const int lane = threadIdx.x & 63;
+  const int rel = blockIdx.y * (LPR * V) + (lane % LPR) * V;
+  const int c = col0 + rel;
+  const bool active = c < width && rel < kPartialWidth;
+  float acc[V];
+  gather_sum<LPR, V>(colidx, dinv, T, ldt, begin, end, c, active, acc);
+  if (active && lane < LPR) {
+#pragma unroll
+    for (int k = 0; k < V; ++k)
+      if (c + k < width) partial[(int64_t)ch * kPartialWidth + rel + k] = acc[k];
+  }
+}
+
+// One thread per (long row, column): adds the row's partial sums in chunk order.
+__global__ __launch_bounds__(256) void spmm_long_reduce(const int64_t* __restrict__ rowptr,
+                                                        const float* __restrict__ dinv,
+                                                        const int32_t* __restrict__ long_row,
+                                                        const int32_t* __restrict__ long_first,
+                                                        const float* __restrict__ partial, int col0, int ncols,
+                                                        float* __restrict__ out, int64_t ldo, int epi,
+                                                        const float* __restrict__ aux, int64_t ldaux) {
+  const int slot = blockIdx.x;
+  const int64_t i = long_row[slot];
+  const int first = long_first[slot];
+  const int k = (int)((rowptr[i + 1] - rowptr[i] + kLongRow - 1) / kLongRow);
+  const float di = dinv[i];
+  for (int rel = threadIdx.x; rel < ncols; rel += blockDim.x) {
+    float s = 0.f;
+    for (int q = 0; q < k; ++q) s += partial[(int64_t)(first + q) * kPartialWidth + rel];
+    float v = di * s;
+    const int c = col0 + rel;
+    if (epi == EPI_RELU) v = fmaxf(v, 0.f);
+    if (epi == EPI_MASK) v = aux[i * ldaux + c] > 0.f ? v : 0.f;
+    out[i * ldo + c] = v;
+  }
+}
+
+template <int LPR, int V>
+int launch(const gad_graph* g, const float* T, int64_t ldt, float* out, int64_t ldo, int width, int epi,
+           const float* aux, int64_t ldaux, hipStream_t s) {
+  constexpr int slab = LPR * V;
+  const unsigned gx = (unsigned)ceil_div(g->n, 4);
+  const unsigned gy = (unsigned)ceil_div(width, slab);
+  spmm_rows<LPR, V><<<dim3(gx, gy), 256, 0, s>>>(g->rowptr, g->colidx, g->dinv, T, ldt, out, ldo, width, g->n, epi,
+                                                 aux, ldaux);
+  GAD_LAUNCH_CHECK();
+  if (g->n_long > 0) {
+    for (int col0 = 0; col0 < width; col0 += kPartialWidth) {
+      const int ncols = width - col0 < kPartialWidth ? width - col0 : kPartialWidth;
+      const unsigned cy = (unsigned)ceil_div(ncols, slab);
+      spmm_chunks<LPR, V><<<dim3((unsigned)ceil_div(g->n_chunks, 4), cy), 256, 0, s>>>(
+          g->rowptr, g->colidx, g->dinv, T, ldt, width, col0, g->chunk_row, g->chunk_begin, g->n_chunks, g->partial);
+      GAD_LAUNCH_CHECK();
+      spmm_long_reduce<<<(unsigned)g->n_long, 256, 0, s>>>(g->rowptr, g->dinv, g->long_row, g->long_first, g->partial,
+                                                           col0, ncols, out, ldo, epi, aux, ldaux);
+      GAD_LAUNCH_CHECK();
+    }
+  }
+  return GAD_OK;
+}
+
+}  // namespace
+
+int spmm_f32(const gad_graph* g, const float* T, int64_t ldt, float* out, int64_t ldo, int width, int epi,
+             const float* aux, int64_t ldaux, hipStream_t s) {
+  if (g->n == 0 || width == 0) return GAD_OK;
+  const bool vec = (ldt % 4 == 0) && ((reinterpret_cast<uintptr_t>(T) & 15u) == 0);
+  if (vec) {
+    const int lanes = (width + 3) / 4;
+    if (lanes <= 4) return launch<4, 4>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+    if (lanes <= 8) return launch<8, 4>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+    if (lanes <= 16) return launch<16, 4>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+    if (lanes <= 32) return launch<32, 4>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+    return launch<64, 4>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+  }
+  if (width <= 4) return launch<4, 1>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+  if (width <= 8) return launch<8, 1>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+  if (width <= 16) return launch<16, 1>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+  if (width <= 32) return launch<32, 1>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+  return launch<64, 1>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+}
+
+}  // namespace gad

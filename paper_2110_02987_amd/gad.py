@@ -1,0 +1,200 @@
+"""Thin ctypes binding over libgad.so (the C ABI declared in include/gad.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.  PyTorch is
+used for device memory (`torch.Tensor.data_ptr()`) and for the current HIP stream, nothing else.
+There is no fallback: if libgad.so is missing or a call fails, a GadError / OSError is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgad.so")
+
+F32, BF16 = 0, 1
+SYMBOLS = ["gad_last_error", "gad_build_subgraph", "gad_graph_info", "gad_graph_destroy",
+           "gad_gcn_workspace_bytes", "gad_gcn_forward", "gad_gcn_backward", "gad_gcn_activation", "gad_spmm",
+           "gad_subgraph_variance", "gad_weighted_consensus"]
+
+_lib = None
+_hip = None
+
+
+class GadError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"libgad status {status}: {msg}")
+        self.status = status
+
+
+def lib() -> C.CDLL:
+    """Load libgad.so (built in-tree by `python -m paper_2110_02987_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise OSError(f"{LIB_PATH} not found: build it with `python -m paper_2110_02987_amd.build`")
+        _lib = C.CDLL(LIB_PATH)
+        _lib.gad_last_error.restype = C.c_char_p
+        for name in SYMBOLS[1:]:
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+def _check(st: int) -> None:
+    if st != 0:
+        raise GadError(st, lib().gad_last_error().decode())
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> C.c_void_p:
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous {dtype} device tensor")
+    return t
+
+
+def _memcpy_d2d(dst: torch.Tensor, src_ptr: int, nbytes: int) -> None:
+    global _hip
+    if _hip is None:
+        _hip = C.CDLL("libamdhip64.so")
+    if nbytes:
+        rc = _hip.hipMemcpy(C.c_void_p(dst.data_ptr()), C.c_void_p(src_ptr), C.c_size_t(nbytes), C.c_int(3))
+        if rc != 0:
+            raise RuntimeError(f"hipMemcpy failed with {rc}")
+
+
+class Graph:
+    """Owner of a gad_graph handle."""
+
+    def __init__(self, handle: C.c_void_p):
+        self.handle = handle
+        n, nl, nnz = C.c_int64(), C.c_int64(), C.c_int64()
+        self._rowptr, self._colidx, self._deg, self._dinv = C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_void_p()
+        _check(lib().gad_graph_info(handle, C.byref(n), C.byref(nl), C.byref(nnz), C.byref(self._rowptr),
+                                    C.byref(self._colidx), C.byref(self._deg), C.byref(self._dinv)))
+        self.n, self.n_local, self.nnz = n.value, nl.value, nnz.value
+
+    def _copy(self, ptr, count, dtype):
+        out = torch.empty(count, dtype=dtype, device="cuda")
+        torch.cuda.synchronize()
+        _memcpy_d2d(out, ptr.value, out.numel() * out.element_size())
+        return out
+
+    def rowptr(self): return self._copy(self._rowptr, self.n + 1, torch.int64)
+    def colidx(self): return self._copy(self._colidx, self.nnz, torch.int32)
+    def deg(self): return self._copy(self._deg, self.n, torch.int32)
+    def dinv(self): return self._copy(self._dinv, self.n, torch.float32)
+
+    def destroy(self):
+        if self.handle:
+            _check(lib().gad_graph_destroy(self.handle))
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def build_subgraph(src: torch.Tensor, dst: torch.Tensor, n_global: int, local_ids: torch.Tensor,
+                   halo_ids: torch.Tensor) -> Graph:
+    for name, t in (("src", src), ("dst", dst), ("local_ids", local_ids), ("halo_ids", halo_ids)):
+        _dev(t, torch.int64, name)
+    if src.numel() != dst.numel():
+        raise ValueError("src and dst differ in length")
+    h = C.c_void_p()
+    _check(lib().gad_build_subgraph(_ptr(src if src.numel() else None), _ptr(dst if dst.numel() else None),
+                                    C.c_int64(src.numel()), C.c_int64(n_global),
+                                    _ptr(local_ids if local_ids.numel() else None), C.c_int64(local_ids.numel()),
+                                    _ptr(halo_ids if halo_ids.numel() else None), C.c_int64(halo_ids.numel()),
+                                    _stream(), C.byref(h)))
+    return Graph(h)
+
+
+def _dims(dims: Sequence[int]):
+    return (C.c_int32 * len(dims))(*dims)
+
+
+def _ptr_array(ts: Sequence[torch.Tensor]):
+    return (C.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+
+
+def gcn_workspace_bytes(g: Graph, dims: Sequence[int], dtype: int = F32) -> int:
+    b = C.c_size_t()
+    _check(lib().gad_gcn_workspace_bytes(g.handle, C.c_int(len(dims) - 1), _dims(dims), C.c_int(dtype), C.byref(b)))
+    return b.value
+
+
+def alloc_workspace(g: Graph, dims: Sequence[int], dtype: int = F32) -> torch.Tensor:
+    return torch.empty(gcn_workspace_bytes(g, dims, dtype), dtype=torch.uint8, device="cuda")
+
+
+def gcn_forward(g: Graph, X: torch.Tensor, dims: Sequence[int], W: List[torch.Tensor], labels: torch.Tensor,
+                mask: Optional[torch.Tensor], loss_scale: float, workspace: torch.Tensor,
+                logits_out: Optional[torch.Tensor] = None, loss_out: Optional[torch.Tensor] = None,
+                dtype: int = F32) -> None:
+    _dev(X, torch.float32 if dtype == F32 else torch.bfloat16, "X")
+    _dev(labels, torch.int32, "labels")
+    if mask is not None:
+        _dev(mask, torch.uint8, "mask")
+    for w in W:
+        _dev(w, torch.float32, "W")
+    if logits_out is not None:
+        _dev(logits_out, torch.float32, "logits_out")
+    if loss_out is not None:
+        _dev(loss_out, torch.float64, "loss_out")
+    _check(lib().gad_gcn_forward(g.handle, _ptr(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims), _ptr_array(W),
+                                 _ptr(labels), _ptr(mask), C.c_float(loss_scale), _ptr(workspace),
+                                 C.c_size_t(workspace.numel()), _ptr(logits_out), _ptr(loss_out), _stream()))
+
+
+def gcn_backward(g: Graph, X: torch.Tensor, dims: Sequence[int], W: List[torch.Tensor], workspace: torch.Tensor,
+                 dW: List[torch.Tensor], G_out: Optional[List[Optional[torch.Tensor]]] = None, dtype: int = F32) -> None:
+    for w in dW:
+        _dev(w, torch.float32, "dW")
+    gp = None
+    if G_out is not None:
+        gp = (C.c_void_p * len(G_out))(*[0 if t is None else _dev(t, torch.float32, "G_out").data_ptr() for t in G_out])
+    _check(lib().gad_gcn_backward(g.handle, _ptr(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims), _ptr_array(W),
+                                  _ptr(workspace), C.c_size_t(workspace.numel()), _ptr_array(dW), gp, _stream()))
+
+
+def gcn_activation(g: Graph, workspace: torch.Tensor, dims: Sequence[int], layer: int, out: torch.Tensor,
+                   dtype: int = F32) -> None:
+    _dev(out, torch.float32, "out")
+    _check(lib().gad_gcn_activation(g.handle, _ptr(workspace), C.c_size_t(workspace.numel()), C.c_int(len(dims) - 1),
+                                    _dims(dims), C.c_int(dtype), C.c_int(layer), _ptr(out), _stream()))
+
+
+def spmm(g: Graph, T: torch.Tensor, out: torch.Tensor, width: Optional[int] = None, dtype: int = F32) -> None:
+    """out = A~ T for 2-D row-major T, out (leading dimensions = their second sizes)."""
+    width = int(width if width is not None else T.shape[1])
+    _check(lib().gad_spmm(g.handle, _ptr(T), C.c_int64(T.shape[1]), _ptr(out), C.c_int64(out.shape[1]),
+                          C.c_int32(width), C.c_int(dtype), _stream()))
+
+
+def subgraph_variance(g: Graph, V: torch.Tensor, beta: float, out3: torch.Tensor,
+                      per_node_out: Optional[torch.Tensor] = None) -> None:
+    dtype = F32 if V.dtype == torch.float32 else BF16
+    _dev(V, torch.float32 if dtype == F32 else torch.bfloat16, "V")
+    _dev(out3, torch.float64, "out3")
+    _check(lib().gad_subgraph_variance(g.handle, _ptr(V), C.c_int32(V.shape[1]), C.c_int(dtype), C.c_double(beta),
+                                       _ptr(out3), _ptr(per_node_out), _stream()))
+
+
+def weighted_consensus(bufs: List[torch.Tensor], zeta: Sequence[float], out: torch.Tensor) -> None:
+    for b in bufs:
+        _dev(b, torch.float32, "bufs")
+    z = (C.c_double * len(zeta))(*[float(v) for v in zeta])
+    _check(lib().gad_weighted_consensus(_ptr_array(bufs), C.c_int(len(bufs)), z, C.c_int64(out.numel()), _ptr(out),
+                                        _stream()))

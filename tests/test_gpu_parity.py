@@ -1,0 +1,366 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded inputs.
+
+Bar: bit-exact for rowptr / colidx / deg (and dinv, which both sides round once from float64);
+relative error <= 1e-4 (float32 path) for activations, loss, gradients and variances, measured per
+tensor as ||gpu - ref||_F / ||ref||_F and as max|gpu - ref| / max|ref|.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gad_csr as T1
+from oracle import gad_dense as T0
+from paper_2110_02987_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def gad():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2110_02987_amd import gad as g
+    g.lib()          # fail loudly if the extension is missing
+    return g
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def rel_err(x, ref):
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    fro = np.linalg.norm(x - ref) / max(np.linalg.norm(ref), 1e-300)
+    mx = np.abs(x - ref).max() / max(np.abs(ref).max(), 1e-300)
+    return max(fro, mx)
+
+
+def build_both(gad, gr):
+    g = gad.build_subgraph(dev(gr["src"]), dev(gr["dst"]), gr["n_global"], dev(gr["local_ids"]), dev(gr["halo_ids"]))
+    ref = T1.build(**gr)
+    return g, ref
+
+
+def assert_csr_equal(g, ref):
+    assert (g.n, g.nnz) == (ref.n, ref.nnz)
+    assert np.array_equal(g.rowptr().cpu().numpy(), ref.rowptr)
+    assert np.array_equal(g.colidx().cpu().numpy(), ref.colidx)
+    assert np.array_equal(g.deg().cpu().numpy(), ref.deg)
+    assert np.array_equal(g.dinv().cpu().numpy(), ref.dinv)
+
+
+# ------------------------------------------------------------------------------------------ graph build
+
+def test_build_hand_example(gad):
+    local = np.array([10, 3, 7], dtype=np.int64)
+    halo = np.array([5, 0], dtype=np.int64)
+    src = np.array([10, 3, 3, 7, 5, 0, 5, 8, 10, 2, 7, 99, -1], dtype=np.int64)
+    dst = np.array([3, 10, 3, 5, 7, 5, 0, 10, 8, 9, 7, 3, 10], dtype=np.int64)
+    gr = dict(src=src, dst=dst, n_global=12, local_ids=local, halo_ids=halo)
+    g, ref = build_both(gad, gr)
+    assert_csr_equal(g, ref)
+    assert g.rowptr().cpu().tolist() == [0, 2, 4, 6, 9, 11]
+    assert g.colidx().cpu().tolist() == [0, 1, 0, 1, 2, 3, 2, 3, 4, 3, 4]
+    assert g.n_local == 3
+
+
+@pytest.mark.parametrize("name", ["tiny", "products_small", "rmat16"])
+def test_build_matches_oracle(gad, name):
+    gr = wl.make_graph(wl.CONFIGS[name])
+    g, ref = build_both(gad, gr)
+    assert_csr_equal(g, ref)
+    # built twice: identical (the unordered append inside the build must not show)
+    g2, _ = build_both(gad, gr)
+    assert torch.equal(g.colidx(), g2.colidx()) and torch.equal(g.rowptr(), g2.rowptr())
+
+
+def test_build_degenerate(gad):
+    none = np.zeros(0, dtype=np.int64)
+    # single node, no edges
+    g, ref = build_both(gad, dict(src=none, dst=none, n_global=1, local_ids=np.array([0]), halo_ids=none))
+    assert_csr_equal(g, ref)
+    # edges only outside the node set; all-halo subgraph
+    gr = dict(src=np.array([5, 6, 7], dtype=np.int64), dst=np.array([6, 7, 5], dtype=np.int64), n_global=9,
+              local_ids=none, halo_ids=np.array([0, 1, 2], dtype=np.int64))
+    g, ref = build_both(gad, gr)
+    assert_csr_equal(g, ref)
+    assert g.nnz == 3
+    # star with a hub longer than the long-row threshold (exercises the chunked rows of the SpMM schedule)
+    n = 5000
+    gr = dict(src=np.zeros(n - 1, dtype=np.int64), dst=np.arange(1, n, dtype=np.int64), n_global=n,
+              local_ids=np.arange(n, dtype=np.int64), halo_ids=none)
+    g, ref = build_both(gad, gr)
+    assert_csr_equal(g, ref)
+
+
+def test_build_errors(gad):
+    src = dev(np.array([0, 1], dtype=np.int64))
+    none = dev(np.zeros(0, dtype=np.int64))
+    for ids, halo, status in ((np.array([0, 1, 1]), None, -4), (np.array([0, 1]), np.array([1]), -4),
+                              (np.array([0, 4]), None, -3), (np.array([-1]), None, -3)):
+        with pytest.raises(gad.GadError) as e:
+            gad.build_subgraph(src, src, 4, dev(ids.astype(np.int64)), none if halo is None else dev(halo.astype(np.int64)))
+        assert e.value.status == status
+    with pytest.raises(gad.GadError) as e:
+        gad.build_subgraph(src, src, 4, none, none)
+    assert e.value.status == -2
+    # the library still works after the errors
+    g = gad.build_subgraph(src, src.flip(0), 4, dev(np.arange(4, dtype=np.int64)), none)
+    assert g.nnz == 6
+
+
+# ------------------------------------------------------------------------------------------ SpMM
+
+@pytest.mark.parametrize("width,ld", [(1, 1), (3, 3), (16, 16), (47, 47), (47, 48), (64, 64), (100, 100), (100, 112),
+                                      (128, 128), (256, 256), (300, 300), (602, 602), (1030, 1032)])
+def test_spmm_widths(gad, width, ld):
+    cfg = wl.CONFIGS["products_small"]       # power-law degrees, max degree above the long-row threshold
+    gr = wl.make_graph(cfg)
+    g, ref = build_both(gad, gr)
+    assert ref.deg.max() > 1024
+    rng = np.random.default_rng(width)
+    T = rng.standard_normal((cfg.n, ld)).astype(np.float32)
+    out = torch.full((cfg.n, ld), float("nan"), device="cuda")
+    gad.spmm(g, dev(T), out, width)
+    exp = T1.spmm(ref, T[:, :width].astype(np.float64))
+    got = out.cpu().numpy()
+    assert rel_err(got[:, :width], exp) < TOL
+    if ld > width:
+        assert np.all(np.isnan(got[:, width:]))       # padding columns are never written
+
+
+def test_spmm_star_and_isolated(gad):
+    n = 5000
+    none = np.zeros(0, dtype=np.int64)
+    gr = dict(src=np.zeros(n - 1001, dtype=np.int64), dst=np.arange(1, n - 1000, dtype=np.int64), n_global=n,
+              local_ids=np.arange(n, dtype=np.int64), halo_ids=none)   # hub 0, 1000 isolated nodes
+    g, ref = build_both(gad, gr)
+    T = np.random.default_rng(0).standard_normal((n, 36)).astype(np.float32)
+    out = torch.empty((n, 36), device="cuda")
+    gad.spmm(g, dev(T), out)
+    assert rel_err(out.cpu().numpy(), T1.spmm(ref, T.astype(np.float64))) < TOL
+    assert torch.equal(out[-1000:].cpu(), torch.from_numpy(T[-1000:]))     # A~ = I on isolated rows
+    # run-to-run bitwise reproducibility
+    out2 = torch.empty_like(out)
+    gad.spmm(g, dev(T), out2)
+    assert torch.equal(out, out2)
+
+
+# ------------------------------------------------------------------------------------------ forward / backward
+
+def run_gpu_step(gad, g, X, Ws, y, mask, c, dims):
+    """One forward + backward through the C ABI.  Returns logits, loss, dW, hidden activations H_1..H_{L-1}
+    and the per-node gradients G_1..G_L."""
+    L = len(dims) - 1
+    ws = gad.alloc_workspace(g, dims)
+    Xd, Wd = dev(X), [dev(w) for w in Ws]
+    logits = torch.empty((g.n, dims[-1]), device="cuda")
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    dW = [torch.full_like(w, float("nan")) for w in Wd]
+    Gout = [torch.full((g.n, dims[l + 1]), float("nan"), device="cuda") for l in range(L)]
+    gad.gcn_forward(g, Xd, dims, Wd, dev(y), None if mask is None else dev(mask), c, ws, logits, loss)
+    Hs = []
+    for l in range(1, L):
+        h = torch.empty((g.n, dims[l]), device="cuda")
+        gad.gcn_activation(g, ws, dims, l, h)
+        Hs.append(h.cpu().numpy())
+    gad.gcn_backward(g, Xd, dims, Wd, ws, dW, Gout)
+    torch.cuda.synchronize()
+    return logits.cpu().numpy(), loss.item(), [d.cpu().numpy() for d in dW], Hs, [t.cpu().numpy() for t in Gout]
+
+
+def relu_decisions(f, Ws, Hs_gpu):
+    """ReLU decisions for the oracle's backward: its own [P_l > 0], except where |P_l| is below float32
+    rounding of the sum that forms it -- there the decision is the kernel's (read off its activation).
+    Returns the decisions and the number of entries taken from the kernel."""
+    out, taken = [], 0
+    for l, h in enumerate(Hs_gpu):
+        P = f["P"][l]
+        on = P > 0
+        differ = on != (h > 0)
+        if differ.any():
+            bound = np.abs(f["AH"][l]) @ np.abs(np.asarray(Ws[l], dtype=np.float64))    # sum of |terms| of P_l
+            assert np.all(np.abs(P[differ]) <= 1e-5 * bound[differ]), "activation sign differs beyond rounding"
+            on = np.where(differ, h > 0, on)
+            taken += int(differ.sum())
+        out.append(on)
+    return out, taken
+
+
+def check_step(gad, g, ref, X, Ws, y, mask, c, dims):
+    logits, loss, dW, Hs, Gs = run_gpu_step(gad, g, X, Ws, y, mask, c, dims)
+    m = np.ones(g.n, dtype=np.uint8) if mask is None else mask
+    f = T1.forward(ref, X, Ws, y, m, c)
+    assert rel_err(logits, f["Z"]) < TOL
+    assert abs(loss - f["loss"]) <= TOL * abs(f["loss"])
+    for l, h in enumerate(Hs):
+        assert rel_err(h, f["H"][l + 1]) < TOL, f"H[{l + 1}]"
+    relu_on, taken = relu_decisions(f, Ws, Hs)
+    assert taken <= 1e-6 * sum(h.size for h in Hs) + 2
+    d_ref, G_ref = T1.backward(ref, Ws, f, y, m, c, relu_on=relu_on)
+    for l in range(len(dW)):
+        assert rel_err(Gs[l], G_ref[l]) < TOL, f"G[{l}]"
+        assert rel_err(dW[l], d_ref[l]) < TOL, f"dW[{l}]"
+    return f
+
+
+@pytest.mark.parametrize("name,dims", [("tiny", None), ("products_small", None), ("products_small", (100, 32, 64, 7)),
+                                       ("tiny", (128, 200, 3)), ("tiny", (5, 4)), ("products_small", (33, 41, 47, 41, 602, 13))])
+def test_gcn_step_matches_oracle(gad, name, dims):
+    cfg = wl.CONFIGS[name]
+    dims = tuple(dims or cfg.dims)
+    gr = wl.make_graph(cfg)
+    g, ref = build_both(gad, gr)
+    X = wl.make_features(cfg.n, dims[0])
+    Ws = wl.make_weights(dims)
+    y = wl.make_labels(cfg.n, dims[-1])
+    mask = wl.make_mask(cfg)
+    check_step(gad, g, ref, X, Ws, y, mask, 1.0 / mask.sum(), dims)
+
+
+def test_gcn_step_sum_loss_no_mask_and_dense_oracle(gad):
+    """loss_scale = 1 (Eq. 9 literally a sum), mask = NULL, against the dense definition-level oracle."""
+    cfg = wl.CONFIGS["tiny"]
+    gr = wl.make_graph(cfg)
+    g, _ = build_both(gad, gr)
+    X = wl.make_features(cfg.n, 128)
+    Ws = wl.make_weights(cfg.dims, seed=3)
+    y = wl.make_labels(cfg.n, 16, seed=3)
+    logits, loss, dW, Hs, _ = run_gpu_step(gad, g, X, Ws, y, None, 1.0, cfg.dims)
+    At = T0.normalized_adjacency(T0.adjacency_dense(**gr))
+    ones = np.ones(cfg.n, dtype=np.uint8)
+    f = T0.forward(At, X, Ws, y, ones, 1.0)
+    relu_on = [np.where(np.abs(f["P"][0]) < 1e-6, Hs[0] > 0, f["P"][0] > 0)]
+    d_ref, _ = T0.backward(At, Ws, f, y, ones, 1.0, relu_on=relu_on)
+    assert rel_err(logits, f["Z"]) < TOL
+    assert abs(loss - f["loss"]) <= TOL * abs(f["loss"])
+    for a, b in zip(dW, d_ref):
+        assert rel_err(a, b) < TOL
+
+
+def test_gcn_errors(gad):
+    cfg = wl.CONFIGS["tiny"]
+    g, _ = build_both(gad, wl.make_graph(cfg))
+    dims = cfg.dims
+    X, Ws = dev(wl.make_features(cfg.n, 128)), [dev(w) for w in wl.make_weights(dims)]
+    y = dev(wl.make_labels(cfg.n, 16))
+    ws = gad.alloc_workspace(g, dims)
+    dW = [torch.empty_like(w) for w in Ws]
+    with pytest.raises(gad.GadError) as e:                    # backward before any forward
+        gad.gcn_backward(g, X, dims, Ws, ws, dW)
+    assert e.value.status == -9
+    with pytest.raises(gad.GadError) as e:                    # workspace too small
+        gad.gcn_forward(g, X, dims, Ws, y, None, 1.0, ws[: ws.numel() // 2])
+    assert e.value.status == -5
+    with pytest.raises(gad.GadError) as e:                    # misaligned workspace
+        gad.gcn_forward(g, X, dims, Ws, y, None, 1.0, torch.empty(ws.numel() + 8, dtype=torch.uint8, device="cuda")[8:])
+    assert e.value.status == -5
+    with pytest.raises(gad.GadError) as e:
+        gad.gcn_workspace_bytes(g, (128, 0, 16))
+    assert e.value.status == -2
+    gad.gcn_forward(g, X, dims, Ws, y, None, 1.0, ws)
+    with pytest.raises(gad.GadError) as e:                    # backward with other dims than the forward
+        gad.gcn_backward(g, X, (128, 64, 16, 16), Ws + [Ws[1]], ws, dW + [dW[1]])
+    assert e.value.status in (-9, -5)
+    gad.gcn_backward(g, X, dims, Ws, ws, dW)
+    torch.cuda.synchronize()
+    assert all(torch.isfinite(d).all() for d in dW)
+
+
+# ------------------------------------------------------------------------------------------ GAD-Optimizer
+
+@pytest.mark.parametrize("name,F", [("tiny", 128), ("products_small", 100), ("products_small", 47), ("tiny", 1),
+                                    ("products_small", 300)])
+def test_subgraph_variance(gad, name, F):
+    cfg = wl.CONFIGS[name]
+    g, ref = build_both(gad, wl.make_graph(cfg))
+    V = wl.make_features(cfg.n, F, sub=1) * 1.7 + 0.3
+    out3 = torch.zeros(3, dtype=torch.float64, device="cuda")
+    per = torch.empty(cfg.n, device="cuda")
+    gad.subgraph_variance(g, dev(V), 1.0, out3, per)
+    z, spp, var, r = T1.zeta(ref, V, 1.0)
+    got = out3.cpu().numpy()
+    assert abs(got[0] - z) <= TOL * z and abs(got[1] - spp) <= 1e-12 * spp and abs(got[2] - var) <= TOL * var
+    assert rel_err(per.cpu().numpy(), r) < TOL
+    out3b = torch.zeros(3, dtype=torch.float64, device="cuda")
+    gad.subgraph_variance(g, dev(V), 0.1, out3b, None)         # per-node output is optional; beta is honoured
+    assert abs(out3b[0].item() - T1.zeta(ref, V, 0.1)[0]) <= TOL * T1.zeta(ref, V, 0.1)[0]
+    assert torch.equal(out3b[1:], out3[1:])                     # reproducible bit for bit
+
+
+def test_variance_worked_example_on_gpu(gad):
+    """The paper's example (Section 3.4.1): d = 0, beta = 0.1 -> 3.75, 3.61, 3.59."""
+    for pairs, printed in (([(0, 1), (1, 2), (2, 3), (3, 0)], 3.75), ([(0, 1), (1, 2), (2, 3)], 3.61),
+                           ([(0, 1), (0, 2), (0, 3), (1, 2)], 3.59)):
+        src = dev(np.array([a for a, _ in pairs], dtype=np.int64))
+        dst = dev(np.array([b for _, b in pairs], dtype=np.int64))
+        g = gad.build_subgraph(src, dst, 4, dev(np.arange(4, dtype=np.int64)), dev(np.zeros(0, dtype=np.int64)))
+        out3 = torch.zeros(3, dtype=torch.float64, device="cuda")
+        gad.subgraph_variance(g, torch.full((4, 3), 0.7, device="cuda"), 0.1, out3)
+        assert round(out3[0].item(), 2) == printed and out3[2].item() == 0.0
+
+
+def test_variance_edgeless_and_errors(gad):
+    none = dev(np.zeros(0, dtype=np.int64))
+    g = gad.build_subgraph(none, none, 3, dev(np.arange(3, dtype=np.int64)), none)
+    out3 = torch.ones(3, dtype=torch.float64, device="cuda")
+    V = torch.randn(3, 5, device="cuda")
+    gad.subgraph_variance(g, V, 1.0, out3)
+    assert out3[0].item() == 0.0 and out3[1].item() == 0.0 and out3[2].item() > 0
+    for beta in (0.0, -1.0, float("nan"), float("inf")):
+        with pytest.raises(gad.GadError) as e:
+            gad.subgraph_variance(g, V, beta, out3)
+        assert e.value.status == -2
+
+
+@pytest.mark.parametrize("K,P", [(4, 103_168), (1, 17), (7, 1_000_003), (128, 4096)])
+def test_weighted_consensus(gad, K, P):
+    rng = np.random.default_rng(K)
+    bufs = [rng.standard_normal(P).astype(np.float32) for _ in range(K)]
+    z = rng.random(K) + 0.05
+    out = torch.empty(P, device="cuda")
+    dbufs = [dev(b) for b in bufs]
+    gad.weighted_consensus(dbufs, z, out)
+    exp = T1.weighted_consensus(bufs, z)
+    assert rel_err(out.cpu().numpy(), exp) < 1e-6
+    # equal weights: the plain mean of Eq. 11
+    gad.weighted_consensus(dbufs, [2.5] * K, out)
+    assert rel_err(out.cpu().numpy(), np.mean(np.array(bufs, dtype=np.float64), axis=0)) < 1e-6
+    # in place: out aliases one of the inputs
+    gad.weighted_consensus(dbufs, z, dbufs[0])
+    assert rel_err(dbufs[0].cpu().numpy(), exp) < 1e-6
+
+
+def test_consensus_on_products_parameter_copies(gad):
+    """4-way weighted consensus of parameter copies with zeta from four variance calls (third workload's shape)."""
+    cfg = wl.CONFIGS["products_small"]
+    g, ref = build_both(gad, wl.make_graph(cfg))
+    zs_gpu, zs_ref = [], []
+    for k in range(cfg.consensus_k):
+        V = wl.make_features(cfg.n, cfg.dims[0], sub=10 + k) * (1.0 + 0.5 * k)
+        out3 = torch.zeros(3, dtype=torch.float64, device="cuda")
+        gad.subgraph_variance(g, dev(V), 1.0, out3)
+        zs_gpu.append(out3[0].item())
+        zs_ref.append(T1.zeta(ref, V, 1.0)[0])
+    copies = wl.make_param_copies(cfg.dims, cfg.consensus_k)
+    out = torch.empty(cfg.n_params, device="cuda")
+    gad.weighted_consensus([dev(c) for c in copies], zs_gpu, out)
+    assert rel_err(out.cpu().numpy(), T1.weighted_consensus(copies, zs_ref)) < TOL
+
+
+def test_consensus_errors(gad):
+    b = [torch.ones(8, device="cuda") for _ in range(3)]
+    out = torch.empty(8, device="cuda")
+    for z in ([0, 0, 0], [1, -1, 1], [1, float("nan"), 1], [1, float("inf"), 1]):
+        with pytest.raises(gad.GadError) as e:
+            gad.weighted_consensus(b, z, out)
+        assert e.value.status == -6
+    with pytest.raises(gad.GadError) as e:
+        gad.weighted_consensus(b * 43, [1.0] * 129, out)
+    assert e.value.status == -2
