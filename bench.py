@@ -30,6 +30,9 @@ def main() -> int:
     ap.add_argument("--workload", default="products_part")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=20, help="standalone launches of the dominant kernel")
+    ap.add_argument("--kernels-only", action="store_true",
+                    help="profiling aid: run only a 1 GiB device copy (counter calibration) and the standalone SpMM "
+                         "launches, no training steps, no CPU baseline")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs one augmented subgraph on ONE GPU; the only cross-GPU step of the method "
@@ -89,6 +92,14 @@ def main() -> int:
             e[3].record()
             record.append(e)
 
+    if args.kernels_only:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)                       # plain copy: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
+        args.warmup, args.steps, args.no_cpu_baseline = 0, 1, True
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

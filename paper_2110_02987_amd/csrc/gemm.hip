@@ -211,7 +211,7 @@ bool vec_ok(const float* p, int64_t ld) { return (ld % 4 == 0) && ((reinterpret_
 
 void tn_split(int64_t M, int K, int N, int* n_slabs, int64_t* slab_rows) {
   const int64_t tiles = ceil_div(K, BM) * ceil_div(N, BN);
-  int64_t want = ceil_div(2048, tiles);               // ~8 blocks per CU over the whole grid
+  int64_t want = ceil_div(512, tiles);                // ~2 blocks per CU over the whole grid
   const int64_t max_slabs = ceil_div(M, 512);         // at least 512 reduction rows per slab
   if (want > max_slabs) want = max_slabs;
   if (want < 1) want = 1;

@@ -6,7 +6,7 @@
 //   * weighted global consensus, Eq. 15 (Eq. 11 when all zeta are equal):
 //       out = sum_k (zeta_k / sum_j zeta_j) B_k.
 // All floating-point reductions are float64 and ordered (per thread, per block, then over blocks), so
-// results are reproducible from run to run; the integer sums use 64-bit atomics, which are exact.
+// results are reproducible from run to run; the degree sums are exact 64-bit integer sums.
 #include <math.h>
 
 #include "gad_internal.h"
@@ -61,7 +61,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void deviations(const T* __restrict__ V, int64_t n, int F,
                                                   const double* __restrict__ mean, const int32_t* __restrict__ deg,
                                                   float* __restrict__ per_node, double* __restrict__ block_r,
-                                                  unsigned long long* __restrict__ deg_sums) {
+                                                  unsigned long long* __restrict__ block_d1,
+                                                  unsigned long long* __restrict__ block_d2) {
   __shared__ double sm_r[16];
   const int grp = threadIdx.x >> 4, l = threadIdx.x & 15;
   const int64_t i = (int64_t)blockIdx.x * 16 + grp;
@@ -101,27 +102,40 @@ __global__ __launch_bounds__(256) void deviations(const T* __restrict__ V, int64
       d2 += __shfl_xor(d2, o, 64);
     }
     if (threadIdx.x == 0) {
-      atomicAdd(&deg_sums[0], d1);
-      atomicAdd(&deg_sums[1], d2);
+      block_d1[blockIdx.x] = d1;
+      block_d2[blockIdx.x] = d2;
     }
   }
 }
 
 __global__ __launch_bounds__(256) void finalize_zeta(const double* __restrict__ block_r, int64_t n_blocks, int64_t n,
-                                                     const unsigned long long* __restrict__ deg_sums, double beta,
+                                                     const unsigned long long* __restrict__ block_d1,
+                                                     const unsigned long long* __restrict__ block_d2, double beta,
                                                      double* __restrict__ out3) {
   __shared__ double sm[256];
+  __shared__ unsigned long long sd1[256], sd2[256];
   double s = 0.0;
-  for (int64_t k = threadIdx.x; k < n_blocks; k += 256) s += block_r[k];
+  unsigned long long a1 = 0, a2 = 0;
+  for (int64_t k = threadIdx.x; k < n_blocks; k += 256) {
+    s += block_r[k];
+    a1 += block_d1[k];
+    a2 += block_d2[k];
+  }
   sm[threadIdx.x] = s;
+  sd1[threadIdx.x] = a1;
+  sd2[threadIdx.x] = a2;
   __syncthreads();
   for (int o = 128; o > 0; o >>= 1) {
-    if ((int)threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
+    if ((int)threadIdx.x < o) {
+      sm[threadIdx.x] += sm[threadIdx.x + o];
+      sd1[threadIdx.x] += sd1[threadIdx.x + o];
+      sd2[threadIdx.x] += sd2[threadIdx.x + o];
+    }
     __syncthreads();
   }
   if (threadIdx.x == 0) {
     const double var = sm[0] / (double)n;
-    const unsigned long long s1 = deg_sums[0], s2 = deg_sums[1];
+    const unsigned long long s1 = sd1[0], s2 = sd2[0];
     double spp = 0.0;
     if (s1 != 0) {
       const double sq = (double)s1 * (double)s1;
@@ -131,10 +145,6 @@ __global__ __launch_bounds__(256) void finalize_zeta(const double* __restrict__ 
     out3[1] = spp;
     out3[2] = var;
   }
-}
-
-__global__ void zero_u64(unsigned long long* p, int count) {
-  if ((int)threadIdx.x < count) p[threadIdx.x] = 0ull;
 }
 
 struct ConsensusArgs {
@@ -154,7 +164,7 @@ __global__ __launch_bounds__(256) void consensus_kernel(ConsensusArgs a, int K, 
 template <typename T>
 int variance_t(const gad_graph* g, const T* V, int F, double beta, double* out3, float* per_node, hipStream_t s) {
   const int64_t n = g->n;
-  // scratch layout (doubles): part[kVarBlocks x F] | mean[F] | block_r[ceil(n/16)] ; then 2 uint64
+  // scratch layout (8-byte words): part[kVarBlocks x F] | mean[F] | block_r[nb] | block_d1[nb] | block_d2[nb], nb = ceil(n/16)
   int n_blocks = (int)(n < kVarBlocks ? n : kVarBlocks);
   const int64_t slab = ceil_div(n, n_blocks);
   n_blocks = (int)ceil_div(n, slab);
@@ -162,9 +172,8 @@ int variance_t(const gad_graph* g, const T* V, int F, double beta, double* out3,
   double* mean = part + (int64_t)kVarBlocks * F;
   double* block_r = mean + F;
   const int64_t r_blocks = ceil_div(n, 16);
-  unsigned long long* deg_sums = reinterpret_cast<unsigned long long*>(block_r + r_blocks);
-  zero_u64<<<1, 64, 0, s>>>(deg_sums, 2);
-  GAD_LAUNCH_CHECK();
+  unsigned long long* block_d1 = reinterpret_cast<unsigned long long*>(block_r + r_blocks);
+  unsigned long long* block_d2 = block_d1 + r_blocks;
   if (F <= 32) column_sums<T, 32><<<n_blocks, 256, 0, s>>>(V, n, F, slab, part);
   else if (F <= 64) column_sums<T, 64><<<n_blocks, 256, 0, s>>>(V, n, F, slab, part);
   else if (F <= 128) column_sums<T, 128><<<n_blocks, 256, 0, s>>>(V, n, F, slab, part);
@@ -172,9 +181,9 @@ int variance_t(const gad_graph* g, const T* V, int F, double beta, double* out3,
   GAD_LAUNCH_CHECK();
   column_means<<<(unsigned)ceil_div(F, 256), 256, 0, s>>>(part, n_blocks, F, n, mean);
   GAD_LAUNCH_CHECK();
-  deviations<T><<<(unsigned)r_blocks, 256, 0, s>>>(V, n, F, mean, g->deg, per_node, block_r, deg_sums);
+  deviations<T><<<(unsigned)r_blocks, 256, 0, s>>>(V, n, F, mean, g->deg, per_node, block_r, block_d1, block_d2);
   GAD_LAUNCH_CHECK();
-  finalize_zeta<<<1, 256, 0, s>>>(block_r, r_blocks, n, deg_sums, beta, out3);
+  finalize_zeta<<<1, 256, 0, s>>>(block_r, r_blocks, n, block_d1, block_d2, beta, out3);
   GAD_LAUNCH_CHECK();
   return GAD_OK;
 }
@@ -182,7 +191,7 @@ int variance_t(const gad_graph* g, const T* V, int F, double beta, double* out3,
 }  // namespace
 
 size_t variance_scratch_doubles(int64_t n) {
-  return (size_t)kVarBlocks * kMaxWidth + kMaxWidth + (size_t)ceil_div(n, 16) + 4;
+  return (size_t)kVarBlocks * kMaxWidth + kMaxWidth + 3 * (size_t)ceil_div(n, 16) + 4;
 }
 
 int subgraph_variance(const gad_graph* g, const void* V, int F, gad_dtype dtype, double beta, double* out3,

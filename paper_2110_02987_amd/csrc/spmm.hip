@@ -14,17 +14,6 @@ namespace gad {
 namespace {
 
 template <int V>
-struct Vec;
-template <>
-struct Vec<1> {
-  float v[1];
-};
-template <>
-struct Vec<4> {
-  float v[4];
-};
-
-template <int V>
 __device__ __forceinline__ void load_vec(const float* p, float (&r)[V]) {
   if constexpr (V == 4) {
     const float4 t = *reinterpret_cast<const float4*>(p);
@@ -97,49 +86,46 @@ __device__ __forceinline__ void store_row(float* __restrict__ out, int64_t ldo, 
   }
 }
 
-// grid.x: 4 rows per block (one per wave); grid.y: column slab of LPR*V columns.
+// One launch covers the whole product.  grid.y: column slab of LPR*V columns.  grid.x: the first
+// `chunk_blocks` blocks take the chunks of the long rows (4 per block, one per wave; the longest work
+// starts first), the remaining blocks take 4 rows each (one per wave) and skip the long rows.
+// Chunk sums go to partial[chunk][column - col0] for columns in [col0, col0 + kPartialWidth).
 template <int LPR, int V>
-__global__ __launch_bounds__(256) void spmm_rows(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
-                                                 const float* __restrict__ dinv, const float* __restrict__ T,
-                                                 int64_t ldt, float* __restrict__ out, int64_t ldo, int width,
-                                                 int64_t n, int epi, const float* __restrict__ aux, int64_t ldaux) {
-  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (i >= n) return;
-  const int64_t begin = rowptr[i], end = rowptr[i + 1];
-  if (end - begin > kLongRow) return;   // handled by spmm_chunks + spmm_long_reduce
-  const int lane = threadIdx.x & 63;
-  const int c = blockIdx.y * (LPR * V) + (lane % LPR) * V;
-  const bool active = c < width;
-  float acc[V];
-  gather_sum<LPR, V>(colidx, dinv, T, ldt, begin, end, c, active, acc);
-  if (active && lane < LPR) store_row<V>(out, ldo, i, c, width, dinv[i], acc, epi, aux, ldaux);
-}
-
-// One wave per chunk of a long row; columns [col0, col0 + slabs * LPR * V) go to partial[chunk][c - col0].
-template <int LPR, int V>
-__global__ __launch_bounds__(256) void spmm_chunks(const int64_t* __restrict__ rowptr,
-                                                   const int32_t* __restrict__ colidx, const float* __restrict__ dinv,
-                                                   const float* __restrict__ T, int64_t ldt, int width, int col0,
+__global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                                                   const float* __restrict__ dinv, const float* __restrict__ T,
+                                                   int64_t ldt, float* __restrict__ out, int64_t ldo, int width,
+                                                   int col0, int64_t n, int epi, const float* __restrict__ aux,
+                                                   int64_t ldaux, int chunk_blocks,
                                                    const int32_t* __restrict__ chunk_row,
                                                    const int32_t* __restrict__ chunk_begin, int n_chunks,
                                                    float* __restrict__ partial) {
-  const int ch = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (ch >= n_chunks) return;
-  const int64_t i = chunk_row[ch];
-  const int64_t begin = rowptr[i] + chunk_begin[ch];
-  const int64_t row_end = rowptr[i + 1];
-  const int64_t end = begin + kLongRow < row_end ? begin + kLongRow : row_end;
   const int lane = threadIdx.x & 63;
   const int rel = blockIdx.y * (LPR * V) + (lane % LPR) * V;
   const int c = col0 + rel;
-  const bool active = c < width && rel < kPartialWidth;
   float acc[V];
-  gather_sum<LPR, V>(colidx, dinv, T, ldt, begin, end, c, active, acc);
-  if (active && lane < LPR) {
+  if ((int)blockIdx.x < chunk_blocks) {
+    const int ch = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (ch >= n_chunks) return;
+    const int64_t i = chunk_row[ch];
+    const int64_t begin = rowptr[i] + chunk_begin[ch];
+    const int64_t row_end = rowptr[i + 1];
+    const int64_t end = begin + kLongRow < row_end ? begin + kLongRow : row_end;
+    const bool active = c < width && rel < kPartialWidth;
+    gather_sum<LPR, V>(colidx, dinv, T, ldt, begin, end, c, active, acc);
+    if (active && lane < LPR) {
 #pragma unroll
-    for (int k = 0; k < V; ++k)
-      if (c + k < width) partial[(int64_t)ch * kPartialWidth + rel + k] = acc[k];
+      for (int k = 0; k < V; ++k)
+        if (c + k < width) partial[(int64_t)ch * kPartialWidth + rel + k] = acc[k];
+    }
+    return;
   }
+  const int64_t i = (int64_t)(blockIdx.x - chunk_blocks) * 4 + (threadIdx.x >> 6);
+  if (i >= n) return;
+  const int64_t begin = rowptr[i], end = rowptr[i + 1];
+  if (end - begin > kLongRow) return;   // summed by the chunk blocks + spmm_long_reduce
+  const bool active = c < width;
+  gather_sum<LPR, V>(colidx, dinv, T, ldt, begin, end, c, active, acc);
+  if (active && lane < LPR) store_row<V>(out, ldo, i, c, width, dinv[i], acc, epi, aux, ldaux);
 }
 
 // One thread per (long row, column): adds the row's partial sums in chunk order.
@@ -170,18 +156,17 @@ template <int LPR, int V>
 int launch(const gad_graph* g, const float* T, int64_t ldt, float* out, int64_t ldo, int width, int epi,
            const float* aux, int64_t ldaux, hipStream_t s) {
   constexpr int slab = LPR * V;
-  const unsigned gx = (unsigned)ceil_div(g->n, 4);
-  const unsigned gy = (unsigned)ceil_div(width, slab);
-  spmm_rows<LPR, V><<<dim3(gx, gy), 256, 0, s>>>(g->rowptr, g->colidx, g->dinv, T, ldt, out, ldo, width, g->n, epi,
-                                                 aux, ldaux);
-  GAD_LAUNCH_CHECK();
-  if (g->n_long > 0) {
-    for (int col0 = 0; col0 < width; col0 += kPartialWidth) {
-      const int ncols = width - col0 < kPartialWidth ? width - col0 : kPartialWidth;
-      const unsigned cy = (unsigned)ceil_div(ncols, slab);
-      spmm_chunks<LPR, V><<<dim3((unsigned)ceil_div(g->n_chunks, 4), cy), 256, 0, s>>>(
-          g->rowptr, g->colidx, g->dinv, T, ldt, width, col0, g->chunk_row, g->chunk_begin, g->n_chunks, g->partial);
-      GAD_LAUNCH_CHECK();
+  const unsigned row_blocks = (unsigned)ceil_div(g->n, 4);
+  const unsigned chunk_blocks = (unsigned)ceil_div(g->n_chunks, 4);
+  // Columns are covered kPartialWidth at a time: one pass for every width the GCN step uses.
+  for (int col0 = 0; col0 < width; col0 += kPartialWidth) {
+    const int ncols = width - col0 < kPartialWidth ? width - col0 : kPartialWidth;
+    const dim3 grid(chunk_blocks + row_blocks, (unsigned)ceil_div(ncols, slab));
+    spmm_kernel<LPR, V><<<grid, 256, 0, s>>>(g->rowptr, g->colidx, g->dinv, T, ldt, out, ldo, col0 + ncols, col0, g->n,
+                                             epi, aux, ldaux, (int)chunk_blocks, g->chunk_row, g->chunk_begin,
+                                             g->n_chunks, g->partial);
+    GAD_LAUNCH_CHECK();
+    if (g->n_long > 0) {
       spmm_long_reduce<<<(unsigned)g->n_long, 256, 0, s>>>(g->rowptr, g->dinv, g->long_row, g->long_first, g->partial,
                                                            col0, ncols, out, ldo, epi, aux, ldaux);
       GAD_LAUNCH_CHECK();
