@@ -144,17 +144,24 @@ def main() -> int:
                        compulsory_bytes=compulsory, gather_model_bytes=gather)
         del T, O
     dom = max(spmm, key=lambda w: spmm[w]["ms"] * spmm[w]["launches_per_step"])
-    roofline = dict(bound="hbm", kernel=f"spmm_rows width {dom} f32", achieved=spmm[dom]["compulsory_GBps"],
+    roofline = dict(bound="hbm", kernel=f"spmm_kernel (A~ T at width {dom}, f32)", achieved=spmm[dom]["compulsory_GBps"],
                     peak=HBM_PEAK_GBPS, unit="GB/s", frac=spmm[dom]["compulsory_GBps"] / HBM_PEAK_GBPS,
                     traffic=None, avg_launch_ms=spmm[dom]["ms"], model="compulsory: 4*nnz + 12*n + 2*n*w*4 bytes",
                     gather_model_GBps=spmm[dom]["gather_model_GBps"],
                     gather_model_frac=spmm[dom]["gather_model_GBps"] / HBM_PEAK_GBPS)
-    tr = os.path.join(ROOT, "profiles", f"spmm_traffic_{cfg.name}.json")
-    if os.path.exists(tr):          # HBM bytes per launch from rocprofv3 --pmc runs (see profiles/)
-        t = json.load(open(tr)).get(str(dom))
-        if t:
-            roofline["traffic"] = t["hbm_bytes_per_launch"]
-            roofline["measured_hbm_frac"] = t["hbm_bytes_per_launch"] / (spmm[dom]["ms"] * 1e-3) / (HBM_PEAK_GBPS * 1e9)
+    # HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE in KiB, each scaled by
+    # what the same counter reads for a plain 1 GiB copy); None when no summary covers this workload.
+    tr = os.path.join(ROOT, "profiles", f"spmm_{cfg.name}_hbm_traffic.txt")
+    if os.path.exists(tr):
+        for line in open(tr):
+            if line.startswith("traffic "):
+                kv = dict(t.split("=") for t in line.split()[1:])
+                if int(kv["width"]) == dom:
+                    nbytes = 1024.0 * (float(kv["fetch_kib"]) * float(kv["fetch_scale"]) +
+                                       float(kv["write_kib"]) * float(kv["write_scale"]))
+                    roofline["traffic"] = nbytes
+                    roofline["traffic_GBps"] = nbytes / spmm[dom]["ms"] * 1e-6
+                    roofline["traffic_frac_of_peak"] = roofline["traffic_GBps"] / HBM_PEAK_GBPS
 
     out = dict(metric="GCN fwd+bwd edges/s per layer and epoch ms per subgraph; SpMM % of HBM peak",
                value=value, unit="edges/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step,
