@@ -49,7 +49,8 @@ int make_plan(const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, P
   for (int l = 0; l <= L; ++l)
     if (dims[l] < 1 || dims[l] > kMaxWidth)
       return set_error(GAD_ERR_SHAPE, "dims[%d] = %d outside [1, %d]", l, dims[l], kMaxWidth);
-  if (dtype != GAD_F32) return set_error(GAD_ERR_UNSUPPORTED, "only GAD_F32 is implemented for the GCN step");
+  if (dtype != GAD_F32 && dtype != GAD_BF16) return set_error(GAD_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
+  const size_t esz = dtype == GAD_F32 ? sizeof(float) : sizeof(uint16_t);   // node matrices; logits stay float32
   p->L = L;
   const size_t n = (size_t)g->n;
   size_t off = 0;
@@ -65,8 +66,8 @@ int make_plan(const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, P
     if (pad_ld(dims[l]) > p->max_ld) p->max_ld = pad_ld(dims[l]);
   for (int l = 0; l < L; ++l) {
     p->agg_first[l] = dims[l] <= dims[l + 1];
-    p->agg[l] = p->agg_first[l] ? take(n * pad_ld(dims[l]) * sizeof(float)) : 0;
-    p->act[l + 1] = take(n * pad_ld(dims[l + 1]) * sizeof(float));
+    p->agg[l] = p->agg_first[l] ? take(n * pad_ld(dims[l]) * esz) : 0;
+    p->act[l + 1] = take(n * pad_ld(dims[l + 1]) * (l + 1 == L ? sizeof(float) : esz));
     if (p->agg_first[l] && pad_ld(dims[l]) > p->max_ld) p->max_ld = pad_ld(dims[l]);
     const size_t w = (size_t)dims[l] * dims[l + 1];
     if (w > max_w) max_w = w;
@@ -74,9 +75,9 @@ int make_plan(const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, P
     if (t > max_tn) max_tn = t;
   }
   p->act[0] = 0;
-  p->g_a = take(n * p->max_ld * sizeof(float));
-  p->g_b = take(n * p->max_ld * sizeof(float));
-  p->tmp = take(n * p->max_ld * sizeof(float));
+  p->g_a = take(n * p->max_ld * esz);
+  p->g_b = take(n * p->max_ld * esz);
+  p->tmp = take(n * p->max_ld * esz);
   p->wt = take(max_w * sizeof(float));
   p->tn = take(max_tn * sizeof(float));
   p->sm = take(softmax_partial_doubles(g->n) * sizeof(double));
@@ -120,7 +121,7 @@ bool forward_saved(const gad_graph* g, const void* ws, int L, const int32_t* dim
   return ok;
 }
 
-inline float* at(void* ws, size_t off) { return reinterpret_cast<float*>(static_cast<char*>(ws) + off); }
+inline void* at(void* ws, size_t off) { return static_cast<char*>(ws) + off; }
 
 }  // namespace
 }  // namespace gad
@@ -201,35 +202,38 @@ int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, c
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int64_t n = g->n;
 
-  const float* h = static_cast<const float*>(X);
+  const void* h = X;
   int64_t ldh = dims[0];
   for (int l = 0; l < L; ++l) {
     const bool last = l == L - 1;
     const int epi = last ? EPI_NONE : EPI_RELU;
-    float* dst = at(workspace, p.act[l + 1]);
+    const gad_dtype t_dst = last ? GAD_F32 : dtype;      // the logits are kept in float32
+    void* dst = at(workspace, p.act[l + 1]);
     const int64_t ldd = pad_ld(dims[l + 1]);
     if (p.agg_first[l]) {
-      float* m = at(workspace, p.agg[l]);
+      void* m = at(workspace, p.agg[l]);
       const int64_t ldm = pad_ld(dims[l]);
-      if ((st = spmm_f32(g, h, ldh, m, ldm, dims[l], EPI_NONE, nullptr, 0, s)) != GAD_OK) return st;
-      if ((st = gemm_nn_f32(m, ldm, W[l], dims[l + 1], dst, ldd, n, dims[l + 1], dims[l], epi, nullptr, 0, s)) != GAD_OK)
+      if ((st = spmm(g, h, ldh, dtype, m, ldm, dtype, dims[l], EPI_NONE, nullptr, 0, s)) != GAD_OK) return st;
+      if ((st = gemm_nn(m, ldm, dtype, W[l], dims[l + 1], dst, ldd, t_dst, n, dims[l + 1], dims[l], epi, nullptr, 0,
+                        s)) != GAD_OK)
         return st;
     } else {
-      float* t = at(workspace, p.tmp);
-      if ((st = gemm_nn_f32(h, ldh, W[l], dims[l + 1], t, ldd, n, dims[l + 1], dims[l], EPI_NONE, nullptr, 0, s)) !=
-          GAD_OK)
+      void* t = at(workspace, p.tmp);
+      if ((st = gemm_nn(h, ldh, dtype, W[l], dims[l + 1], t, ldd, dtype, n, dims[l + 1], dims[l], EPI_NONE, nullptr, 0,
+                        s)) != GAD_OK)
         return st;
-      if ((st = spmm_f32(g, t, ldd, dst, ldd, dims[l + 1], epi, nullptr, 0, s)) != GAD_OK) return st;
+      if ((st = spmm(g, t, ldd, dtype, dst, ldd, t_dst, dims[l + 1], epi, nullptr, 0, s)) != GAD_OK) return st;
     }
     h = dst;
     ldh = ldd;
   }
   const int C = dims[L];
   const int64_t ldz = pad_ld(C);
-  st = softmax_xent_f32(h, ldz, labels, mask, loss_scale, n, C, at(workspace, p.g_a), ldz,
-                        reinterpret_cast<double*>(at(workspace, p.sm)), loss_out, s);
+  const float* Z = static_cast<const float*>(h);
+  st = softmax_xent(Z, ldz, labels, mask, loss_scale, n, C, at(workspace, p.g_a), ldz, dtype,
+                    static_cast<double*>(at(workspace, p.sm)), loss_out, s);
   if (st != GAD_OK) return st;
-  if (logits_out && (st = copy_rows_f32(h, ldz, logits_out, C, n, C, s)) != GAD_OK) return st;
+  if (logits_out && (st = copy_rows(Z, ldz, GAD_F32, logits_out, C, n, C, s)) != GAD_OK) return st;
   {
     std::lock_guard<std::mutex> lk(g_saved_mu);
     g_saved[workspace] = Saved{g, L, std::vector<int32_t>(dims, dims + L + 1), dtype, X};
@@ -252,36 +256,37 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
     return set_error(GAD_ERR_STATE, "workspace holds no forward pass matching this graph / model / X");
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int64_t n = g->n;
-  float* gcur = at(workspace, p.g_a);
-  float* gnext = at(workspace, p.g_b);
-  float* tmp = at(workspace, p.tmp);
-  float* wt = at(workspace, p.wt);
-  float* tn = at(workspace, p.tn);
+  void* gcur = at(workspace, p.g_a);
+  void* gnext = at(workspace, p.g_b);
+  void* tmp = at(workspace, p.tmp);
+  float* wt = static_cast<float*>(at(workspace, p.wt));
+  float* tn = static_cast<float*>(at(workspace, p.tn));
   for (int l = L - 1; l >= 0; --l) {
     const int fin = dims[l], fout = dims[l + 1];
     const int64_t ldg = pad_ld(fout);        // G_l, S_l
     const int64_t ldi = pad_ld(fin);         // dM, G_{l-1}, H_l
-    const float* hin = l == 0 ? static_cast<const float*>(X) : at(workspace, p.act[l]);
+    const void* hin = l == 0 ? X : at(workspace, p.act[l]);
     const int64_t ldhin = l == 0 ? dims[0] : ldi;
-    if (G_out && G_out[l] && (st = copy_rows_f32(gcur, ldg, G_out[l], fout, n, fout, s)) != GAD_OK) return st;
+    if (G_out && G_out[l] && (st = copy_rows(gcur, ldg, dtype, G_out[l], fout, n, fout, s)) != GAD_OK) return st;
     if (p.agg_first[l]) {
-      if ((st = gemm_tn_f32(at(workspace, p.agg[l]), ldi, gcur, ldg, dW[l], fout, n, fin, fout, tn, s)) != GAD_OK)
+      if ((st = gemm_tn(at(workspace, p.agg[l]), ldi, gcur, ldg, dtype, dW[l], fout, n, fin, fout, tn, s)) != GAD_OK)
         return st;
       if (l > 0) {
         if ((st = transpose_f32(W[l], fin, fout, wt, s)) != GAD_OK) return st;
-        if ((st = gemm_nn_f32(gcur, ldg, wt, fin, tmp, ldi, n, fin, fout, EPI_NONE, nullptr, 0, s)) != GAD_OK) return st;
-        if ((st = spmm_f32(g, tmp, ldi, gnext, ldi, fin, EPI_MASK, hin, ldhin, s)) != GAD_OK) return st;
+        if ((st = gemm_nn(gcur, ldg, dtype, wt, fin, tmp, ldi, dtype, n, fin, fout, EPI_NONE, nullptr, 0, s)) != GAD_OK)
+          return st;
+        if ((st = spmm(g, tmp, ldi, dtype, gnext, ldi, dtype, fin, EPI_MASK, hin, ldhin, s)) != GAD_OK) return st;
       }
     } else {
-      if ((st = spmm_f32(g, gcur, ldg, tmp, ldg, fout, EPI_NONE, nullptr, 0, s)) != GAD_OK) return st;
-      if ((st = gemm_tn_f32(hin, ldhin, tmp, ldg, dW[l], fout, n, fin, fout, tn, s)) != GAD_OK) return st;
+      if ((st = spmm(g, gcur, ldg, dtype, tmp, ldg, dtype, fout, EPI_NONE, nullptr, 0, s)) != GAD_OK) return st;
+      if ((st = gemm_tn(hin, ldhin, tmp, ldg, dtype, dW[l], fout, n, fin, fout, tn, s)) != GAD_OK) return st;
       if (l > 0) {
         if ((st = transpose_f32(W[l], fin, fout, wt, s)) != GAD_OK) return st;
-        if ((st = gemm_nn_f32(tmp, ldg, wt, fin, gnext, ldi, n, fin, fout, EPI_MASK, hin, ldhin, s)) != GAD_OK)
+        if ((st = gemm_nn(tmp, ldg, dtype, wt, fin, gnext, ldi, dtype, n, fin, fout, EPI_MASK, hin, ldhin, s)) != GAD_OK)
           return st;
       }
     }
-    float* t = gcur;
+    void* t = gcur;
     gcur = gnext;
     gnext = t;
   }
@@ -298,8 +303,8 @@ int gad_gcn_activation(const gad_graph* g, const void* workspace, size_t workspa
   if (layer < 1 || layer > L) return set_error(GAD_ERR_SHAPE, "layer = %d outside [1, %d]", layer, L);
   if (!forward_saved(g, workspace, L, dims, dtype, nullptr))
     return set_error(GAD_ERR_STATE, "workspace holds no forward pass matching this graph / model");
-  return copy_rows_f32(at(const_cast<void*>(workspace), p.act[layer]), pad_ld(dims[layer]), out, dims[layer], g->n,
-                       dims[layer], static_cast<hipStream_t>(hip_stream));
+  return copy_rows(at(const_cast<void*>(workspace), p.act[layer]), pad_ld(dims[layer]), layer == L ? GAD_F32 : dtype, out,
+                   dims[layer], g->n, dims[layer], static_cast<hipStream_t>(hip_stream));
 }
 
 int gad_spmm(const gad_graph* g, const void* T, int64_t ldt, void* out, int64_t ldo, int32_t width, gad_dtype dtype,
@@ -307,9 +312,8 @@ int gad_spmm(const gad_graph* g, const void* T, int64_t ldt, void* out, int64_t 
   if (!g || !T || !out) return set_error(GAD_ERR_NULL, "graph, T or out is NULL");
   if (width < 1 || ldt < width || ldo < width) return set_error(GAD_ERR_SHAPE, "width < 1 or a leading dimension < width");
   if (T == out) return set_error(GAD_ERR_SHAPE, "out must not alias T");
-  if (dtype != GAD_F32) return set_error(GAD_ERR_UNSUPPORTED, "only GAD_F32 is implemented for gad_spmm");
-  return spmm_f32(g, static_cast<const float*>(T), ldt, static_cast<float*>(out), ldo, width, EPI_NONE, nullptr, 0,
-                  static_cast<hipStream_t>(hip_stream));
+  if (dtype != GAD_F32 && dtype != GAD_BF16) return set_error(GAD_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
+  return spmm(g, T, ldt, dtype, out, ldo, dtype, width, EPI_NONE, nullptr, 0, static_cast<hipStream_t>(hip_stream));
 }
 
 int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta, double* out3,

@@ -69,26 +69,28 @@ namespace gad {
 // ---- kernels' host entry points (each enqueues on `s` and returns a gad_status) -------------
 int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int64_t n_global, const int64_t* local_ids,
                    int64_t n_local, const int64_t* halo_ids, int64_t n_halo, hipStream_t s, gad_graph** out);
-int spmm_f32(const gad_graph* g, const float* T, int64_t ldt, float* out, int64_t ldo, int width, int epilogue,
-             const float* aux, int64_t ldaux, hipStream_t s);
+// Node matrices are float32 or bfloat16 (gad_dtype); weights, partial sums and logits are float32.
+// out = A~ T with the epilogue applied; aux (EPI_MASK) has T's storage type.
+int spmm(const gad_graph* g, const void* T, int64_t ldt, gad_dtype t_in, void* out, int64_t ldo, gad_dtype t_out,
+         int width, int epilogue, const void* aux, int64_t ldaux, hipStream_t s);
 
-// C[M x N] (ldc) = A[M x K] (lda) * B[K x N] (ldb), with the SpMM epilogues applied to C.
-int gemm_nn_f32(const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t M, int N,
-                int K, int epilogue, const float* aux, int64_t ldaux, hipStream_t s);
+// C[M x N] (ldc) = A[M x K] (lda) * B[K x N] (ldb) with the epilogue applied to C; aux has A's storage type.
+int gemm_nn(const void* A, int64_t lda, gad_dtype ta, const float* B, int64_t ldb, void* C, int64_t ldc, gad_dtype tc,
+            int64_t M, int N, int K, int epilogue, const void* aux, int64_t ldaux, hipStream_t s);
 // C[K x N] (ldc) = A[M x K]^T * G[M x N]; `partials` must hold gemm_tn_partial_floats(M, K, N) floats.
 size_t gemm_tn_partial_floats(int64_t M, int K, int N);
-int gemm_tn_f32(const float* A, int64_t lda, const float* G, int64_t ldg, float* C, int64_t ldc, int64_t M, int K,
-                int N, float* partials, hipStream_t s);
+int gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, gad_dtype t, float* C, int64_t ldc, int64_t M,
+            int K, int N, float* partials, hipStream_t s);
 int transpose_f32(const float* in, int rows, int cols, float* out, hipStream_t s);   // out[cols x rows]
 
-// Z [n x C] (ldz) -> G [n x C] (ldg), loss (double, device).  block_partials: ceil(n/64) doubles.
+// Z [n x C] (ldz, float32) -> G [n x C] (ldg, storage type tg), loss (double, device).
 size_t softmax_partial_doubles(int64_t n);
-int softmax_xent_f32(const float* Z, int64_t ldz, const int32_t* labels, const uint8_t* mask, float scale, int64_t n,
-                     int C, float* G, int64_t ldg, double* block_partials, double* loss_out, hipStream_t s);
+int softmax_xent(const float* Z, int64_t ldz, const int32_t* labels, const uint8_t* mask, float scale, int64_t n, int C,
+                 void* G, int64_t ldg, gad_dtype tg, double* block_partials, double* loss_out, hipStream_t s);
+int copy_rows(const void* in, int64_t ldi, gad_dtype ti, float* out, int64_t ldo, int64_t n, int width, hipStream_t s);
 size_t variance_scratch_doubles(int64_t n);
 int subgraph_variance(const gad_graph* g, const void* V, int F, gad_dtype dtype, double beta, double* out3,
                       float* per_node, hipStream_t s);
 int weighted_consensus(const float* const* bufs, int K, const double* w, int64_t n, float* out, hipStream_t s);
-int copy_rows_f32(const float* in, int64_t ldi, float* out, int64_t ldo, int64_t n, int width, hipStream_t s);
 
 }  // namespace gad

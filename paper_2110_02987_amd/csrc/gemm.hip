@@ -10,6 +10,9 @@
 // 2 x 2 MFMA 32x32 accumulators.  Both operands are staged through LDS with the reduction index
 // leading (As[kk][i], Bs[kk][j]) so that a fragment read is 64 consecutive floats; the next tile is
 // fetched from global memory into registers while the current one is multiplied (double-buffered LDS).
+// Node matrices (A, G, C of NN, the mask operand) may be stored as float32 or bfloat16; they are widened
+// to float32 when staged, products and sums are float32, weights are always float32.
+#include "dtype.h"
 #include "gad_internal.h"
 
 namespace gad {
@@ -45,21 +48,29 @@ __device__ __forceinline__ void mma_tile(const Tile& t, int wm, int wn, v16f (&a
   }
 }
 
-// Element (row, col) of accumulator register r of a 32x32 MFMA result held by `lane`.
+// Row of accumulator register r of a 32x32 MFMA result held by `lane` (its column is lane % 32).
 __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
-// ---- loaders: 8 consecutive floats per thread, zero-filled outside the matrix -----------------
-// "row-major, reduction index contiguous" (A of NN): thread -> (row = t/2, k-segment = (t%2)*8)
-__device__ __forceinline__ void load8(const float* __restrict__ base, int64_t ld, int64_t row, int64_t n_rows, int col,
+// 8 consecutive elements of row `row` starting at column `col`, zero outside the matrix, widened to float.
+// vec_ok: 8 elements may be fetched with 16-byte loads (alignment checked on the host).
+template <typename T>
+__device__ __forceinline__ void load8(const T* __restrict__ base, int64_t ld, int64_t row, int64_t n_rows, int col,
                                       int n_cols, bool vec_ok, float (&r)[8]) {
   if (row < n_rows && vec_ok && col + 8 <= n_cols) {
-    const float4* p = reinterpret_cast<const float4*>(base + row * ld + col);
-    const float4 x = p[0], y = p[1];
-    r[0] = x.x; r[1] = x.y; r[2] = x.z; r[3] = x.w;
-    r[4] = y.x; r[5] = y.y; r[6] = y.z; r[7] = y.w;
+    const T* p = base + row * ld + col;
+    if constexpr (sizeof(T) == 4) {
+      float lo[4], hi[4];
+      load_row_piece<4, T>(p, lo);
+      load_row_piece<4, T>(p + 4, hi);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { r[q] = lo[q]; r[4 + q] = hi[q]; }
+    } else {
+      load_row_piece<8, T>(p, r);
+    }
   } else {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) r[q] = (row < n_rows && col + q < n_cols) ? base[row * ld + col + q] : 0.f;
+    for (int q = 0; q < 8; ++q)
+      r[q] = (row < n_rows && col + q < n_cols) ? to_f32<T>(base[row * ld + col + q]) : 0.f;
   }
 }
 
@@ -73,9 +84,9 @@ __device__ __forceinline__ void store_transposed(float (*dst)[LDS_LD], int i, in
   for (int q = 0; q < 8; ++q) dst[kseg + q][i] = r[q];
 }
 
-template <int EPI>
-__device__ __forceinline__ void store_acc(const v16f (&acc)[2][2], float* __restrict__ C, int64_t ldc, int64_t row0,
-                                          int col0, int64_t M, int N, int wm, int wn, const float* __restrict__ aux,
+template <int EPI, typename TC, typename TX>
+__device__ __forceinline__ void store_acc(const v16f (&acc)[2][2], TC* __restrict__ C, int64_t ldc, int64_t row0,
+                                          int col0, int64_t M, int N, int wm, int wn, const TX* __restrict__ aux,
                                           int64_t ldaux) {
   const int lane = threadIdx.x & 63;
 #pragma unroll
@@ -89,19 +100,19 @@ __device__ __forceinline__ void store_acc(const v16f (&acc)[2][2], float* __rest
         if (row < M && col < N) {
           float v = acc[tm][tn][r];
           if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
-          if (EPI == EPI_MASK) v = aux[row * ldaux + col] > 0.f ? v : 0.f;
-          C[row * ldc + col] = v;
+          if (EPI == EPI_MASK) v = to_f32<TX>(aux[row * ldaux + col]) > 0.f ? v : 0.f;
+          C[row * ldc + col] = from_f32<TC>(v);
         }
       }
     }
 }
 
 // ---- NN ----------------------------------------------------------------------------------------
-template <int EPI>
-__global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ A, int64_t lda,
-                                                      const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
+template <int EPI, typename TA, typename TC>
+__global__ __launch_bounds__(256) void gemm_nn_kernel(const TA* __restrict__ A, int64_t lda,
+                                                      const float* __restrict__ B, int64_t ldb, TC* __restrict__ C,
                                                       int64_t ldc, int64_t M, int N, int K, bool a_vec, bool b_vec,
-                                                      const float* __restrict__ aux, int64_t ldaux) {
+                                                      const TA* __restrict__ aux, int64_t ldaux) {
   __shared__ Tile tiles[2];
   const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
   const int64_t row0 = (int64_t)blockIdx.x * BM;
@@ -118,8 +129,8 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
   float ra[8], rb[8];
-  load8(A, lda, row0 + a_i, M, a_k, K, a_vec, ra);
-  load8(B, ldb, b_k, K, col0 + b_j, N, b_vec, rb);
+  load8<TA>(A, lda, row0 + a_i, M, a_k, K, a_vec, ra);
+  load8<float>(B, ldb, b_k, K, col0 + b_j, N, b_vec, rb);
   store_transposed(tiles[0].a, a_i, a_k, ra);
   store_direct(tiles[0].b, b_k, b_j, rb);
   __syncthreads();
@@ -128,8 +139,8 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
     const int cur = kt & 1;
     if (kt + 1 < n_kt) {
       const int k1 = (kt + 1) * BK;
-      load8(A, lda, row0 + a_i, M, k1 + a_k, K, a_vec, ra);
-      load8(B, ldb, k1 + b_k, K, col0 + b_j, N, b_vec, rb);
+      load8<TA>(A, lda, row0 + a_i, M, k1 + a_k, K, a_vec, ra);
+      load8<float>(B, ldb, k1 + b_k, K, col0 + b_j, N, b_vec, rb);
     }
     mma_tile(tiles[cur], wm, wn, acc);
     if (kt + 1 < n_kt) {
@@ -138,15 +149,15 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
     }
     __syncthreads();
   }
-  store_acc<EPI>(acc, C, ldc, row0, col0, M, N, wm, wn, aux, ldaux);
+  store_acc<EPI, TC, TA>(acc, C, ldc, row0, col0, M, N, wm, wn, aux, ldaux);
 }
 
 // ---- TN ----------------------------------------------------------------------------------------
 // grid: x = output tile (tiles_k * tiles_n), y = slab of M.  Writes P[slab][K x N] (ld N).
-__global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ A, int64_t lda,
-                                                      const float* __restrict__ G, int64_t ldg, float* __restrict__ P,
-                                                      int64_t M, int K, int N, int64_t slab_rows, int tiles_n,
-                                                      bool a_vec, bool g_vec) {
+template <typename TA>
+__global__ __launch_bounds__(256) void gemm_tn_kernel(const TA* __restrict__ A, int64_t lda, const TA* __restrict__ G,
+                                                      int64_t ldg, float* __restrict__ P, int64_t M, int K, int N,
+                                                      int64_t slab_rows, int tiles_n, bool a_vec, bool g_vec) {
   __shared__ Tile tiles[2];
   const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
   const int k0 = (blockIdx.x / tiles_n) * BM;   // output row block (columns of A)
@@ -163,8 +174,8 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ 
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
   float ra[8], rb[8];
-  load8(A, lda, m_begin + l_m, m_end, k0 + l_c, K, a_vec, ra);
-  load8(G, ldg, m_begin + l_m, m_end, n0 + l_c, N, g_vec, rb);
+  load8<TA>(A, lda, m_begin + l_m, m_end, k0 + l_c, K, a_vec, ra);
+  load8<TA>(G, ldg, m_begin + l_m, m_end, n0 + l_c, N, g_vec, rb);
   store_direct(tiles[0].a, l_m, l_c, ra);
   store_direct(tiles[0].b, l_m, l_c, rb);
   __syncthreads();
@@ -173,8 +184,8 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ 
     const int cur = (int)(mt & 1);
     if (mt + 1 < n_mt) {
       const int64_t m1 = m_begin + (mt + 1) * BK + l_m;
-      load8(A, lda, m1, m_end, k0 + l_c, K, a_vec, ra);
-      load8(G, ldg, m1, m_end, n0 + l_c, N, g_vec, rb);
+      load8<TA>(A, lda, m1, m_end, k0 + l_c, K, a_vec, ra);
+      load8<TA>(G, ldg, m1, m_end, n0 + l_c, N, g_vec, rb);
     }
     mma_tile(tiles[cur], wm, wn, acc);
     if (mt + 1 < n_mt) {
@@ -184,7 +195,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ 
     __syncthreads();
   }
   float* Pslab = P + (int64_t)blockIdx.y * K * N;
-  store_acc<EPI_NONE>(acc, Pslab, N, k0, n0, K, N, wm, wn, nullptr, 0);
+  store_acc<EPI_NONE, float, float>(acc, Pslab, N, k0, n0, K, N, wm, wn, nullptr, 0);
 }
 
 __global__ void reduce_slabs(const float* __restrict__ P, int n_slabs, int64_t elems, int N, float* __restrict__ C,
@@ -207,7 +218,11 @@ __global__ void transpose_kernel(const float* __restrict__ in, int rows, int col
     if (ox < rows && oy0 + dy < cols) out[(int64_t)(oy0 + dy) * rows + ox] = tile[threadIdx.x][dy];
 }
 
-bool vec_ok(const float* p, int64_t ld) { return (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(p) & 15u) == 0); }
+// 8 elements of a row can be fetched with 16-byte loads from any column that is a multiple of 8
+template <typename T>
+bool vec_ok(const T* p, int64_t ld) {
+  return (ld % (16 / (int)sizeof(T)) == 0) && ((reinterpret_cast<uintptr_t>(p) & 15u) == 0);
+}
 
 void tn_split(int64_t M, int K, int N, int* n_slabs, int64_t* slab_rows) {
   const int64_t tiles = ceil_div(K, BM) * ceil_div(N, BN);
@@ -219,28 +234,57 @@ void tn_split(int64_t M, int K, int N, int* n_slabs, int64_t* slab_rows) {
   *n_slabs = (int)ceil_div(M, *slab_rows);
 }
 
-}  // namespace
-
-int gemm_nn_f32(const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t M, int N,
-                int K, int epi, const float* aux, int64_t ldaux, hipStream_t s) {
-  if (M == 0 || N == 0) return GAD_OK;
+template <typename TA, typename TC>
+int gemm_nn_typed(const TA* A, int64_t lda, const float* B, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
+                  int epi, const TA* aux, int64_t ldaux, hipStream_t s) {
   const dim3 grid((unsigned)ceil_div(M, BM), (unsigned)ceil_div(N, BN));
   const bool av = vec_ok(A, lda), bv = vec_ok(B, ldb);
   switch (epi) {
     case EPI_NONE:
-      gemm_nn_kernel<EPI_NONE><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, aux, ldaux);
+      gemm_nn_kernel<EPI_NONE, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, aux, ldaux);
       break;
     case EPI_RELU:
-      gemm_nn_kernel<EPI_RELU><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, aux, ldaux);
+      gemm_nn_kernel<EPI_RELU, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, aux, ldaux);
       break;
     case EPI_MASK:
-      gemm_nn_kernel<EPI_MASK><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, aux, ldaux);
+      gemm_nn_kernel<EPI_MASK, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, aux, ldaux);
       break;
     default:
       return set_error(GAD_ERR_UNSUPPORTED, "unknown epilogue %d", epi);
   }
   GAD_LAUNCH_CHECK();
   return GAD_OK;
+}
+
+template <typename TA>
+int gemm_tn_typed(const TA* A, int64_t lda, const TA* G, int64_t ldg, float* C, int64_t ldc, int64_t M, int K, int N,
+                  float* partials, hipStream_t s) {
+  int n_slabs;
+  int64_t slab_rows;
+  tn_split(M, K, N, &n_slabs, &slab_rows);
+  const int tiles_n = (int)ceil_div(N, BN);
+  const dim3 grid((unsigned)(ceil_div(K, BM) * tiles_n), (unsigned)n_slabs);
+  gemm_tn_kernel<TA><<<grid, 256, 0, s>>>(A, lda, G, ldg, partials, M, K, N, slab_rows, tiles_n, vec_ok(A, lda),
+                                          vec_ok(G, ldg));
+  GAD_LAUNCH_CHECK();
+  const int64_t elems = (int64_t)K * N;
+  reduce_slabs<<<(unsigned)ceil_div(elems, 256), 256, 0, s>>>(partials, n_slabs, elems, N, C, ldc);
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
+}
+
+}  // namespace
+
+int gemm_nn(const void* A, int64_t lda, gad_dtype ta, const float* B, int64_t ldb, void* C, int64_t ldc, gad_dtype tc,
+            int64_t M, int N, int K, int epi, const void* aux, int64_t ldaux, hipStream_t s) {
+  if (M == 0 || N == 0) return GAD_OK;
+  if (ta == GAD_F32 && tc == GAD_F32)
+    return gemm_nn_typed<float, float>((const float*)A, lda, B, ldb, (float*)C, ldc, M, N, K, epi, (const float*)aux, ldaux, s);
+  if (ta == GAD_BF16 && tc == GAD_BF16)
+    return gemm_nn_typed<bf16_t, bf16_t>((const bf16_t*)A, lda, B, ldb, (bf16_t*)C, ldc, M, N, K, epi, (const bf16_t*)aux, ldaux, s);
+  if (ta == GAD_BF16 && tc == GAD_F32)
+    return gemm_nn_typed<bf16_t, float>((const bf16_t*)A, lda, B, ldb, (float*)C, ldc, M, N, K, epi, (const bf16_t*)aux, ldaux, s);
+  return set_error(GAD_ERR_UNSUPPORTED, "GEMM from float32 storage to bfloat16 storage is not implemented");
 }
 
 size_t gemm_tn_partial_floats(int64_t M, int K, int N) {
@@ -250,21 +294,11 @@ size_t gemm_tn_partial_floats(int64_t M, int K, int N) {
   return (size_t)n_slabs * (size_t)K * (size_t)N;
 }
 
-int gemm_tn_f32(const float* A, int64_t lda, const float* G, int64_t ldg, float* C, int64_t ldc, int64_t M, int K,
-                int N, float* partials, hipStream_t s) {
+int gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, gad_dtype t, float* C, int64_t ldc, int64_t M,
+            int K, int N, float* partials, hipStream_t s) {
   if (K == 0 || N == 0) return GAD_OK;
-  int n_slabs;
-  int64_t slab_rows;
-  tn_split(M, K, N, &n_slabs, &slab_rows);
-  const int tiles_n = (int)ceil_div(N, BN);
-  const dim3 grid((unsigned)(ceil_div(K, BM) * tiles_n), (unsigned)n_slabs);
-  gemm_tn_kernel<<<grid, 256, 0, s>>>(A, lda, G, ldg, partials, M, K, N, slab_rows, tiles_n, vec_ok(A, lda),
-                                      vec_ok(G, ldg));
-  GAD_LAUNCH_CHECK();
-  const int64_t elems = (int64_t)K * N;
-  reduce_slabs<<<(unsigned)ceil_div(elems, 256), 256, 0, s>>>(partials, n_slabs, elems, N, C, ldc);
-  GAD_LAUNCH_CHECK();
-  return GAD_OK;
+  if (t == GAD_F32) return gemm_tn_typed<float>((const float*)A, lda, (const float*)G, ldg, C, ldc, M, K, N, partials, s);
+  return gemm_tn_typed<bf16_t>((const bf16_t*)A, lda, (const bf16_t*)G, ldg, C, ldc, M, K, N, partials, s);
 }
 
 int transpose_f32(const float* in, int rows, int cols, float* out, hipStream_t s) {

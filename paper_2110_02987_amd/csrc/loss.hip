@@ -6,6 +6,7 @@
 // The loss is summed in float64: per block in a fixed order, then over blocks in a fixed order.
 #include <math.h>
 
+#include "dtype.h"
 #include "gad_internal.h"
 
 namespace gad {
@@ -25,10 +26,11 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
+template <typename TG>
 __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restrict__ Z, int64_t ldz,
                                                            const int32_t* __restrict__ labels,
                                                            const uint8_t* __restrict__ mask, float scale, int64_t n,
-                                                           int C, float* __restrict__ G, int64_t ldg,
+                                                           int C, TG* __restrict__ G, int64_t ldg,
                                                            double* __restrict__ block_partials) {
   __shared__ double row_loss[kRowsPerBlock];
   const int grp = threadIdx.x / kGroup, l = threadIdx.x % kGroup;
@@ -48,7 +50,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restri
     const float inv = 1.f / se;
     for (int c = l; c < C; c += kGroup) {
       const float p = expf(z[c] - m) * inv;
-      G[i * ldg + c] = g_scale * (p - (c == y ? 1.f : 0.f));
+      G[i * ldg + c] = from_f32<TG>(g_scale * (p - (c == y ? 1.f : 0.f)));
     }
     if (on && l == 0) my_loss = (double)scale * ((double)logf(se) + (double)m - (double)z[y]);
   }
@@ -76,24 +78,30 @@ __global__ __launch_bounds__(256) void sum_doubles(const double* __restrict__ v,
   if (threadIdx.x == 0) out[0] = sm[0];
 }
 
-__global__ void copy_rows_kernel(const float* __restrict__ in, int64_t ldi, float* __restrict__ out, int64_t ldo,
+template <typename TI>
+__global__ void copy_rows_kernel(const TI* __restrict__ in, int64_t ldi, float* __restrict__ out, int64_t ldo,
                                  int64_t n, int width) {
   const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
   if (e >= n * width) return;
   const int64_t i = e / width;
   const int c = (int)(e % width);
-  out[i * ldo + c] = in[i * ldi + c];
+  out[i * ldo + c] = to_f32<TI>(in[i * ldi + c]);
 }
 
 }  // namespace
 
 size_t softmax_partial_doubles(int64_t n) { return (size_t)ceil_div(n, kRowsPerBlock) + 1; }
 
-int softmax_xent_f32(const float* Z, int64_t ldz, const int32_t* labels, const uint8_t* mask, float scale, int64_t n,
-                     int C, float* G, int64_t ldg, double* block_partials, double* loss_out, hipStream_t s) {
+int softmax_xent(const float* Z, int64_t ldz, const int32_t* labels, const uint8_t* mask, float scale, int64_t n, int C,
+                 void* G, int64_t ldg, gad_dtype tg, double* block_partials, double* loss_out, hipStream_t s) {
   if (n == 0) return GAD_OK;
   const int64_t blocks = ceil_div(n, kRowsPerBlock);
-  softmax_xent_kernel<<<(unsigned)blocks, 256, 0, s>>>(Z, ldz, labels, mask, scale, n, C, G, ldg, block_partials);
+  if (tg == GAD_F32)
+    softmax_xent_kernel<float><<<(unsigned)blocks, 256, 0, s>>>(Z, ldz, labels, mask, scale, n, C, (float*)G, ldg,
+                                                                block_partials);
+  else
+    softmax_xent_kernel<bf16_t><<<(unsigned)blocks, 256, 0, s>>>(Z, ldz, labels, mask, scale, n, C, (bf16_t*)G, ldg,
+                                                                 block_partials);
   GAD_LAUNCH_CHECK();
   if (loss_out) {
     sum_doubles<<<1, 256, 0, s>>>(block_partials, blocks, loss_out);
@@ -102,9 +110,13 @@ int softmax_xent_f32(const float* Z, int64_t ldz, const int32_t* labels, const u
   return GAD_OK;
 }
 
-int copy_rows_f32(const float* in, int64_t ldi, float* out, int64_t ldo, int64_t n, int width, hipStream_t s) {
+int copy_rows(const void* in, int64_t ldi, gad_dtype ti, float* out, int64_t ldo, int64_t n, int width, hipStream_t s) {
   if (n == 0 || width == 0) return GAD_OK;
-  copy_rows_kernel<<<(unsigned)ceil_div(n * width, 256), 256, 0, s>>>(in, ldi, out, ldo, n, width);
+  const unsigned blocks = (unsigned)ceil_div(n * width, 256);
+  if (ti == GAD_F32)
+    copy_rows_kernel<float><<<blocks, 256, 0, s>>>((const float*)in, ldi, out, ldo, n, width);
+  else
+    copy_rows_kernel<bf16_t><<<blocks, 256, 0, s>>>((const bf16_t*)in, ldi, out, ldo, n, width);
   GAD_LAUNCH_CHECK();
   return GAD_OK;
 }

@@ -3,32 +3,25 @@
 //
 // out_i = dinv_i * sum_{j in row i} dinv_j * T_j.  One wave64 owns one row.  The wave is cut into
 // 64/LPR groups of LPR lanes; a group gathers one neighbour row at a time, each lane holding V
-// consecutive columns (V = 4: 16-byte loads), so a gathered row is read as one contiguous burst.
-// Groups walk the neighbour list interleaved and are combined with wave shuffles at the end.
-// Only the 4-byte column index is read per edge; dinv_j comes from a 4n-byte array that stays in L2.
-// Rows longer than kLongRow are cut into chunks, one wave per chunk, whose raw sums go to a partial
-// buffer and are added in chunk order by a second kernel (deterministic, no floating-point atomics).
+// consecutive columns (16-byte loads: V = 4 float32 or 8 bfloat16), so a gathered row is read as one
+// contiguous burst.  Groups walk the neighbour list interleaved and are combined with wave shuffles at
+// the end.  Accumulation is float32 whatever the storage type.  Only the 4-byte column index is read per
+// edge; dinv_j comes from a 4n-byte array that stays in L2.
+// Rows longer than kLongRow are cut into chunks, one wave per chunk (the first blocks of the same
+// launch), whose raw sums go to a partial buffer and are added in chunk order by a second kernel
+// (deterministic: no floating-point atomics).
+#include "dtype.h"
 #include "gad_internal.h"
 
 namespace gad {
 namespace {
 
-template <int V>
-__device__ __forceinline__ void load_vec(const float* p, float (&r)[V]) {
-  if constexpr (V == 4) {
-    const float4 t = *reinterpret_cast<const float4*>(p);
-    r[0] = t.x; r[1] = t.y; r[2] = t.z; r[3] = t.w;
-  } else {
-    r[0] = p[0];
-  }
-}
-
 // Sum over the neighbour positions [begin, end) of dinv_j * T_j for this lane's V columns starting at
 // column c (if `active`), combined over the wave's groups.  All lanes return the combined value.
-template <int LPR, int V>
+template <int LPR, int V, typename TI>
 __device__ __forceinline__ void gather_sum(const int32_t* __restrict__ colidx, const float* __restrict__ dinv,
-                                           const float* __restrict__ T, int64_t ldt, int64_t begin, int64_t end,
-                                           int c, bool active, float (&acc)[V]) {
+                                           const TI* __restrict__ T, int64_t ldt, int64_t begin, int64_t end, int c,
+                                           bool active, float (&acc)[V]) {
   constexpr int G = 64 / LPR;
   const int lane = threadIdx.x & 63;
   const int grp = lane / LPR;
@@ -41,10 +34,10 @@ __device__ __forceinline__ void gather_sum(const int32_t* __restrict__ colidx, c
     const float d0 = dinv[j0], d1 = dinv[j1], d2 = dinv[j2], d3 = dinv[j3];
     if (active) {
       float t0[V], t1[V], t2[V], t3[V];
-      load_vec<V>(T + (int64_t)j0 * ldt + c, t0);
-      load_vec<V>(T + (int64_t)j1 * ldt + c, t1);
-      load_vec<V>(T + (int64_t)j2 * ldt + c, t2);
-      load_vec<V>(T + (int64_t)j3 * ldt + c, t3);
+      load_row_piece<V, TI>(T + (int64_t)j0 * ldt + c, t0);
+      load_row_piece<V, TI>(T + (int64_t)j1 * ldt + c, t1);
+      load_row_piece<V, TI>(T + (int64_t)j2 * ldt + c, t2);
+      load_row_piece<V, TI>(T + (int64_t)j3 * ldt + c, t3);
 #pragma unroll
       for (int k = 0; k < V; ++k) {
         acc[k] = fmaf(d0, t0[k], acc[k]);
@@ -59,7 +52,7 @@ __device__ __forceinline__ void gather_sum(const int32_t* __restrict__ colidx, c
     const float d = dinv[j];
     if (active) {
       float t[V];
-      load_vec<V>(T + (int64_t)j * ldt + c, t);
+      load_row_piece<V, TI>(T + (int64_t)j * ldt + c, t);
 #pragma unroll
       for (int k = 0; k < V; ++k) acc[k] = fmaf(d, t[k], acc[k]);
     }
@@ -71,32 +64,24 @@ __device__ __forceinline__ void gather_sum(const int32_t* __restrict__ colidx, c
   }
 }
 
-template <int V>
-__device__ __forceinline__ void store_row(float* __restrict__ out, int64_t ldo, int64_t i, int c, int width,
-                                          float scale, const float (&acc)[V], int epi, const float* __restrict__ aux,
-                                          int64_t ldaux) {
-#pragma unroll
-  for (int k = 0; k < V; ++k) {
-    if (c + k < width) {
-      float v = scale * acc[k];
-      if (epi == EPI_RELU) v = fmaxf(v, 0.f);
-      if (epi == EPI_MASK) v = aux[i * ldaux + c + k] > 0.f ? v : 0.f;
-      out[i * ldo + c + k] = v;
-    }
-  }
+template <typename TI, typename TO>
+__device__ __forceinline__ void store_elem(TO* __restrict__ out, int64_t ldo, int64_t i, int c, float v, int epi,
+                                           const TI* __restrict__ aux, int64_t ldaux) {
+  if (epi == EPI_RELU) v = fmaxf(v, 0.f);
+  if (epi == EPI_MASK) v = to_f32<TI>(aux[i * ldaux + c]) > 0.f ? v : 0.f;
+  out[i * ldo + c] = from_f32<TO>(v);
 }
 
 // One launch covers the whole product.  grid.y: column slab of LPR*V columns.  grid.x: the first
 // `chunk_blocks` blocks take the chunks of the long rows (4 per block, one per wave; the longest work
 // starts first), the remaining blocks take 4 rows each (one per wave) and skip the long rows.
 // Chunk sums go to partial[chunk][column - col0] for columns in [col0, col0 + kPartialWidth).
-template <int LPR, int V>
+template <int LPR, int V, typename TI, typename TO>
 __global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
-                                                   const float* __restrict__ dinv, const float* __restrict__ T,
-                                                   int64_t ldt, float* __restrict__ out, int64_t ldo, int width,
-                                                   int col0, int64_t n, int epi, const float* __restrict__ aux,
-                                                   int64_t ldaux, int chunk_blocks,
-                                                   const int32_t* __restrict__ chunk_row,
+                                                   const float* __restrict__ dinv, const TI* __restrict__ T,
+                                                   int64_t ldt, TO* __restrict__ out, int64_t ldo, int width, int col0,
+                                                   int64_t n, int epi, const TI* __restrict__ aux, int64_t ldaux,
+                                                   int chunk_blocks, const int32_t* __restrict__ chunk_row,
                                                    const int32_t* __restrict__ chunk_begin, int n_chunks,
                                                    float* __restrict__ partial) {
   const int lane = threadIdx.x & 63;
@@ -111,7 +96,7 @@ __global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ r
     const int64_t row_end = rowptr[i + 1];
     const int64_t end = begin + kLongRow < row_end ? begin + kLongRow : row_end;
     const bool active = c < width && rel < kPartialWidth;
-    gather_sum<LPR, V>(colidx, dinv, T, ldt, begin, end, c, active, acc);
+    gather_sum<LPR, V, TI>(colidx, dinv, T, ldt, begin, end, c, active, acc);
     if (active && lane < LPR) {
 #pragma unroll
       for (int k = 0; k < V; ++k)
@@ -124,18 +109,24 @@ __global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ r
   const int64_t begin = rowptr[i], end = rowptr[i + 1];
   if (end - begin > kLongRow) return;   // summed by the chunk blocks + spmm_long_reduce
   const bool active = c < width;
-  gather_sum<LPR, V>(colidx, dinv, T, ldt, begin, end, c, active, acc);
-  if (active && lane < LPR) store_row<V>(out, ldo, i, c, width, dinv[i], acc, epi, aux, ldaux);
+  gather_sum<LPR, V, TI>(colidx, dinv, T, ldt, begin, end, c, active, acc);
+  if (active && lane < LPR) {
+    const float di = dinv[i];
+#pragma unroll
+    for (int k = 0; k < V; ++k)
+      if (c + k < width) store_elem<TI, TO>(out, ldo, i, c + k, di * acc[k], epi, aux, ldaux);
+  }
 }
 
 // One thread per (long row, column): adds the row's partial sums in chunk order.
+template <typename TI, typename TO>
 __global__ __launch_bounds__(256) void spmm_long_reduce(const int64_t* __restrict__ rowptr,
                                                         const float* __restrict__ dinv,
                                                         const int32_t* __restrict__ long_row,
                                                         const int32_t* __restrict__ long_first,
                                                         const float* __restrict__ partial, int col0, int ncols,
-                                                        float* __restrict__ out, int64_t ldo, int epi,
-                                                        const float* __restrict__ aux, int64_t ldaux) {
+                                                        TO* __restrict__ out, int64_t ldo, int epi,
+                                                        const TI* __restrict__ aux, int64_t ldaux) {
   const int slot = blockIdx.x;
   const int64_t i = long_row[slot];
   const int first = long_first[slot];
@@ -144,17 +135,13 @@ __global__ __launch_bounds__(256) void spmm_long_reduce(const int64_t* __restric
   for (int rel = threadIdx.x; rel < ncols; rel += blockDim.x) {
     float s = 0.f;
     for (int q = 0; q < k; ++q) s += partial[(int64_t)(first + q) * kPartialWidth + rel];
-    float v = di * s;
-    const int c = col0 + rel;
-    if (epi == EPI_RELU) v = fmaxf(v, 0.f);
-    if (epi == EPI_MASK) v = aux[i * ldaux + c] > 0.f ? v : 0.f;
-    out[i * ldo + c] = v;
+    store_elem<TI, TO>(out, ldo, i, col0 + rel, di * s, epi, aux, ldaux);
   }
 }
 
-template <int LPR, int V>
-int launch(const gad_graph* g, const float* T, int64_t ldt, float* out, int64_t ldo, int width, int epi,
-           const float* aux, int64_t ldaux, hipStream_t s) {
+template <int LPR, int V, typename TI, typename TO>
+int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, int width, int epi, const TI* aux,
+           int64_t ldaux, hipStream_t s) {
   constexpr int slab = LPR * V;
   const unsigned row_blocks = (unsigned)ceil_div(g->n, 4);
   const unsigned chunk_blocks = (unsigned)ceil_div(g->n_chunks, 4);
@@ -162,38 +149,50 @@ int launch(const gad_graph* g, const float* T, int64_t ldt, float* out, int64_t 
   for (int col0 = 0; col0 < width; col0 += kPartialWidth) {
     const int ncols = width - col0 < kPartialWidth ? width - col0 : kPartialWidth;
     const dim3 grid(chunk_blocks + row_blocks, (unsigned)ceil_div(ncols, slab));
-    spmm_kernel<LPR, V><<<grid, 256, 0, s>>>(g->rowptr, g->colidx, g->dinv, T, ldt, out, ldo, col0 + ncols, col0, g->n,
-                                             epi, aux, ldaux, (int)chunk_blocks, g->chunk_row, g->chunk_begin,
-                                             g->n_chunks, g->partial);
+    spmm_kernel<LPR, V, TI, TO><<<grid, 256, 0, s>>>(g->rowptr, g->colidx, g->dinv, T, ldt, out, ldo, col0 + ncols, col0,
+                                                     g->n, epi, aux, ldaux, (int)chunk_blocks, g->chunk_row,
+                                                     g->chunk_begin, g->n_chunks, g->partial);
     GAD_LAUNCH_CHECK();
     if (g->n_long > 0) {
-      spmm_long_reduce<<<(unsigned)g->n_long, 256, 0, s>>>(g->rowptr, g->dinv, g->long_row, g->long_first, g->partial,
-                                                           col0, ncols, out, ldo, epi, aux, ldaux);
+      spmm_long_reduce<TI, TO><<<(unsigned)g->n_long, 256, 0, s>>>(g->rowptr, g->dinv, g->long_row, g->long_first,
+                                                                   g->partial, col0, ncols, out, ldo, epi, aux, ldaux);
       GAD_LAUNCH_CHECK();
     }
   }
   return GAD_OK;
 }
 
+template <typename TI, typename TO>
+int spmm_typed(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, int width, int epi, const TI* aux,
+               int64_t ldaux, hipStream_t s) {
+  constexpr int VEC = 16 / (int)sizeof(TI);      // elements per 16-byte load
+  const bool vec = (ldt % VEC == 0) && ((reinterpret_cast<uintptr_t>(T) & 15u) == 0);
+  const int lanes = vec ? (width + VEC - 1) / VEC : width;
+#define GAD_SPMM_CASE(L)                                                                                   \
+  if (lanes <= L)                                                                                          \
+    return vec ? launch<L, VEC, TI, TO>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s)                  \
+               : launch<L, 1, TI, TO>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+  GAD_SPMM_CASE(4)
+  GAD_SPMM_CASE(8)
+  GAD_SPMM_CASE(16)
+  GAD_SPMM_CASE(32)
+#undef GAD_SPMM_CASE
+  return vec ? launch<64, VEC, TI, TO>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s)
+             : launch<64, 1, TI, TO>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+}
+
 }  // namespace
 
-int spmm_f32(const gad_graph* g, const float* T, int64_t ldt, float* out, int64_t ldo, int width, int epi,
-             const float* aux, int64_t ldaux, hipStream_t s) {
+int spmm(const gad_graph* g, const void* T, int64_t ldt, gad_dtype t_in, void* out, int64_t ldo, gad_dtype t_out,
+         int width, int epi, const void* aux, int64_t ldaux, hipStream_t s) {
   if (g->n == 0 || width == 0) return GAD_OK;
-  const bool vec = (ldt % 4 == 0) && ((reinterpret_cast<uintptr_t>(T) & 15u) == 0);
-  if (vec) {
-    const int lanes = (width + 3) / 4;
-    if (lanes <= 4) return launch<4, 4>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
-    if (lanes <= 8) return launch<8, 4>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
-    if (lanes <= 16) return launch<16, 4>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
-    if (lanes <= 32) return launch<32, 4>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
-    return launch<64, 4>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
-  }
-  if (width <= 4) return launch<4, 1>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
-  if (width <= 8) return launch<8, 1>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
-  if (width <= 16) return launch<16, 1>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
-  if (width <= 32) return launch<32, 1>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
-  return launch<64, 1>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+  if (t_in == GAD_F32 && t_out == GAD_F32)
+    return spmm_typed<float, float>(g, (const float*)T, ldt, (float*)out, ldo, width, epi, (const float*)aux, ldaux, s);
+  if (t_in == GAD_BF16 && t_out == GAD_BF16)
+    return spmm_typed<bf16_t, bf16_t>(g, (const bf16_t*)T, ldt, (bf16_t*)out, ldo, width, epi, (const bf16_t*)aux, ldaux, s);
+  if (t_in == GAD_BF16 && t_out == GAD_F32)
+    return spmm_typed<bf16_t, float>(g, (const bf16_t*)T, ldt, (float*)out, ldo, width, epi, (const bf16_t*)aux, ldaux, s);
+  return set_error(GAD_ERR_UNSUPPORTED, "SpMM from float32 storage to bfloat16 storage is not implemented");
 }
 
 }  // namespace gad

@@ -14,7 +14,14 @@ from paper_2110_02987_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-TOL = 1e-4
+TOL = 1e-4          # float32 storage
+TOL_BF16 = 2e-2     # bfloat16 storage of features / activations, float32 accumulation
+
+
+def bf16_dev(x32):
+    """float32 array -> (device bfloat16 tensor rounded to nearest even, the same values widened back to float32)."""
+    bits = wl.to_bf16_rne(x32)
+    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda(), wl.bf16_to_f32(bits)
 
 
 @pytest.fixture(scope="module")
@@ -154,28 +161,28 @@ def test_spmm_star_and_isolated(gad):
 
 # ------------------------------------------------------------------------------------------ forward / backward
 
-def run_gpu_step(gad, g, X, Ws, y, mask, c, dims):
+def run_gpu_step(gad, g, X, Ws, y, mask, c, dims, dtype=0):
     """One forward + backward through the C ABI.  Returns logits, loss, dW, hidden activations H_1..H_{L-1}
     and the per-node gradients G_1..G_L."""
     L = len(dims) - 1
-    ws = gad.alloc_workspace(g, dims)
-    Xd, Wd = dev(X), [dev(w) for w in Ws]
+    ws = gad.alloc_workspace(g, dims, dtype)
+    Xd, Wd = (X if torch.is_tensor(X) else dev(X)), [dev(w) for w in Ws]
     logits = torch.empty((g.n, dims[-1]), device="cuda")
     loss = torch.zeros(1, dtype=torch.float64, device="cuda")
     dW = [torch.full_like(w, float("nan")) for w in Wd]
     Gout = [torch.full((g.n, dims[l + 1]), float("nan"), device="cuda") for l in range(L)]
-    gad.gcn_forward(g, Xd, dims, Wd, dev(y), None if mask is None else dev(mask), c, ws, logits, loss)
+    gad.gcn_forward(g, Xd, dims, Wd, dev(y), None if mask is None else dev(mask), c, ws, logits, loss, dtype)
     Hs = []
     for l in range(1, L):
         h = torch.empty((g.n, dims[l]), device="cuda")
-        gad.gcn_activation(g, ws, dims, l, h)
+        gad.gcn_activation(g, ws, dims, l, h, dtype)
         Hs.append(h.cpu().numpy())
-    gad.gcn_backward(g, Xd, dims, Wd, ws, dW, Gout)
+    gad.gcn_backward(g, Xd, dims, Wd, ws, dW, Gout, dtype)
     torch.cuda.synchronize()
     return logits.cpu().numpy(), loss.item(), [d.cpu().numpy() for d in dW], Hs, [t.cpu().numpy() for t in Gout]
 
 
-def relu_decisions(f, Ws, Hs_gpu):
+def relu_decisions(f, Ws, Hs_gpu, band=1e-5):
     """ReLU decisions for the oracle's backward: its own [P_l > 0], except where |P_l| is below float32
     rounding of the sum that forms it -- there the decision is the kernel's (read off its activation).
     Returns the decisions and the number of entries taken from the kernel."""
@@ -186,27 +193,34 @@ def relu_decisions(f, Ws, Hs_gpu):
         differ = on != (h > 0)
         if differ.any():
             bound = np.abs(f["AH"][l]) @ np.abs(np.asarray(Ws[l], dtype=np.float64))    # sum of |terms| of P_l
-            assert np.all(np.abs(P[differ]) <= 1e-5 * bound[differ]), "activation sign differs beyond rounding"
+            assert np.all(np.abs(P[differ]) <= band * bound[differ]), "activation sign differs beyond rounding"
             on = np.where(differ, h > 0, on)
             taken += int(differ.sum())
         out.append(on)
     return out, taken
 
 
-def check_step(gad, g, ref, X, Ws, y, mask, c, dims):
-    logits, loss, dW, Hs, Gs = run_gpu_step(gad, g, X, Ws, y, mask, c, dims)
+def check_step(gad, g, ref, X, Ws, y, mask, c, dims, bf16=False):
+    """bf16: X is rounded to bfloat16 for both sides; the oracle then computes in float64 from those values."""
+    tol = TOL_BF16 if bf16 else TOL
+    if bf16:
+        Xd, X = bf16_dev(X)
+    else:
+        Xd = X
+    logits, loss, dW, Hs, Gs = run_gpu_step(gad, g, Xd, Ws, y, mask, c, dims, 1 if bf16 else 0)
     m = np.ones(g.n, dtype=np.uint8) if mask is None else mask
     f = T1.forward(ref, X, Ws, y, m, c)
-    assert rel_err(logits, f["Z"]) < TOL
-    assert abs(loss - f["loss"]) <= TOL * abs(f["loss"])
+    assert rel_err(logits, f["Z"]) < tol
+    assert abs(loss - f["loss"]) <= tol * abs(f["loss"])
     for l, h in enumerate(Hs):
-        assert rel_err(h, f["H"][l + 1]) < TOL, f"H[{l + 1}]"
-    relu_on, taken = relu_decisions(f, Ws, Hs)
-    assert taken <= 1e-6 * sum(h.size for h in Hs) + 2
+        assert rel_err(h, f["H"][l + 1]) < tol, f"H[{l + 1}]"
+    # ReLU decisions inside the rounding band of the storage type are the kernel's (see relu_decisions)
+    relu_on, taken = relu_decisions(f, Ws, Hs, band=1e-2 if bf16 else 1e-5)
+    assert taken <= (3e-2 if bf16 else 1e-6) * sum(h.size for h in Hs) + 2
     d_ref, G_ref = T1.backward(ref, Ws, f, y, m, c, relu_on=relu_on)
     for l in range(len(dW)):
-        assert rel_err(Gs[l], G_ref[l]) < TOL, f"G[{l}]"
-        assert rel_err(dW[l], d_ref[l]) < TOL, f"dW[{l}]"
+        assert rel_err(Gs[l], G_ref[l]) < tol, f"G[{l}]"
+        assert rel_err(dW[l], d_ref[l]) < tol, f"dW[{l}]"
     return f
 
 
@@ -222,6 +236,33 @@ def test_gcn_step_matches_oracle(gad, name, dims):
     y = wl.make_labels(cfg.n, dims[-1])
     mask = wl.make_mask(cfg)
     check_step(gad, g, ref, X, Ws, y, mask, 1.0 / mask.sum(), dims)
+
+
+@pytest.mark.parametrize("name,dims", [("rmat16", None), ("products_small", (100, 72, 33, 7)), ("tiny", (128, 64, 16)),
+                                       ("tiny", (20, 24, 9))])
+def test_gcn_step_bf16_matches_oracle(gad, name, dims):
+    """bfloat16 storage of features and activations, float32 accumulation, float32 weights (fifth workload's type)."""
+    cfg = wl.CONFIGS[name]
+    dims = tuple(dims or cfg.dims)
+    g, ref = build_both(gad, wl.make_graph(cfg))
+    X = wl.make_features(cfg.n, dims[0])
+    Ws = wl.make_weights(dims)
+    y = wl.make_labels(cfg.n, dims[-1])
+    mask = wl.make_mask(cfg)
+    check_step(gad, g, ref, X, Ws, y, mask, 1.0 / mask.sum(), dims, bf16=True)
+
+
+@pytest.mark.parametrize("width,ld", [(8, 8), (47, 47), (47, 48), (100, 104), (128, 128), (512, 512), (600, 608)])
+def test_spmm_bf16(gad, width, ld):
+    cfg = wl.CONFIGS["products_small"]
+    g, ref = build_both(gad, wl.make_graph(cfg))
+    Td, T = bf16_dev(np.random.default_rng(width).standard_normal((cfg.n, ld)).astype(np.float32))
+    out = torch.zeros((cfg.n, ld), dtype=torch.bfloat16, device="cuda")
+    gad.spmm(g, Td, out, width, dtype=1)
+    exp = T1.spmm(ref, T[:, :width].astype(np.float64))
+    got = out.float().cpu().numpy()
+    assert rel_err(got[:, :width], exp) < 4e-3          # one rounding of the output to bfloat16 (2^-9 relative)
+    assert np.all(got[:, width:] == 0)
 
 
 def test_gcn_step_sum_loss_no_mask_and_dense_oracle(gad):
