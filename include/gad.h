@@ -157,6 +157,29 @@ int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtyp
 int gad_weighted_consensus(const float* const* bufs, int K, const double* zeta, int64_t n_elems, float* out,
                            void* hip_stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * 6. Consensus with parameter update, and one synchronous training round (Algorithm 2, the steps after the
+ *    per-processor loop; Eq. 15 followed by Eq. 16, read as plain SGD:  W <- W - eta * grad_hat).
+ *
+ * gad_consensus_update:  params[e] <- params[e] - eta * sum_k (zeta_k / sum_j zeta_j) * grads[k][e];
+ *   the averaged gradient is also written to avg_out when avg_out != NULL.  grads: host array of K device
+ *   pointers to float32[n_elems]; params must not alias any of them.  Errors as gad_weighted_consensus.
+ *
+ * gad_train_round: the K subgraphs play the K processors of Algorithm 2 on one device.  All of them see the same
+ *   parameters (one flat float32 buffer `params` holding W_1 .. W_L back to back, W_l row-major
+ *   [dims[l-1] x dims[l]]); for k = 0..K-1 a forward and a backward on graphs[k] fill gradient copy k
+ *   (grads + k * n_params, same layout), then gad_consensus_update is applied with zeta (host, K doubles) and eta.
+ *   X, labels, masks, workspaces: host arrays of K device pointers (masks or masks[k] may be NULL);
+ *   loss_scales, workspace_bytes: host arrays of K values; losses: device double[K] or NULL.
+ *   Nothing is launched if the weights are invalid. */
+int gad_consensus_update(const float* const* grads, int K, const double* zeta, int64_t n_elems, float eta,
+                         float* params, float* avg_out, void* hip_stream);
+
+int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X, gad_dtype dtype, int L,
+                    const int32_t* dims, float* params, const int32_t* const* labels, const uint8_t* const* masks,
+                    const float* loss_scales, void* const* workspaces, const size_t* workspace_bytes, float* grads,
+                    const double* zeta, float eta, double* losses, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -167,3 +167,22 @@ def weighted_consensus(bufs, zetas):
     for wi, b in zip(w, bufs):
         out += wi * np.asarray(b, dtype=np.float64)
     return out
+
+
+def train_round(graphs, Xs, Ws, labels, masks, cs, zetas, eta):
+    """One synchronous round of Algorithm 2 with the K subgraphs as the K processors: every processor runs
+    forward + backward with the same parameters (Eq. 7-10), the gradients are averaged with the importance
+    weights (Eq. 15) and every processor applies W <- W - eta * grad_hat (Eq. 16 read as plain SGD).
+    Returns (new weights, per-subgraph losses, averaged gradient)."""
+    grads, losses = [], []
+    for g, X, y, m, c in zip(graphs, Xs, labels, masks, cs):
+        f = forward(g, X, Ws, y, m, c)
+        dW, _ = backward(g, Ws, f, y, m, c)
+        grads.append(dW)
+        losses.append(f["loss"])
+    new_W, avg = [], []
+    for l in range(len(Ws)):
+        g_hat = weighted_consensus([gk[l] for gk in grads], zetas)
+        avg.append(g_hat)
+        new_W.append(np.asarray(Ws[l], dtype=np.float64) - eta * g_hat)
+    return new_W, losses, avg

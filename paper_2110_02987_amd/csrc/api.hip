@@ -325,9 +325,9 @@ int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtyp
   return subgraph_variance(g, V, F, dtype, beta, out3, per_node_out, static_cast<hipStream_t>(hip_stream));
 }
 
-int gad_weighted_consensus(const float* const* bufs, int K, const double* zeta, int64_t n_elems, float* out,
-                           void* hip_stream) {
-  if (!bufs || !zeta || !out) return set_error(GAD_ERR_NULL, "bufs, zeta or out is NULL");
+// Validates the importance weights and forms zeta_k / sum_j zeta_j in float64.
+static int consensus_weights(const float* const* bufs, int K, const double* zeta, int64_t n_elems, double* w) {
+  if (!bufs || !zeta) return set_error(GAD_ERR_NULL, "bufs or zeta is NULL");
   if (K < 1 || K > kMaxConsensus) return set_error(GAD_ERR_SHAPE, "K = %d outside [1, %d]", K, kMaxConsensus);
   if (n_elems < 0) return set_error(GAD_ERR_SHAPE, "n_elems is negative");
   double sum = 0.0;
@@ -337,9 +337,63 @@ int gad_weighted_consensus(const float* const* bufs, int K, const double* zeta, 
     sum += zeta[k];
   }
   if (!(sum > 0.0) || !isfinite(sum)) return set_error(GAD_ERR_WEIGHTS, "the weights sum to zero (or overflow)");
-  double w[kMaxConsensus];
   for (int k = 0; k < K; ++k) w[k] = zeta[k] / sum;
+  return GAD_OK;
+}
+
+int gad_weighted_consensus(const float* const* bufs, int K, const double* zeta, int64_t n_elems, float* out,
+                           void* hip_stream) {
+  if (!out) return set_error(GAD_ERR_NULL, "out is NULL");
+  double w[kMaxConsensus];
+  int st = consensus_weights(bufs, K, zeta, n_elems, w);
+  if (st != GAD_OK) return st;
   return weighted_consensus(bufs, K, w, n_elems, out, static_cast<hipStream_t>(hip_stream));
+}
+
+int gad_consensus_update(const float* const* grads, int K, const double* zeta, int64_t n_elems, float eta,
+                         float* params, float* avg_out, void* hip_stream) {
+  if (!params) return set_error(GAD_ERR_NULL, "params is NULL");
+  if (!isfinite(eta)) return set_error(GAD_ERR_SHAPE, "eta is not finite");
+  double w[kMaxConsensus];
+  int st = consensus_weights(grads, K, zeta, n_elems, w);
+  if (st != GAD_OK) return st;
+  for (int k = 0; k < K; ++k)
+    if (grads[k] == params) return set_error(GAD_ERR_SHAPE, "params must not alias a gradient buffer");
+  return consensus_update(grads, K, w, n_elems, eta, params, avg_out, static_cast<hipStream_t>(hip_stream));
+}
+
+int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X, gad_dtype dtype, int L,
+                    const int32_t* dims, float* params, const int32_t* const* labels, const uint8_t* const* masks,
+                    const float* loss_scales, void* const* workspaces, const size_t* workspace_bytes, float* grads,
+                    const double* zeta, float eta, double* losses, void* hip_stream) {
+  if (K < 1 || K > kMaxConsensus) return set_error(GAD_ERR_SHAPE, "K = %d outside [1, %d]", K, kMaxConsensus);
+  if (!graphs || !X || !dims || !params || !labels || !loss_scales || !workspaces || !workspace_bytes || !grads || !zeta)
+    return set_error(GAD_ERR_NULL, "a required argument is NULL");
+  if (L < 1 || L > kMaxLayers) return set_error(GAD_ERR_SHAPE, "L = %d outside [1, %d]", L, kMaxLayers);
+  int64_t off[kMaxLayers + 1];
+  off[0] = 0;
+  for (int l = 0; l < L; ++l) {
+    if (dims[l] < 1 || dims[l + 1] < 1) return set_error(GAD_ERR_SHAPE, "dims must be positive");
+    off[l + 1] = off[l] + (int64_t)dims[l] * dims[l + 1];
+  }
+  const int64_t P = off[L];
+  const float* W[kMaxLayers];
+  for (int l = 0; l < L; ++l) W[l] = params + off[l];
+  const float* gptr[kMaxConsensus];
+  double w[kMaxConsensus];
+  for (int k = 0; k < K; ++k) gptr[k] = grads + (int64_t)k * P;
+  int st = consensus_weights(gptr, K, zeta, P, w);           // reject bad weights before any launch
+  if (st != GAD_OK) return st;
+  for (int k = 0; k < K; ++k) {
+    float* dW[kMaxLayers];
+    for (int l = 0; l < L; ++l) dW[l] = grads + (int64_t)k * P + off[l];
+    st = gad_gcn_forward(graphs[k], X[k], dtype, L, dims, W, labels[k], masks ? masks[k] : nullptr, loss_scales[k],
+                         workspaces[k], workspace_bytes[k], nullptr, losses ? losses + k : nullptr, hip_stream);
+    if (st != GAD_OK) return st;
+    st = gad_gcn_backward(graphs[k], X[k], dtype, L, dims, W, workspaces[k], workspace_bytes[k], dW, nullptr, hip_stream);
+    if (st != GAD_OK) return st;
+  }
+  return consensus_update(gptr, K, w, P, eta, params, nullptr, static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"

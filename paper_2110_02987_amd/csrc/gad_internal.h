@@ -92,5 +92,7 @@ size_t variance_scratch_doubles(int64_t n);
 int subgraph_variance(const gad_graph* g, const void* V, int F, gad_dtype dtype, double beta, double* out3,
                       float* per_node, hipStream_t s);
 int weighted_consensus(const float* const* bufs, int K, const double* w, int64_t n, float* out, hipStream_t s);
+int consensus_update(const float* const* bufs, int K, const double* w, int64_t n, float eta, float* params,
+                     float* avg_out, hipStream_t s);
 
 }  // namespace gad

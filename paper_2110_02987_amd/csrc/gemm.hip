@@ -107,7 +107,10 @@ __device__ __forceinline__ void store_acc(const v16f (&acc)[2][2], TC* __restric
     }
 }
 
+constexpr int NP = BK / 16;      // 8-element pieces each thread moves per operand and tile
+
 // ---- NN ----------------------------------------------------------------------------------------
+// grid: x = row tile of C (128 rows), y = column tile (128 columns).
 template <int EPI, typename TA, typename TC>
 __global__ __launch_bounds__(256) void gemm_nn_kernel(const TA* __restrict__ A, int64_t lda,
                                                       const float* __restrict__ B, int64_t ldb, TC* __restrict__ C,
@@ -117,9 +120,6 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const TA* __restrict__ A, 
   const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
   const int64_t row0 = (int64_t)blockIdx.x * BM;
   const int col0 = blockIdx.y * BN;
-  // A: thread -> row t/2, k segment (t%2)*8;  B: thread -> k row t/16, column segment (t%16)*8
-  const int a_i = t >> 1, a_k = (t & 1) * 8;
-  const int b_k = t >> 4, b_j = (t & 15) * 8;
   v16f acc[2][2];
 #pragma unroll
   for (int x = 0; x < 2; ++x)
@@ -128,25 +128,33 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const TA* __restrict__ A, 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-  float ra[8], rb[8];
-  load8<TA>(A, lda, row0 + a_i, M, a_k, K, a_vec, ra);
-  load8<float>(B, ldb, b_k, K, col0 + b_j, N, b_vec, rb);
-  store_transposed(tiles[0].a, a_i, a_k, ra);
-  store_direct(tiles[0].b, b_k, b_j, rb);
+  // piece pi = t + 256 j:  A: row pi / (BK/8), k segment (pi % (BK/8)) * 8;  B: k row pi / 16, column segment (pi % 16) * 8
+  float ra[NP][8], rb[NP][8];
+  auto fetch = [&](int k1) {
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+      const int pi = t + 256 * j;
+      load8<TA>(A, lda, row0 + pi / (BK / 8), M, k1 + (pi % (BK / 8)) * 8, K, a_vec, ra[j]);
+      load8<float>(B, ldb, k1 + pi / 16, K, col0 + (pi % 16) * 8, N, b_vec, rb[j]);
+    }
+  };
+  auto stage = [&](Tile& tile) {
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+      const int pi = t + 256 * j;
+      store_transposed(tile.a, pi / (BK / 8), (pi % (BK / 8)) * 8, ra[j]);
+      store_direct(tile.b, pi / 16, (pi % 16) * 8, rb[j]);
+    }
+  };
+  fetch(0);
+  stage(tiles[0]);
   __syncthreads();
   const int n_kt = (K + BK - 1) / BK;
   for (int kt = 0; kt < n_kt; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < n_kt) {
-      const int k1 = (kt + 1) * BK;
-      load8<TA>(A, lda, row0 + a_i, M, k1 + a_k, K, a_vec, ra);
-      load8<float>(B, ldb, k1 + b_k, K, col0 + b_j, N, b_vec, rb);
-    }
+    if (kt + 1 < n_kt) fetch((kt + 1) * BK);
     mma_tile(tiles[cur], wm, wn, acc);
-    if (kt + 1 < n_kt) {
-      store_transposed(tiles[cur ^ 1].a, a_i, a_k, ra);
-      store_direct(tiles[cur ^ 1].b, b_k, b_j, rb);
-    }
+    if (kt + 1 < n_kt) stage(tiles[cur ^ 1]);
     __syncthreads();
   }
   store_acc<EPI, TC, TA>(acc, C, ldc, row0, col0, M, N, wm, wn, aux, ldaux);
@@ -164,7 +172,6 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const TA* __restrict__ A, 
   const int n0 = (blockIdx.x % tiles_n) * BN;   // output column block (columns of G)
   const int64_t m_begin = (int64_t)blockIdx.y * slab_rows;
   const int64_t m_end = m_begin + slab_rows < M ? m_begin + slab_rows : M;
-  const int l_m = t >> 4, l_c = (t & 15) * 8;   // thread -> reduction row t/16, column segment (t%16)*8
   v16f acc[2][2];
 #pragma unroll
   for (int x = 0; x < 2; ++x)
@@ -173,25 +180,33 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const TA* __restrict__ A, 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-  float ra[8], rb[8];
-  load8<TA>(A, lda, m_begin + l_m, m_end, k0 + l_c, K, a_vec, ra);
-  load8<TA>(G, ldg, m_begin + l_m, m_end, n0 + l_c, N, g_vec, rb);
-  store_direct(tiles[0].a, l_m, l_c, ra);
-  store_direct(tiles[0].b, l_m, l_c, rb);
+  // piece pi = t + 256 j: reduction row pi / 16, column segment (pi % 16) * 8, for both operands
+  float ra[NP][8], rb[NP][8];
+  auto fetch = [&](int64_t m1) {
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+      const int pi = t + 256 * j;
+      load8<TA>(A, lda, m1 + pi / 16, m_end, k0 + (pi % 16) * 8, K, a_vec, ra[j]);
+      load8<TA>(G, ldg, m1 + pi / 16, m_end, n0 + (pi % 16) * 8, N, g_vec, rb[j]);
+    }
+  };
+  auto stage = [&](Tile& tile) {
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+      const int pi = t + 256 * j;
+      store_direct(tile.a, pi / 16, (pi % 16) * 8, ra[j]);
+      store_direct(tile.b, pi / 16, (pi % 16) * 8, rb[j]);
+    }
+  };
+  fetch(m_begin);
+  stage(tiles[0]);
   __syncthreads();
   const int64_t n_mt = (m_end - m_begin + BK - 1) / BK;
   for (int64_t mt = 0; mt < n_mt; ++mt) {
     const int cur = (int)(mt & 1);
-    if (mt + 1 < n_mt) {
-      const int64_t m1 = m_begin + (mt + 1) * BK + l_m;
-      load8<TA>(A, lda, m1, m_end, k0 + l_c, K, a_vec, ra);
-      load8<TA>(G, ldg, m1, m_end, n0 + l_c, N, g_vec, rb);
-    }
+    if (mt + 1 < n_mt) fetch(m_begin + (mt + 1) * BK);
     mma_tile(tiles[cur], wm, wn, acc);
-    if (mt + 1 < n_mt) {
-      store_direct(tiles[cur ^ 1].a, l_m, l_c, ra);
-      store_direct(tiles[cur ^ 1].b, l_m, l_c, rb);
-    }
+    if (mt + 1 < n_mt) stage(tiles[cur ^ 1]);
     __syncthreads();
   }
   float* Pslab = P + (int64_t)blockIdx.y * K * N;

@@ -161,6 +161,18 @@ __global__ __launch_bounds__(256) void consensus_kernel(ConsensusArgs a, int K, 
   out[e] = (float)s;
 }
 
+// Eq. 15 followed by the update of Eq. 16: params <- params - eta * sum_k w_k g_k; the averaged gradient itself goes
+// to avg_out when it is not NULL.
+__global__ __launch_bounds__(256) void consensus_update_kernel(ConsensusArgs a, int K, int64_t n, float eta,
+                                                               float* __restrict__ params, float* avg_out) {
+  const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (e >= n) return;
+  double s = 0.0;
+  for (int k = 0; k < K; ++k) s += a.w[k] * (double)a.buf[k][e];
+  if (avg_out) avg_out[e] = (float)s;
+  params[e] = (float)((double)params[e] - (double)eta * s);
+}
+
 template <typename T>
 int variance_t(const gad_graph* g, const T* V, int F, double beta, double* out3, float* per_node, hipStream_t s) {
   const int64_t n = g->n;
@@ -212,6 +224,19 @@ int weighted_consensus(const float* const* bufs, int K, const double* w, int64_t
     a.w[k] = 0.0;
   }
   consensus_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(a, K, n, out);
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
+}
+
+int consensus_update(const float* const* bufs, int K, const double* w, int64_t n, float eta, float* params,
+                     float* avg_out, hipStream_t s) {
+  if (n == 0) return GAD_OK;
+  ConsensusArgs a;
+  for (int k = 0; k < kMaxConsensus; ++k) {
+    a.buf[k] = k < K ? bufs[k] : nullptr;
+    a.w[k] = k < K ? w[k] : 0.0;
+  }
+  consensus_update_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(a, K, n, eta, params, avg_out);
   GAD_LAUNCH_CHECK();
   return GAD_OK;
 }

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libgad.so")
 F32, BF16 = 0, 1
 SYMBOLS = ["gad_last_error", "gad_build_subgraph", "gad_graph_info", "gad_graph_destroy",
            "gad_gcn_workspace_bytes", "gad_gcn_forward", "gad_gcn_backward", "gad_gcn_activation", "gad_spmm",
-           "gad_subgraph_variance", "gad_weighted_consensus"]
+           "gad_subgraph_variance", "gad_weighted_consensus", "gad_consensus_update", "gad_train_round"]
 
 _lib = None
 _hip = None
@@ -198,3 +198,32 @@ def weighted_consensus(bufs: List[torch.Tensor], zeta: Sequence[float], out: tor
     z = (C.c_double * len(zeta))(*[float(v) for v in zeta])
     _check(lib().gad_weighted_consensus(_ptr_array(bufs), C.c_int(len(bufs)), z, C.c_int64(out.numel()), _ptr(out),
                                         _stream()))
+
+
+def consensus_update(grads: List[torch.Tensor], zeta: Sequence[float], eta: float, params: torch.Tensor,
+                     avg_out: Optional[torch.Tensor] = None) -> None:
+    for b in grads:
+        _dev(b, torch.float32, "grads")
+    _dev(params, torch.float32, "params")
+    z = (C.c_double * len(zeta))(*[float(v) for v in zeta])
+    _check(lib().gad_consensus_update(_ptr_array(grads), C.c_int(len(grads)), z, C.c_int64(params.numel()),
+                                      C.c_float(eta), _ptr(params), _ptr(avg_out), _stream()))
+
+
+def train_round(graphs: List[Graph], X: List[torch.Tensor], dims: Sequence[int], params: torch.Tensor,
+                labels: List[torch.Tensor], masks: Optional[List[Optional[torch.Tensor]]], loss_scales: Sequence[float],
+                workspaces: List[torch.Tensor], grads: torch.Tensor, zeta: Sequence[float], eta: float,
+                losses: Optional[torch.Tensor] = None, dtype: int = F32) -> None:
+    K = len(graphs)
+    _dev(params, torch.float32, "params")
+    _dev(grads, torch.float32, "grads")
+    if grads.numel() < K * params.numel():
+        raise ValueError("grads must hold K * n_params floats")
+    gh = (C.c_void_p * K)(*[g.handle.value for g in graphs])
+    mk = None if masks is None else (C.c_void_p * K)(*[0 if m is None else m.data_ptr() for m in masks])
+    ls = (C.c_float * K)(*[float(v) for v in loss_scales])
+    wb = (C.c_size_t * K)(*[w.numel() for w in workspaces])
+    z = (C.c_double * K)(*[float(v) for v in zeta])
+    _check(lib().gad_train_round(C.c_int(K), gh, _ptr_array(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims),
+                                 _ptr(params), _ptr_array(labels), mk, ls, _ptr_array(workspaces), wb, _ptr(grads), z,
+                                 C.c_float(eta), _ptr(losses), _stream()))

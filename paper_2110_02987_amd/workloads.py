@@ -230,3 +230,10 @@ def to_bf16_rne(x: np.ndarray) -> np.ndarray:
 def bf16_to_f32(b: np.ndarray) -> np.ndarray:
     """Widen bfloat16 bit patterns (uint16) to float32 exactly."""
     return (b.astype(np.uint32) << 16).view(np.float32)
+
+
+def make_planted_labels(X: np.ndarray, n_classes: int, seed: int = 0) -> np.ndarray:
+    """Labels a linear map of the features can explain (argmax of X R for a seeded random R): gives the training
+    loop something to learn.  Input generation only."""
+    R = _rng(seed, "labels", 1).standard_normal((X.shape[1], n_classes)).astype(np.float32)
+    return np.argmax(X @ R, axis=1).astype(np.int32)

@@ -405,3 +405,72 @@ def test_consensus_errors(gad):
     with pytest.raises(gad.GadError) as e:
         gad.weighted_consensus(b * 43, [1.0] * 129, out)
     assert e.value.status == -2
+
+
+# ------------------------------------------------------------------------------------------ training round (Algorithm 2)
+
+def test_consensus_update(gad):
+    rng = np.random.default_rng(9)
+    P, K, eta = 50_001, 5, 0.37
+    grads = [rng.standard_normal(P).astype(np.float32) for _ in range(K)]
+    params = rng.standard_normal(P).astype(np.float32)
+    z = rng.random(K) + 0.1
+    pd, avg = dev(params), torch.empty(P, device="cuda")
+    gad.consensus_update([dev(g) for g in grads], z, eta, pd, avg)
+    g_hat = T1.weighted_consensus(grads, z)
+    assert rel_err(avg.cpu().numpy(), g_hat) < 1e-6
+    assert rel_err(pd.cpu().numpy(), params.astype(np.float64) - eta * g_hat) < 1e-6
+    with pytest.raises(gad.GadError) as e:
+        gad.consensus_update([pd], [1.0], eta, pd)             # params aliasing a gradient
+    assert e.value.status == -2
+    with pytest.raises(gad.GadError) as e:
+        gad.consensus_update([dev(grads[0])], [0.0], eta, pd)
+    assert e.value.status == -6
+
+
+def test_train_rounds_match_oracle(gad):
+    """Five synchronous rounds of Algorithm 2 with four subgraphs as the four processors: forward, backward,
+    weighted consensus (Eq. 15) and update (Eq. 16), against the same loop of the float64 oracle."""
+    dims, K, eta, rounds = (32, 48, 24, 6), 4, 0.5, 5
+    import dataclasses
+    cfgs = [dataclasses.replace(wl.CONFIGS["products_small"], n_local=3000 + 500 * k, n_halo=400, max_degree=1500)
+            for k in range(K)]
+    graphs, refs, Xs, ys, ms, cs = [], [], [], [], [], []
+    for k, cfg in enumerate(cfgs):
+        g, ref = build_both(gad, wl.make_graph(cfg, seed=k))
+        X = wl.make_features(cfg.n, dims[0], seed=k)
+        graphs.append(g); refs.append(ref); Xs.append(X)
+        ys.append(wl.make_planted_labels(X, dims[-1]))
+        ms.append(wl.make_mask(cfg)); cs.append(1.0 / ms[-1].sum())
+    # importance from the library's own variance call on the features (Eq. 14), read back once as at load time
+    zeta = []
+    for g, ref, X in zip(graphs, refs, Xs):
+        out3 = torch.zeros(3, dtype=torch.float64, device="cuda")
+        gad.subgraph_variance(g, dev(X), 1.0, out3)
+        zeta.append(out3[0].item())
+        assert abs(zeta[-1] - T1.zeta(ref, X, 1.0)[0]) <= TOL * zeta[-1]
+    Ws = wl.make_weights(dims)
+    flat = np.concatenate([w.ravel() for w in Ws])
+    params = dev(flat)
+    grads = torch.empty(K * flat.size, device="cuda")
+    losses = torch.zeros(K, dtype=torch.float64, device="cuda")
+    wss = [gad.alloc_workspace(g, dims) for g in graphs]
+    Xd, yd, md = [dev(x) for x in Xs], [dev(y) for y in ys], [dev(m) for m in ms]
+    W_ref = [w.astype(np.float64) for w in Ws]
+    tots = []
+    for r in range(rounds):
+        gad.train_round(graphs, Xd, dims, params, yd, md, cs, wss, grads, zeta, eta, losses)
+        W_ref, l_ref, _ = T1.train_round(refs, Xs, W_ref, ys, ms, cs, zeta, eta)
+        got = losses.cpu().numpy()
+        assert np.all(np.abs(got - l_ref) <= 2e-4 * np.abs(l_ref)), f"round {r}"
+        tots.append(float(np.dot(zeta, got) / np.sum(zeta)))
+    flat_ref = np.concatenate([w.ravel() for w in W_ref])
+    got = params.cpu().numpy().astype(np.float64)
+    assert rel_err(got, flat_ref) < TOL
+    assert rel_err(got - flat, flat_ref - flat) < 2e-3          # the learned change itself, not just the start
+    assert all(b < a for a, b in zip(tots, tots[1:]))          # the importance-weighted loss falls every round
+    # invalid importance: nothing is launched, parameters stay as they are
+    before = params.clone()
+    with pytest.raises(gad.GadError) as e:
+        gad.train_round(graphs, Xd, dims, params, yd, md, cs, wss, grads, [0.0] * K, eta, losses)
+    assert e.value.status == -6 and torch.equal(before, params)

@@ -449,3 +449,66 @@ def test_workload_shapes():
     assert np.array_equal(wl.bf16_to_f32(b), torch.tensor(x).to(torch.bfloat16).float().numpy())
     W = wl.make_weights((100, 256))
     assert np.abs(W[0]).max() <= np.sqrt(6 / 356) and W[0].dtype == np.float32
+
+
+# --------------------------------------------------------------------------- training round (Algorithm 2; Eq. 15, Eq. 16)
+
+def _round_problem(K=3, seed=0):
+    dims = (6, 8, 4)
+    parts = [_random_problem(40 + 7 * k, 150, dims, 100 * seed + k, n_halo=5, n_global=60 + 7 * k) for k in range(K)]
+    graphs = [T1.build(**p[0]) for p in parts]
+    Xs = [p[1] for p in parts]
+    Ws = parts[0][2]
+    ys = [p[3] for p in parts]
+    ms = [p[4] for p in parts]
+    cs = [1.0 / m.sum() for m in ms]
+    return parts, graphs, Xs, Ws, ys, ms, cs, dims
+
+
+def test_train_round_single_processor_is_sgd_step():
+    """K = 1: the round is one plain SGD step; checked against torch.optim.SGD on an autograd model with dense A~."""
+    parts, graphs, Xs, Ws, ys, ms, cs, dims = _round_problem(K=1)
+    eta = 0.3
+    new_W, losses, _ = T1.train_round(graphs, Xs, Ws, ys, ms, cs, [0.7], eta)
+    At = torch.tensor(T0.normalized_adjacency(T0.adjacency_dense(**parts[0][0])))
+    tW = [torch.tensor(w, requires_grad=True) for w in Ws]
+    opt = torch.optim.SGD(tW, lr=eta)
+    H = torch.tensor(Xs[0])
+    for l, w in enumerate(tW):
+        H = At @ H @ w
+        if l < len(tW) - 1:
+            H = torch.relu(H)
+    m = torch.tensor(ms[0].astype(bool))
+    loss = cs[0] * torch.nn.functional.cross_entropy(H[m], torch.tensor(ys[0]).long()[m], reduction="sum")
+    loss.backward()
+    opt.step()
+    assert losses[0] == pytest.approx(loss.item(), rel=1e-12)
+    for a, b in zip(new_W, tW):
+        np.testing.assert_allclose(a, b.detach().numpy(), rtol=1e-10, atol=1e-13)
+
+
+def test_train_round_weighted_consensus_properties():
+    parts, graphs, Xs, Ws, ys, ms, cs, dims = _round_problem(K=3, seed=1)
+    eta = 0.05
+    z = [0.2, 0.5, 0.9]
+    new_W, losses, avg = T1.train_round(graphs, Xs, Ws, ys, ms, cs, z, eta)
+    # literal Eq. 15 / Eq. 16 from the per-subgraph gradients
+    per = []
+    for g, X, y, m, c in zip(graphs, Xs, ys, ms, cs):
+        f = T1.forward(g, X, Ws, y, m, c)
+        per.append(T1.backward(g, Ws, f, y, m, c)[0])
+    for l in range(2):
+        g_hat = sum(z[k] * per[k][l] for k in range(3)) / sum(z)
+        np.testing.assert_allclose(avg[l], g_hat, rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(new_W[l], Ws[l] - eta * g_hat, rtol=1e-12, atol=1e-15)
+    # equal importance: Eq. 11 (plain mean of the gradients)
+    _, _, avg_eq = T1.train_round(graphs, Xs, Ws, ys, ms, cs, [3.0, 3.0, 3.0], eta)
+    for l in range(2):
+        np.testing.assert_allclose(avg_eq[l], np.mean([per[k][l] for k in range(3)], axis=0), rtol=1e-12, atol=1e-15)
+    # small steps along the averaged gradient lower the importance-weighted loss
+    W, prev = Ws, None
+    for _ in range(12):
+        W, losses, _ = T1.train_round(graphs, Xs, W, ys, ms, cs, z, 0.2)
+        tot = sum(zk * lk for zk, lk in zip(z, losses)) / sum(z)
+        assert prev is None or tot < prev
+        prev = tot
