@@ -29,6 +29,8 @@ struct Tile {
 };
 
 // acc[tm][tn] += As[:, 64*wm + 32*tm .. ]^T Bs[:, 64*wn + 32*tn ..]
+// (Reading all fragments of a tile ahead of the MFMAs, or a 32-deep tile at two blocks per CU, both measured
+// slower than this per-k-step form at three blocks per CU.)
 __device__ __forceinline__ void mma_tile(const Tile& t, int wm, int wn, v16f (&acc)[2][2]) {
   const int lane = threadIdx.x & 63;
   const int i = lane & 31, half = lane >> 5;
