@@ -85,11 +85,13 @@ int gad_graph_destroy(gad_graph* g);
 /* ---------------------------------------------------------------------------------------------
  * 2./3. Forward and backward propagation (Section 3.3; Algorithm 2, forward and backward steps).
  *
- * Model: H_0 = X;  P_l = A~ H_{l-1} W_l (Eq. 7);  H_l = ReLU(P_l) for l < L;  Z = P_L (Eq. 8: no bias,
- * no activation after the last layer);  y^ = softmax(Z).  Loss (Eq. 9 read as softmax cross-entropy):
+ * Model: H_0 = X;  P_l = A~ H_{l-1} W_l (Eq. 7);  H_l = sigma(P_l) for l < L;  Z = P_L (Eq. 8: no bias,
+ * no activation after the last layer);  sigma(p) = p for p > 0, negative_slope * p otherwise: ReLU for
+ * negative_slope = 0, LeakyReLU for 0 < negative_slope < 1 (the two activations Eq. 7 names);  y^ = softmax(Z).  Loss (Eq. 9 read as softmax cross-entropy):
  *   loss = loss_scale * sum_{i : mask_i != 0} ( log sum_c exp Z_ic - Z_{i, labels_i} ).
  * Backward (Eq. 10 through the softmax):  G_L = loss_scale * mask_i * (y^ - onehot(labels)),
- *   dW_l = (A~ H_{l-1})^T G_l,   G_{l-1} = (A~ G_l W_l^T) * [P_{l-1} > 0]   (ReLU'(0) = 0).
+ *   dW_l = (A~ H_{l-1})^T G_l,   G_{l-1} = (A~ G_l W_l^T) * sigma'(P_{l-1}),  sigma'(p) = 1 for p > 0, negative_slope
+ *   otherwise (so ReLU'(0) = 0).
  * Per layer the library evaluates A~ (H W) or (A~ H) W, whichever has the narrower sparse product.
  *
  *   X          [n x dims[0]] features, leading dimension dims[0]; float32, or bfloat16 for GAD_BF16.
@@ -104,22 +106,22 @@ int gad_graph_destroy(gad_graph* g);
  *              that receives the per-node gradient G_{l+1} = dLoss/dP_{l+1} (e.g. as node vectors for
  *              gad_subgraph_variance).
  *
- * gad_gcn_backward must follow a gad_gcn_forward on the same graph, workspace, L, dims and dtype
+ * gad_gcn_backward must follow a gad_gcn_forward on the same graph, workspace, L, dims, dtype and negative_slope
  * (else GAD_ERR_STATE); X and W must still hold the values the forward saw.  Rows whose label is
  * outside [0, F_L) contribute nothing (treated as masked). */
 int gad_gcn_workspace_bytes(const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, size_t* bytes);
 
 int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
                     const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
-                    void* workspace, size_t workspace_bytes, float* logits_out, double* loss_out,
-                    void* hip_stream);
+                    float negative_slope, void* workspace, size_t workspace_bytes, float* logits_out,
+                    double* loss_out, void* hip_stream);
 
 int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
-                     const float* const* W, void* workspace, size_t workspace_bytes, float* const* dW,
-                     float* const* G_out, void* hip_stream);
+                     const float* const* W, float negative_slope, void* workspace, size_t workspace_bytes,
+                     float* const* dW, float* const* G_out, void* hip_stream);
 
 /* Copies a saved activation of the last forward on `workspace` into out (float32 [n x dims[layer]], ld
- * dims[layer]):  layer in [1, L-1] gives H_layer = ReLU(P_layer), layer = L gives the logits Z.
+ * dims[layer]):  layer in [1, L-1] gives H_layer = sigma(P_layer), layer = L gives the logits Z.
  * GAD_ERR_STATE if the workspace holds no forward matching (g, L, dims, dtype). */
 int gad_gcn_activation(const gad_graph* g, const void* workspace, size_t workspace_bytes, int L,
                        const int32_t* dims, gad_dtype dtype, int layer, float* out, void* hip_stream);
@@ -177,8 +179,9 @@ int gad_consensus_update(const float* const* grads, int K, const double* zeta, i
 
 int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X, gad_dtype dtype, int L,
                     const int32_t* dims, float* params, const int32_t* const* labels, const uint8_t* const* masks,
-                    const float* loss_scales, void* const* workspaces, const size_t* workspace_bytes, float* grads,
-                    const double* zeta, float eta, double* losses, void* hip_stream);
+                    const float* loss_scales, float negative_slope, void* const* workspaces,
+                    const size_t* workspace_bytes, float* grads, const double* zeta, float eta, double* losses,
+                    void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -101,8 +101,8 @@ def spmm_rows(g: Graph, T32, rows, width=None) -> np.ndarray:
     return out
 
 
-def forward(g: Graph, X, Ws, labels, mask, c=1.0):
-    """Eq. 7-9.  Keeps AH[l] = A~ H_l for the backward."""
+def forward(g: Graph, X, Ws, labels, mask, c=1.0, slope=0.0):
+    """Eq. 7-9.  Keeps AH[l] = A~ H_l for the backward.  sigma = ReLU (slope 0) or LeakyReLU (Eq. 7 names both)."""
     H = [np.asarray(X, dtype=np.float64)]
     AH, P = [], []
     L = len(Ws)
@@ -110,7 +110,7 @@ def forward(g: Graph, X, Ws, labels, mask, c=1.0):
         AH.append(spmm(g, H[l]))
         P.append(AH[l] @ np.asarray(Ws[l], dtype=np.float64))
         if l < L - 1:
-            H.append(np.maximum(P[l], 0.0))
+            H.append(np.where(P[l] > 0, P[l], slope * P[l]))
     Z = P[-1]
     zmax = Z.max(axis=1, keepdims=True)
     e = np.exp(Z - zmax)
@@ -122,7 +122,7 @@ def forward(g: Graph, X, Ws, labels, mask, c=1.0):
     return dict(Z=Z, loss=float(loss), H=H, P=P, AH=AH, yhat=yhat)
 
 
-def backward(g: Graph, Ws, fwd, labels, mask, c=1.0, relu_on=None):
+def backward(g: Graph, Ws, fwd, labels, mask, c=1.0, relu_on=None, slope=0.0):
     """dW_l = (A~ H_{l-1})^T G_l ;  G_{l-1} = (A~ G_l W_l^T) * [P_{l-1} > 0].
 
     relu_on: optional list of boolean arrays (one per hidden layer) replacing the decisions [P_l > 0].
@@ -140,7 +140,7 @@ def backward(g: Graph, Ws, fwd, labels, mask, c=1.0, relu_on=None):
         dW[l] = fwd["AH"][l].T @ G
         if l > 0:
             on = fwd["P"][l - 1] > 0 if relu_on is None else relu_on[l - 1]
-            G = (spmm(g, G) @ np.asarray(Ws[l], dtype=np.float64).T) * on
+            G = (spmm(g, G) @ np.asarray(Ws[l], dtype=np.float64).T) * np.where(on, 1.0, slope)
     return dW, Gs
 
 
@@ -169,15 +169,15 @@ def weighted_consensus(bufs, zetas):
     return out
 
 
-def train_round(graphs, Xs, Ws, labels, masks, cs, zetas, eta):
+def train_round(graphs, Xs, Ws, labels, masks, cs, zetas, eta, slope=0.0):
     """One synchronous round of Algorithm 2 with the K subgraphs as the K processors: every processor runs
     forward + backward with the same parameters (Eq. 7-10), the gradients are averaged with the importance
     weights (Eq. 15) and every processor applies W <- W - eta * grad_hat (Eq. 16 read as plain SGD).
     Returns (new weights, per-subgraph losses, averaged gradient)."""
     grads, losses = [], []
     for g, X, y, m, c in zip(graphs, Xs, labels, masks, cs):
-        f = forward(g, X, Ws, y, m, c)
-        dW, _ = backward(g, Ws, f, y, m, c)
+        f = forward(g, X, Ws, y, m, c, slope)
+        dW, _ = backward(g, Ws, f, y, m, c, slope=slope)
         grads.append(dW)
         losses.append(f["loss"])
     new_W, avg = [], []

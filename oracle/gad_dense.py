@@ -93,7 +93,7 @@ def csr_of(A):
 
 # ----------------------------------------------------------------------------- GCN step
 
-def forward(At, X, Ws, labels, mask, c=1.0):
+def forward(At, X, Ws, labels, mask, c=1.0, slope=0.0):
     """Eq. 7-9.  Returns dict(Z, loss, H=[H_0..H_{L-1}], P=[P_1..P_L], yhat)."""
     H = [np.asarray(X, dtype=np.float64)]
     P = []
@@ -102,7 +102,7 @@ def forward(At, X, Ws, labels, mask, c=1.0):
         p = At @ H[l] @ np.asarray(Ws[l], dtype=np.float64)        # Eq. 7 argument
         P.append(p)
         if l < L - 1:
-            H.append(np.maximum(p, 0.0))                           # sigma = ReLU
+            H.append(np.where(p > 0, p, slope * p))                # sigma = ReLU (slope 0) or LeakyReLU
     Z = P[-1]
     zmax = Z.max(axis=1, keepdims=True)
     e = np.exp(Z - zmax)
@@ -114,7 +114,7 @@ def forward(At, X, Ws, labels, mask, c=1.0):
     return dict(Z=Z, loss=float(loss), H=H, P=P, yhat=yhat)
 
 
-def backward(At, Ws, fwd, labels, mask, c=1.0, relu_on=None):
+def backward(At, Ws, fwd, labels, mask, c=1.0, relu_on=None, slope=0.0):
     """Chain rule of Eq. 7-10.  Returns (dW list, G list with G[l] = dLoss/dP_{l+1}).
 
     relu_on: optional list of boolean arrays (one per hidden layer) replacing the decisions [P_l > 0];
@@ -131,7 +131,7 @@ def backward(At, Ws, fwd, labels, mask, c=1.0, relu_on=None):
         dW[l] = (At @ fwd["H"][l]).T @ G
         if l > 0:
             on = fwd["P"][l - 1] > 0 if relu_on is None else relu_on[l - 1]
-            G = (At.T @ G @ np.asarray(Ws[l], dtype=np.float64).T) * on
+            G = (At.T @ G @ np.asarray(Ws[l], dtype=np.float64).T) * np.where(on, 1.0, slope)
     return dW, Gs
 
 

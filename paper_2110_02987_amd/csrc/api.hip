@@ -92,6 +92,7 @@ struct Saved {
   std::vector<int32_t> dims;
   gad_dtype dtype;
   const void* X;
+  float slope;
 };
 std::mutex g_saved_mu;
 std::unordered_map<const void*, Saved> g_saved;
@@ -111,11 +112,12 @@ int check_common(const gad_graph* g, const void* X, int L, const int32_t* dims, 
 }
 
 // True iff `ws` holds a forward of exactly this problem (X = nullptr: any features).
-bool forward_saved(const gad_graph* g, const void* ws, int L, const int32_t* dims, gad_dtype dtype, const void* X) {
+bool forward_saved(const gad_graph* g, const void* ws, int L, const int32_t* dims, gad_dtype dtype, const void* X,
+                   const float* slope = nullptr) {
   std::lock_guard<std::mutex> lk(g_saved_mu);
   auto it = g_saved.find(ws);
   bool ok = it != g_saved.end() && it->second.g == g && it->second.L == L && it->second.dtype == dtype &&
-            (X == nullptr || it->second.X == X);
+            (X == nullptr || it->second.X == X) && (slope == nullptr || it->second.slope == *slope);
   if (ok)
     for (int l = 0; l <= L; ++l) ok = ok && it->second.dims[l] == dims[l];
   return ok;
@@ -191,7 +193,8 @@ int gad_gcn_workspace_bytes(const gad_graph* g, int L, const int32_t* dims, gad_
 
 int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
                     const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
-                    void* workspace, size_t workspace_bytes, float* logits_out, double* loss_out, void* hip_stream) {
+                    float negative_slope, void* workspace, size_t workspace_bytes, float* logits_out,
+                    double* loss_out, void* hip_stream) {
   Plan p;
   int st = make_plan(g, L, dims, dtype, &p);
   if (st != GAD_OK) return st;
@@ -199,6 +202,8 @@ int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, c
   if (st != GAD_OK) return st;
   if (!labels) return set_error(GAD_ERR_NULL, "labels is NULL");
   if (!isfinite(loss_scale)) return set_error(GAD_ERR_SHAPE, "loss_scale is not finite");
+  if (!(negative_slope >= 0.f && negative_slope < 1.f))
+    return set_error(GAD_ERR_SHAPE, "negative_slope must lie in [0, 1)");
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int64_t n = g->n;
 
@@ -206,23 +211,24 @@ int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, c
   int64_t ldh = dims[0];
   for (int l = 0; l < L; ++l) {
     const bool last = l == L - 1;
-    const int epi = last ? EPI_NONE : EPI_RELU;
+    Epi act;                                             // sigma of Eq. 7 on every layer but the last
+    act.kind = last ? EPI_NONE : EPI_RELU;
+    act.slope = negative_slope;
+    const Epi none;
     const gad_dtype t_dst = last ? GAD_F32 : dtype;      // the logits are kept in float32
     void* dst = at(workspace, p.act[l + 1]);
     const int64_t ldd = pad_ld(dims[l + 1]);
     if (p.agg_first[l]) {
       void* m = at(workspace, p.agg[l]);
       const int64_t ldm = pad_ld(dims[l]);
-      if ((st = spmm(g, h, ldh, dtype, m, ldm, dtype, dims[l], EPI_NONE, nullptr, 0, s)) != GAD_OK) return st;
-      if ((st = gemm_nn(m, ldm, dtype, W[l], dims[l + 1], dst, ldd, t_dst, n, dims[l + 1], dims[l], epi, nullptr, 0,
-                        s)) != GAD_OK)
+      if ((st = spmm(g, h, ldh, dtype, m, ldm, dtype, dims[l], none, s)) != GAD_OK) return st;
+      if ((st = gemm_nn(m, ldm, dtype, W[l], dims[l + 1], dst, ldd, t_dst, n, dims[l + 1], dims[l], act, s)) != GAD_OK)
         return st;
     } else {
       void* t = at(workspace, p.tmp);
-      if ((st = gemm_nn(h, ldh, dtype, W[l], dims[l + 1], t, ldd, dtype, n, dims[l + 1], dims[l], EPI_NONE, nullptr, 0,
-                        s)) != GAD_OK)
+      if ((st = gemm_nn(h, ldh, dtype, W[l], dims[l + 1], t, ldd, dtype, n, dims[l + 1], dims[l], none, s)) != GAD_OK)
         return st;
-      if ((st = spmm(g, t, ldd, dtype, dst, ldd, t_dst, dims[l + 1], epi, nullptr, 0, s)) != GAD_OK) return st;
+      if ((st = spmm(g, t, ldd, dtype, dst, ldd, t_dst, dims[l + 1], act, s)) != GAD_OK) return st;
     }
     h = dst;
     ldh = ldd;
@@ -236,14 +242,14 @@ int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, c
   if (logits_out && (st = copy_rows(Z, ldz, GAD_F32, logits_out, C, n, C, s)) != GAD_OK) return st;
   {
     std::lock_guard<std::mutex> lk(g_saved_mu);
-    g_saved[workspace] = Saved{g, L, std::vector<int32_t>(dims, dims + L + 1), dtype, X};
+    g_saved[workspace] = Saved{g, L, std::vector<int32_t>(dims, dims + L + 1), dtype, X, negative_slope};
   }
   return GAD_OK;
 }
 
 int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
-                     const float* const* W, void* workspace, size_t workspace_bytes, float* const* dW,
-                     float* const* G_out, void* hip_stream) {
+                     const float* const* W, float negative_slope, void* workspace, size_t workspace_bytes,
+                     float* const* dW, float* const* G_out, void* hip_stream) {
   Plan p;
   int st = make_plan(g, L, dims, dtype, &p);
   if (st != GAD_OK) return st;
@@ -252,8 +258,8 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
   if (!dW) return set_error(GAD_ERR_NULL, "dW is NULL");
   for (int l = 0; l < L; ++l)
     if (!dW[l]) return set_error(GAD_ERR_NULL, "dW[%d] is NULL", l);
-  if (!forward_saved(g, workspace, L, dims, dtype, X))
-    return set_error(GAD_ERR_STATE, "workspace holds no forward pass matching this graph / model / X");
+  if (!forward_saved(g, workspace, L, dims, dtype, X, &negative_slope))
+    return set_error(GAD_ERR_STATE, "workspace holds no forward pass matching this graph / model / X / slope");
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int64_t n = g->n;
   void* gcur = at(workspace, p.g_a);
@@ -267,23 +273,27 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
     const int64_t ldi = pad_ld(fin);         // dM, G_{l-1}, H_l
     const void* hin = l == 0 ? X : at(workspace, p.act[l]);
     const int64_t ldhin = l == 0 ? dims[0] : ldi;
+    const Epi none;
+    Epi dact;                                            // derivative of sigma, decided by the saved activation H_l
+    dact.kind = EPI_MASK;
+    dact.slope = negative_slope;
+    dact.aux = hin;
+    dact.ldaux = ldhin;
     if (G_out && G_out[l] && (st = copy_rows(gcur, ldg, dtype, G_out[l], fout, n, fout, s)) != GAD_OK) return st;
     if (p.agg_first[l]) {
       if ((st = gemm_tn(at(workspace, p.agg[l]), ldi, gcur, ldg, dtype, dW[l], fout, n, fin, fout, tn, s)) != GAD_OK)
         return st;
       if (l > 0) {
         if ((st = transpose_f32(W[l], fin, fout, wt, s)) != GAD_OK) return st;
-        if ((st = gemm_nn(gcur, ldg, dtype, wt, fin, tmp, ldi, dtype, n, fin, fout, EPI_NONE, nullptr, 0, s)) != GAD_OK)
-          return st;
-        if ((st = spmm(g, tmp, ldi, dtype, gnext, ldi, dtype, fin, EPI_MASK, hin, ldhin, s)) != GAD_OK) return st;
+        if ((st = gemm_nn(gcur, ldg, dtype, wt, fin, tmp, ldi, dtype, n, fin, fout, none, s)) != GAD_OK) return st;
+        if ((st = spmm(g, tmp, ldi, dtype, gnext, ldi, dtype, fin, dact, s)) != GAD_OK) return st;
       }
     } else {
-      if ((st = spmm(g, gcur, ldg, dtype, tmp, ldg, dtype, fout, EPI_NONE, nullptr, 0, s)) != GAD_OK) return st;
+      if ((st = spmm(g, gcur, ldg, dtype, tmp, ldg, dtype, fout, none, s)) != GAD_OK) return st;
       if ((st = gemm_tn(hin, ldhin, tmp, ldg, dtype, dW[l], fout, n, fin, fout, tn, s)) != GAD_OK) return st;
       if (l > 0) {
         if ((st = transpose_f32(W[l], fin, fout, wt, s)) != GAD_OK) return st;
-        if ((st = gemm_nn(tmp, ldg, dtype, wt, fin, gnext, ldi, dtype, n, fin, fout, EPI_MASK, hin, ldhin, s)) != GAD_OK)
-          return st;
+        if ((st = gemm_nn(tmp, ldg, dtype, wt, fin, gnext, ldi, dtype, n, fin, fout, dact, s)) != GAD_OK) return st;
       }
     }
     void* t = gcur;
@@ -313,7 +323,7 @@ int gad_spmm(const gad_graph* g, const void* T, int64_t ldt, void* out, int64_t 
   if (width < 1 || ldt < width || ldo < width) return set_error(GAD_ERR_SHAPE, "width < 1 or a leading dimension < width");
   if (T == out) return set_error(GAD_ERR_SHAPE, "out must not alias T");
   if (dtype != GAD_F32 && dtype != GAD_BF16) return set_error(GAD_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
-  return spmm(g, T, ldt, dtype, out, ldo, dtype, width, EPI_NONE, nullptr, 0, static_cast<hipStream_t>(hip_stream));
+  return spmm(g, T, ldt, dtype, out, ldo, dtype, width, Epi(), static_cast<hipStream_t>(hip_stream));
 }
 
 int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta, double* out3,
@@ -364,8 +374,9 @@ int gad_consensus_update(const float* const* grads, int K, const double* zeta, i
 
 int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X, gad_dtype dtype, int L,
                     const int32_t* dims, float* params, const int32_t* const* labels, const uint8_t* const* masks,
-                    const float* loss_scales, void* const* workspaces, const size_t* workspace_bytes, float* grads,
-                    const double* zeta, float eta, double* losses, void* hip_stream) {
+                    const float* loss_scales, float negative_slope, void* const* workspaces,
+                    const size_t* workspace_bytes, float* grads, const double* zeta, float eta, double* losses,
+                    void* hip_stream) {
   if (K < 1 || K > kMaxConsensus) return set_error(GAD_ERR_SHAPE, "K = %d outside [1, %d]", K, kMaxConsensus);
   if (!graphs || !X || !dims || !params || !labels || !loss_scales || !workspaces || !workspace_bytes || !grads || !zeta)
     return set_error(GAD_ERR_NULL, "a required argument is NULL");
@@ -388,9 +399,10 @@ int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X,
     float* dW[kMaxLayers];
     for (int l = 0; l < L; ++l) dW[l] = grads + (int64_t)k * P + off[l];
     st = gad_gcn_forward(graphs[k], X[k], dtype, L, dims, W, labels[k], masks ? masks[k] : nullptr, loss_scales[k],
-                         workspaces[k], workspace_bytes[k], nullptr, losses ? losses + k : nullptr, hip_stream);
+                         negative_slope, workspaces[k], workspace_bytes[k], nullptr, losses ? losses + k : nullptr, hip_stream);
     if (st != GAD_OK) return st;
-    st = gad_gcn_backward(graphs[k], X[k], dtype, L, dims, W, workspaces[k], workspace_bytes[k], dW, nullptr, hip_stream);
+    st = gad_gcn_backward(graphs[k], X[k], dtype, L, dims, W, negative_slope, workspaces[k], workspace_bytes[k], dW,
+                          nullptr, hip_stream);
     if (st != GAD_OK) return st;
   }
   return consensus_update(gptr, K, w, P, eta, params, nullptr, static_cast<hipStream_t>(hip_stream));

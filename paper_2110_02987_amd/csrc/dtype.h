@@ -48,4 +48,9 @@ __device__ __forceinline__ void load_row_piece(const T* p, float (&r)[V]) {
   }
 }
 
+// sigma(v) and sigma'(.) * v for sigma = ReLU (slope 0) or LeakyReLU (Eq. 7's activation); `on` = pre-activation > 0.
+__device__ __forceinline__ float leaky(float v, bool on, float slope) {
+  return on ? v : (slope == 0.f ? 0.f : slope * v);
+}
+
 }  // namespace gad

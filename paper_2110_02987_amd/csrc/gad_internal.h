@@ -29,8 +29,16 @@ inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 // ---- SpMM epilogues -----------------------------------------------------------------------
 enum Epilogue : int {
   EPI_NONE = 0,
-  EPI_RELU = 1,   // out = max(out, 0)
-  EPI_MASK = 2,   // out = aux > 0 ? out : 0   (aux has the layout of out)
+  EPI_RELU = 1,   // out = out > 0 ? out : slope * out              (ReLU for slope = 0, LeakyReLU otherwise)
+  EPI_MASK = 2,   // out = aux > 0 ? out : slope * out              (its derivative; aux has the layout of out)
+};
+
+// Epilogue of a producing kernel (SpMM or GEMM): kind, negative slope, and the activation that decides the mask.
+struct Epi {
+  int kind = EPI_NONE;
+  float slope = 0.f;
+  const void* aux = nullptr;   // storage type of the kernel's node-matrix input
+  int64_t ldaux = 0;
 };
 
 // Rows longer than this many non-zeros are split into chunks of this size; each chunk is summed by
@@ -70,13 +78,13 @@ namespace gad {
 int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int64_t n_global, const int64_t* local_ids,
                    int64_t n_local, const int64_t* halo_ids, int64_t n_halo, hipStream_t s, gad_graph** out);
 // Node matrices are float32 or bfloat16 (gad_dtype); weights, partial sums and logits are float32.
-// out = A~ T with the epilogue applied; aux (EPI_MASK) has T's storage type.
+// out = A~ T with the epilogue applied; epi.aux (EPI_MASK) has T's storage type.
 int spmm(const gad_graph* g, const void* T, int64_t ldt, gad_dtype t_in, void* out, int64_t ldo, gad_dtype t_out,
-         int width, int epilogue, const void* aux, int64_t ldaux, hipStream_t s);
+         int width, const Epi& epi, hipStream_t s);
 
-// C[M x N] (ldc) = A[M x K] (lda) * B[K x N] (ldb) with the epilogue applied to C; aux has A's storage type.
+// C[M x N] (ldc) = A[M x K] (lda) * B[K x N] (ldb) with the epilogue applied to C; epi.aux has A's storage type.
 int gemm_nn(const void* A, int64_t lda, gad_dtype ta, const float* B, int64_t ldb, void* C, int64_t ldc, gad_dtype tc,
-            int64_t M, int N, int K, int epilogue, const void* aux, int64_t ldaux, hipStream_t s);
+            int64_t M, int N, int K, const Epi& epi, hipStream_t s);
 // C[K x N] (ldc) = A[M x K]^T * G[M x N]; `partials` must hold gemm_tn_partial_floats(M, K, N) floats.
 size_t gemm_tn_partial_floats(int64_t M, int K, int N);
 int gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, gad_dtype t, float* C, int64_t ldc, int64_t M,

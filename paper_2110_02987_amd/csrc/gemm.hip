@@ -88,8 +88,8 @@ __device__ __forceinline__ void store_transposed(float (*dst)[LDS_LD], int i, in
 
 template <int EPI, typename TC, typename TX>
 __device__ __forceinline__ void store_acc(const v16f (&acc)[2][2], TC* __restrict__ C, int64_t ldc, int64_t row0,
-                                          int col0, int64_t M, int N, int wm, int wn, const TX* __restrict__ aux,
-                                          int64_t ldaux) {
+                                          int col0, int64_t M, int N, int wm, int wn, float slope,
+                                          const TX* __restrict__ aux, int64_t ldaux) {
   const int lane = threadIdx.x & 63;
 #pragma unroll
   for (int tm = 0; tm < 2; ++tm)
@@ -101,8 +101,8 @@ __device__ __forceinline__ void store_acc(const v16f (&acc)[2][2], TC* __restric
         const int64_t row = row0 + wm * 64 + tm * 32 + acc_row(r, lane);
         if (row < M && col < N) {
           float v = acc[tm][tn][r];
-          if (EPI == EPI_RELU) v = fmaxf(v, 0.f);
-          if (EPI == EPI_MASK) v = to_f32<TX>(aux[row * ldaux + col]) > 0.f ? v : 0.f;
+          if (EPI == EPI_RELU) v = leaky(v, v > 0.f, slope);
+          if (EPI == EPI_MASK) v = leaky(v, to_f32<TX>(aux[row * ldaux + col]) > 0.f, slope);
           C[row * ldc + col] = from_f32<TC>(v);
         }
       }
@@ -117,7 +117,7 @@ template <int EPI, typename TA, typename TC>
 __global__ __launch_bounds__(256) void gemm_nn_kernel(const TA* __restrict__ A, int64_t lda,
                                                       const float* __restrict__ B, int64_t ldb, TC* __restrict__ C,
                                                       int64_t ldc, int64_t M, int N, int K, bool a_vec, bool b_vec,
-                                                      const TA* __restrict__ aux, int64_t ldaux) {
+                                                      float slope, const TA* __restrict__ aux, int64_t ldaux) {
   __shared__ Tile tiles[2];
   const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
   const int64_t row0 = (int64_t)blockIdx.x * BM;
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const TA* __restrict__ A, 
     if (kt + 1 < n_kt) stage(tiles[cur ^ 1]);
     __syncthreads();
   }
-  store_acc<EPI, TC, TA>(acc, C, ldc, row0, col0, M, N, wm, wn, aux, ldaux);
+  store_acc<EPI, TC, TA>(acc, C, ldc, row0, col0, M, N, wm, wn, slope, aux, ldaux);
 }
 
 // ---- TN ----------------------------------------------------------------------------------------
@@ -212,7 +212,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const TA* __restrict__ A, 
     __syncthreads();
   }
   float* Pslab = P + (int64_t)blockIdx.y * K * N;
-  store_acc<EPI_NONE, float, float>(acc, Pslab, N, k0, n0, K, N, wm, wn, nullptr, 0);
+  store_acc<EPI_NONE, float, float>(acc, Pslab, N, k0, n0, K, N, wm, wn, 0.f, nullptr, 0);
 }
 
 __global__ void reduce_slabs(const float* __restrict__ P, int n_slabs, int64_t elems, int N, float* __restrict__ C,
@@ -253,21 +253,23 @@ void tn_split(int64_t M, int K, int N, int* n_slabs, int64_t* slab_rows) {
 
 template <typename TA, typename TC>
 int gemm_nn_typed(const TA* A, int64_t lda, const float* B, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
-                  int epi, const TA* aux, int64_t ldaux, hipStream_t s) {
+                  const Epi& e, hipStream_t s) {
+  const TA* aux = static_cast<const TA*>(e.aux);
+  const int64_t ldaux = e.ldaux;
   const dim3 grid((unsigned)ceil_div(M, BM), (unsigned)ceil_div(N, BN));
   const bool av = vec_ok(A, lda), bv = vec_ok(B, ldb);
-  switch (epi) {
+  switch (e.kind) {
     case EPI_NONE:
-      gemm_nn_kernel<EPI_NONE, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, aux, ldaux);
+      gemm_nn_kernel<EPI_NONE, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, e.slope, aux, ldaux);
       break;
     case EPI_RELU:
-      gemm_nn_kernel<EPI_RELU, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, aux, ldaux);
+      gemm_nn_kernel<EPI_RELU, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, e.slope, aux, ldaux);
       break;
     case EPI_MASK:
-      gemm_nn_kernel<EPI_MASK, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, aux, ldaux);
+      gemm_nn_kernel<EPI_MASK, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, e.slope, aux, ldaux);
       break;
     default:
-      return set_error(GAD_ERR_UNSUPPORTED, "unknown epilogue %d", epi);
+      return set_error(GAD_ERR_UNSUPPORTED, "unknown epilogue %d", e.kind);
   }
   GAD_LAUNCH_CHECK();
   return GAD_OK;
@@ -293,14 +295,14 @@ int gemm_tn_typed(const TA* A, int64_t lda, const TA* G, int64_t ldg, float* C, 
 }  // namespace
 
 int gemm_nn(const void* A, int64_t lda, gad_dtype ta, const float* B, int64_t ldb, void* C, int64_t ldc, gad_dtype tc,
-            int64_t M, int N, int K, int epi, const void* aux, int64_t ldaux, hipStream_t s) {
+            int64_t M, int N, int K, const Epi& e, hipStream_t s) {
   if (M == 0 || N == 0) return GAD_OK;
   if (ta == GAD_F32 && tc == GAD_F32)
-    return gemm_nn_typed<float, float>((const float*)A, lda, B, ldb, (float*)C, ldc, M, N, K, epi, (const float*)aux, ldaux, s);
+    return gemm_nn_typed<float, float>((const float*)A, lda, B, ldb, (float*)C, ldc, M, N, K, e, s);
   if (ta == GAD_BF16 && tc == GAD_BF16)
-    return gemm_nn_typed<bf16_t, bf16_t>((const bf16_t*)A, lda, B, ldb, (bf16_t*)C, ldc, M, N, K, epi, (const bf16_t*)aux, ldaux, s);
+    return gemm_nn_typed<bf16_t, bf16_t>((const bf16_t*)A, lda, B, ldb, (bf16_t*)C, ldc, M, N, K, e, s);
   if (ta == GAD_BF16 && tc == GAD_F32)
-    return gemm_nn_typed<bf16_t, float>((const bf16_t*)A, lda, B, ldb, (float*)C, ldc, M, N, K, epi, (const bf16_t*)aux, ldaux, s);
+    return gemm_nn_typed<bf16_t, float>((const bf16_t*)A, lda, B, ldb, (float*)C, ldc, M, N, K, e, s);
   return set_error(GAD_ERR_UNSUPPORTED, "GEMM from float32 storage to bfloat16 storage is not implemented");
 }
 

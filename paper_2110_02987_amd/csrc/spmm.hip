@@ -66,9 +66,9 @@ __device__ __forceinline__ void gather_sum(const int32_t* __restrict__ colidx, c
 
 template <typename TI, typename TO>
 __device__ __forceinline__ void store_elem(TO* __restrict__ out, int64_t ldo, int64_t i, int c, float v, int epi,
-                                           const TI* __restrict__ aux, int64_t ldaux) {
-  if (epi == EPI_RELU) v = fmaxf(v, 0.f);
-  if (epi == EPI_MASK) v = to_f32<TI>(aux[i * ldaux + c]) > 0.f ? v : 0.f;
+                                           float slope, const TI* __restrict__ aux, int64_t ldaux) {
+  if (epi == EPI_RELU) v = leaky(v, v > 0.f, slope);
+  if (epi == EPI_MASK) v = leaky(v, to_f32<TI>(aux[i * ldaux + c]) > 0.f, slope);
   out[i * ldo + c] = from_f32<TO>(v);
 }
 
@@ -80,8 +80,8 @@ template <int LPR, int V, typename TI, typename TO>
 __global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
                                                    const float* __restrict__ dinv, const TI* __restrict__ T,
                                                    int64_t ldt, TO* __restrict__ out, int64_t ldo, int width, int col0,
-                                                   int64_t n, int epi, const TI* __restrict__ aux, int64_t ldaux,
-                                                   int chunk_blocks, const int32_t* __restrict__ chunk_row,
+                                                   int64_t n, int epi, float slope, const TI* __restrict__ aux,
+                                                   int64_t ldaux, int chunk_blocks, const int32_t* __restrict__ chunk_row,
                                                    const int32_t* __restrict__ chunk_begin, int n_chunks,
                                                    float* __restrict__ partial) {
   const int lane = threadIdx.x & 63;
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ r
     const float di = dinv[i];
 #pragma unroll
     for (int k = 0; k < V; ++k)
-      if (c + k < width) store_elem<TI, TO>(out, ldo, i, c + k, di * acc[k], epi, aux, ldaux);
+      if (c + k < width) store_elem<TI, TO>(out, ldo, i, c + k, di * acc[k], epi, slope, aux, ldaux);
   }
 }
 
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void spmm_long_reduce(const int64_t* __restric
                                                         const int32_t* __restrict__ long_row,
                                                         const int32_t* __restrict__ long_first,
                                                         const float* __restrict__ partial, int col0, int ncols,
-                                                        TO* __restrict__ out, int64_t ldo, int epi,
+                                                        TO* __restrict__ out, int64_t ldo, int epi, float slope,
                                                         const TI* __restrict__ aux, int64_t ldaux) {
   const int slot = blockIdx.x;
   const int64_t i = long_row[slot];
@@ -135,13 +135,16 @@ __global__ __launch_bounds__(256) void spmm_long_reduce(const int64_t* __restric
   for (int rel = threadIdx.x; rel < ncols; rel += blockDim.x) {
     float s = 0.f;
     for (int q = 0; q < k; ++q) s += partial[(int64_t)(first + q) * kPartialWidth + rel];
-    store_elem<TI, TO>(out, ldo, i, col0 + rel, di * s, epi, aux, ldaux);
+    store_elem<TI, TO>(out, ldo, i, col0 + rel, di * s, epi, slope, aux, ldaux);
   }
 }
 
 template <int LPR, int V, typename TI, typename TO>
-int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, int width, int epi, const TI* aux,
-           int64_t ldaux, hipStream_t s) {
+int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, int width, const Epi& e, hipStream_t s) {
+  const int epi = e.kind;
+  const float slope = e.slope;
+  const TI* aux = static_cast<const TI*>(e.aux);
+  const int64_t ldaux = e.ldaux;
   constexpr int slab = LPR * V;
   const unsigned row_blocks = (unsigned)ceil_div(g->n, 4);
   const unsigned chunk_blocks = (unsigned)ceil_div(g->n_chunks, 4);
@@ -150,12 +153,13 @@ int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, i
     const int ncols = width - col0 < kPartialWidth ? width - col0 : kPartialWidth;
     const dim3 grid(chunk_blocks + row_blocks, (unsigned)ceil_div(ncols, slab));
     spmm_kernel<LPR, V, TI, TO><<<grid, 256, 0, s>>>(g->rowptr, g->colidx, g->dinv, T, ldt, out, ldo, col0 + ncols, col0,
-                                                     g->n, epi, aux, ldaux, (int)chunk_blocks, g->chunk_row,
+                                                     g->n, epi, slope, aux, ldaux, (int)chunk_blocks, g->chunk_row,
                                                      g->chunk_begin, g->n_chunks, g->partial);
     GAD_LAUNCH_CHECK();
     if (g->n_long > 0) {
       spmm_long_reduce<TI, TO><<<(unsigned)g->n_long, 256, 0, s>>>(g->rowptr, g->dinv, g->long_row, g->long_first,
-                                                                   g->partial, col0, ncols, out, ldo, epi, aux, ldaux);
+                                                                   g->partial, col0, ncols, out, ldo, epi, slope, aux,
+                                                                   ldaux);
       GAD_LAUNCH_CHECK();
     }
   }
@@ -163,35 +167,35 @@ int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, i
 }
 
 template <typename TI, typename TO>
-int spmm_typed(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, int width, int epi, const TI* aux,
-               int64_t ldaux, hipStream_t s) {
+int spmm_typed(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, int width, const Epi& e,
+               hipStream_t s) {
   constexpr int VEC = 16 / (int)sizeof(TI);      // elements per 16-byte load
   const bool vec = (ldt % VEC == 0) && ((reinterpret_cast<uintptr_t>(T) & 15u) == 0);
   const int lanes = vec ? (width + VEC - 1) / VEC : width;
 #define GAD_SPMM_CASE(L)                                                                                   \
   if (lanes <= L)                                                                                          \
-    return vec ? launch<L, VEC, TI, TO>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s)                  \
-               : launch<L, 1, TI, TO>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+    return vec ? launch<L, VEC, TI, TO>(g, T, ldt, out, ldo, width, e, s)                  \
+               : launch<L, 1, TI, TO>(g, T, ldt, out, ldo, width, e, s);
   GAD_SPMM_CASE(4)
   GAD_SPMM_CASE(8)
   GAD_SPMM_CASE(16)
   GAD_SPMM_CASE(32)
 #undef GAD_SPMM_CASE
-  return vec ? launch<64, VEC, TI, TO>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s)
-             : launch<64, 1, TI, TO>(g, T, ldt, out, ldo, width, epi, aux, ldaux, s);
+  return vec ? launch<64, VEC, TI, TO>(g, T, ldt, out, ldo, width, e, s)
+             : launch<64, 1, TI, TO>(g, T, ldt, out, ldo, width, e, s);
 }
 
 }  // namespace
 
 int spmm(const gad_graph* g, const void* T, int64_t ldt, gad_dtype t_in, void* out, int64_t ldo, gad_dtype t_out,
-         int width, int epi, const void* aux, int64_t ldaux, hipStream_t s) {
+         int width, const Epi& e, hipStream_t s) {
   if (g->n == 0 || width == 0) return GAD_OK;
   if (t_in == GAD_F32 && t_out == GAD_F32)
-    return spmm_typed<float, float>(g, (const float*)T, ldt, (float*)out, ldo, width, epi, (const float*)aux, ldaux, s);
+    return spmm_typed<float, float>(g, (const float*)T, ldt, (float*)out, ldo, width, e, s);
   if (t_in == GAD_BF16 && t_out == GAD_BF16)
-    return spmm_typed<bf16_t, bf16_t>(g, (const bf16_t*)T, ldt, (bf16_t*)out, ldo, width, epi, (const bf16_t*)aux, ldaux, s);
+    return spmm_typed<bf16_t, bf16_t>(g, (const bf16_t*)T, ldt, (bf16_t*)out, ldo, width, e, s);
   if (t_in == GAD_BF16 && t_out == GAD_F32)
-    return spmm_typed<bf16_t, float>(g, (const bf16_t*)T, ldt, (float*)out, ldo, width, epi, (const bf16_t*)aux, ldaux, s);
+    return spmm_typed<bf16_t, float>(g, (const bf16_t*)T, ldt, (float*)out, ldo, width, e, s);
   return set_error(GAD_ERR_UNSUPPORTED, "SpMM from float32 storage to bfloat16 storage is not implemented");
 }
 

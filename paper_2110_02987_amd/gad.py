@@ -142,7 +142,7 @@ def alloc_workspace(g: Graph, dims: Sequence[int], dtype: int = F32) -> torch.Te
 def gcn_forward(g: Graph, X: torch.Tensor, dims: Sequence[int], W: List[torch.Tensor], labels: torch.Tensor,
                 mask: Optional[torch.Tensor], loss_scale: float, workspace: torch.Tensor,
                 logits_out: Optional[torch.Tensor] = None, loss_out: Optional[torch.Tensor] = None,
-                dtype: int = F32) -> None:
+                dtype: int = F32, negative_slope: float = 0.0) -> None:
     _dev(X, torch.float32 if dtype == F32 else torch.bfloat16, "X")
     _dev(labels, torch.int32, "labels")
     if mask is not None:
@@ -154,19 +154,21 @@ def gcn_forward(g: Graph, X: torch.Tensor, dims: Sequence[int], W: List[torch.Te
     if loss_out is not None:
         _dev(loss_out, torch.float64, "loss_out")
     _check(lib().gad_gcn_forward(g.handle, _ptr(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims), _ptr_array(W),
-                                 _ptr(labels), _ptr(mask), C.c_float(loss_scale), _ptr(workspace),
+                                 _ptr(labels), _ptr(mask), C.c_float(loss_scale), C.c_float(negative_slope), _ptr(workspace),
                                  C.c_size_t(workspace.numel()), _ptr(logits_out), _ptr(loss_out), _stream()))
 
 
 def gcn_backward(g: Graph, X: torch.Tensor, dims: Sequence[int], W: List[torch.Tensor], workspace: torch.Tensor,
-                 dW: List[torch.Tensor], G_out: Optional[List[Optional[torch.Tensor]]] = None, dtype: int = F32) -> None:
+                 dW: List[torch.Tensor], G_out: Optional[List[Optional[torch.Tensor]]] = None, dtype: int = F32,
+                 negative_slope: float = 0.0) -> None:
     for w in dW:
         _dev(w, torch.float32, "dW")
     gp = None
     if G_out is not None:
         gp = (C.c_void_p * len(G_out))(*[0 if t is None else _dev(t, torch.float32, "G_out").data_ptr() for t in G_out])
     _check(lib().gad_gcn_backward(g.handle, _ptr(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims), _ptr_array(W),
-                                  _ptr(workspace), C.c_size_t(workspace.numel()), _ptr_array(dW), gp, _stream()))
+                                  C.c_float(negative_slope), _ptr(workspace), C.c_size_t(workspace.numel()), _ptr_array(dW),
+                                  gp, _stream()))
 
 
 def gcn_activation(g: Graph, workspace: torch.Tensor, dims: Sequence[int], layer: int, out: torch.Tensor,
@@ -213,7 +215,7 @@ def consensus_update(grads: List[torch.Tensor], zeta: Sequence[float], eta: floa
 def train_round(graphs: List[Graph], X: List[torch.Tensor], dims: Sequence[int], params: torch.Tensor,
                 labels: List[torch.Tensor], masks: Optional[List[Optional[torch.Tensor]]], loss_scales: Sequence[float],
                 workspaces: List[torch.Tensor], grads: torch.Tensor, zeta: Sequence[float], eta: float,
-                losses: Optional[torch.Tensor] = None, dtype: int = F32) -> None:
+                losses: Optional[torch.Tensor] = None, dtype: int = F32, negative_slope: float = 0.0) -> None:
     K = len(graphs)
     _dev(params, torch.float32, "params")
     _dev(grads, torch.float32, "grads")
@@ -225,5 +227,6 @@ def train_round(graphs: List[Graph], X: List[torch.Tensor], dims: Sequence[int],
     wb = (C.c_size_t * K)(*[w.numel() for w in workspaces])
     z = (C.c_double * K)(*[float(v) for v in zeta])
     _check(lib().gad_train_round(C.c_int(K), gh, _ptr_array(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims),
-                                 _ptr(params), _ptr_array(labels), mk, ls, _ptr_array(workspaces), wb, _ptr(grads), z,
+                                 _ptr(params), _ptr_array(labels), mk, ls, C.c_float(negative_slope), _ptr_array(workspaces), wb,
+                                 _ptr(grads), z,
                                  C.c_float(eta), _ptr(losses), _stream()))

@@ -161,7 +161,7 @@ def test_spmm_star_and_isolated(gad):
 
 # ------------------------------------------------------------------------------------------ forward / backward
 
-def run_gpu_step(gad, g, X, Ws, y, mask, c, dims, dtype=0):
+def run_gpu_step(gad, g, X, Ws, y, mask, c, dims, dtype=0, slope=0.0):
     """One forward + backward through the C ABI.  Returns logits, loss, dW, hidden activations H_1..H_{L-1}
     and the per-node gradients G_1..G_L."""
     L = len(dims) - 1
@@ -171,13 +171,13 @@ def run_gpu_step(gad, g, X, Ws, y, mask, c, dims, dtype=0):
     loss = torch.zeros(1, dtype=torch.float64, device="cuda")
     dW = [torch.full_like(w, float("nan")) for w in Wd]
     Gout = [torch.full((g.n, dims[l + 1]), float("nan"), device="cuda") for l in range(L)]
-    gad.gcn_forward(g, Xd, dims, Wd, dev(y), None if mask is None else dev(mask), c, ws, logits, loss, dtype)
+    gad.gcn_forward(g, Xd, dims, Wd, dev(y), None if mask is None else dev(mask), c, ws, logits, loss, dtype, slope)
     Hs = []
     for l in range(1, L):
         h = torch.empty((g.n, dims[l]), device="cuda")
         gad.gcn_activation(g, ws, dims, l, h, dtype)
         Hs.append(h.cpu().numpy())
-    gad.gcn_backward(g, Xd, dims, Wd, ws, dW, Gout, dtype)
+    gad.gcn_backward(g, Xd, dims, Wd, ws, dW, Gout, dtype, slope)
     torch.cuda.synchronize()
     return logits.cpu().numpy(), loss.item(), [d.cpu().numpy() for d in dW], Hs, [t.cpu().numpy() for t in Gout]
 
@@ -200,16 +200,16 @@ def relu_decisions(f, Ws, Hs_gpu, band=1e-5):
     return out, taken
 
 
-def check_step(gad, g, ref, X, Ws, y, mask, c, dims, bf16=False):
+def check_step(gad, g, ref, X, Ws, y, mask, c, dims, bf16=False, slope=0.0):
     """bf16: X is rounded to bfloat16 for both sides; the oracle then computes in float64 from those values."""
     tol = TOL_BF16 if bf16 else TOL
     if bf16:
         Xd, X = bf16_dev(X)
     else:
         Xd = X
-    logits, loss, dW, Hs, Gs = run_gpu_step(gad, g, Xd, Ws, y, mask, c, dims, 1 if bf16 else 0)
+    logits, loss, dW, Hs, Gs = run_gpu_step(gad, g, Xd, Ws, y, mask, c, dims, 1 if bf16 else 0, slope)
     m = np.ones(g.n, dtype=np.uint8) if mask is None else mask
-    f = T1.forward(ref, X, Ws, y, m, c)
+    f = T1.forward(ref, X, Ws, y, m, c, slope)
     assert rel_err(logits, f["Z"]) < tol
     assert abs(loss - f["loss"]) <= tol * abs(f["loss"])
     for l, h in enumerate(Hs):
@@ -217,7 +217,7 @@ def check_step(gad, g, ref, X, Ws, y, mask, c, dims, bf16=False):
     # ReLU decisions inside the rounding band of the storage type are the kernel's (see relu_decisions)
     relu_on, taken = relu_decisions(f, Ws, Hs, band=1e-2 if bf16 else 1e-5)
     assert taken <= (3e-2 if bf16 else 1e-6) * sum(h.size for h in Hs) + 2
-    d_ref, G_ref = T1.backward(ref, Ws, f, y, m, c, relu_on=relu_on)
+    d_ref, G_ref = T1.backward(ref, Ws, f, y, m, c, relu_on=relu_on, slope=slope)
     for l in range(len(dW)):
         assert rel_err(Gs[l], G_ref[l]) < tol, f"G[{l}]"
         assert rel_err(dW[l], d_ref[l]) < tol, f"dW[{l}]"
@@ -250,6 +250,30 @@ def test_gcn_step_bf16_matches_oracle(gad, name, dims):
     y = wl.make_labels(cfg.n, dims[-1])
     mask = wl.make_mask(cfg)
     check_step(gad, g, ref, X, Ws, y, mask, 1.0 / mask.sum(), dims, bf16=True)
+
+
+@pytest.mark.parametrize("name,dims,bf16", [("products_small", (100, 256, 256, 47), False), ("tiny", (128, 64, 16), False),
+                                            ("products_small", (64, 96, 40, 10), True)])
+def test_gcn_step_leaky_relu(gad, name, dims, bf16):
+    """sigma = LeakyReLU (the other activation Eq. 7 names), negative slope 0.2, both storage types."""
+    cfg = wl.CONFIGS[name]
+    g, ref = build_both(gad, wl.make_graph(cfg))
+    X = wl.make_features(cfg.n, dims[0])
+    Ws = wl.make_weights(dims)
+    y = wl.make_labels(cfg.n, dims[-1])
+    mask = wl.make_mask(cfg)
+    f = check_step(gad, g, ref, X, Ws, y, mask, 1.0 / mask.sum(), dims, bf16=bf16, slope=0.2)
+    assert (f["H"][1] < 0).any()                     # the negative side is really exercised
+    # the slope is part of the saved state: a backward with another slope is refused
+    ws = gad.alloc_workspace(g, dims)
+    Xd, Wd = dev(X), [dev(w) for w in Ws]
+    gad.gcn_forward(g, Xd, dims, Wd, dev(y), dev(mask), 1.0, ws, negative_slope=0.2)
+    with pytest.raises(gad.GadError) as e:
+        gad.gcn_backward(g, Xd, dims, Wd, ws, [torch.empty_like(w) for w in Wd], negative_slope=0.0)
+    assert e.value.status == -9
+    with pytest.raises(gad.GadError) as e:
+        gad.gcn_forward(g, Xd, dims, Wd, dev(y), dev(mask), 1.0, ws, negative_slope=1.5)
+    assert e.value.status == -2
 
 
 @pytest.mark.parametrize("width,ld", [(8, 8), (47, 47), (47, 48), (100, 104), (128, 128), (512, 512), (600, 608)])

@@ -377,6 +377,39 @@ def test_gradients_finite_differences_and_autograd(tier, dims):
         np.testing.assert_allclose(dW[l], tW[l].grad.numpy(), rtol=1e-9, atol=1e-12)
 
 
+@pytest.mark.parametrize("tier", ["T0", "T1"])
+def test_leaky_relu_gradients_autograd(tier):
+    """sigma = LeakyReLU (Eq. 7 names ReLU or LeakyReLU): forward and dW against torch autograd; slope 0 is ReLU."""
+    dims, slope, c = (5, 7, 6, 3), 0.2, 0.41
+    gr, X, Ws, y, mask = _random_problem(45, 150, dims, 77, n_halo=6, n_global=60)
+    At = T0.normalized_adjacency(T0.adjacency_dense(**gr))
+    if tier == "T0":
+        f = T0.forward(At, X, Ws, y, mask, c, slope)
+        dW, _ = T0.backward(At, Ws, f, y, mask, c, slope=slope)
+        f0 = T0.forward(At, X, Ws, y, mask, c, 0.0)
+    else:
+        g = T1.build(**gr)
+        f = T1.forward(g, X, Ws, y, mask, c, slope)
+        dW, _ = T1.backward(g, Ws, f, y, mask, c, slope=slope)
+        f0 = T1.forward(g, X, Ws, y, mask, c, 0.0)
+    tA = torch.tensor(At)
+    tW = [torch.tensor(w, requires_grad=True) for w in Ws]
+    H = torch.tensor(X)
+    for l, w in enumerate(tW):
+        H = tA @ H @ w
+        if l < len(tW) - 1:
+            H = torch.nn.functional.leaky_relu(H, slope)
+    m = torch.tensor(mask.astype(bool))
+    loss = c * torch.nn.functional.cross_entropy(H[m], torch.tensor(y).long()[m], reduction="sum")
+    loss.backward()
+    assert f["loss"] == pytest.approx(loss.item(), rel=1e-12)
+    np.testing.assert_allclose(f["Z"], H.detach().numpy(), rtol=1e-10, atol=1e-13)
+    for l in range(len(Ws)):
+        np.testing.assert_allclose(dW[l], tW[l].grad.numpy(), rtol=1e-9, atol=1e-12)
+    assert (f["H"][1] < 0).any() and f0["loss"] != f["loss"]
+    np.testing.assert_array_equal(f0["H"][1], np.maximum(f0["P"][0], 0))
+
+
 def test_t1_matches_t0_on_tiny_workload():
     """The first synthetic workload (4,096 nodes, 2-layer 128-64-16) end to end, T1 against the dense definition."""
     cfg = wl.CONFIGS["tiny"]
