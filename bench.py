@@ -57,7 +57,16 @@ def main() -> int:
     c = 1.0 / float(mask.sum())
     src, dst = dev(gr["src"]), dev(gr["dst"])
     loc, halo = dev(gr["local_ids"]), dev(gr["halo_ids"])
-    Xd, Wd, yd, md = dev(X), [dev(w) for w in Ws], dev(y), dev(mask)
+    bf16 = cfg.dtype == "bf16"
+    dt = gad.BF16 if bf16 else gad.F32
+    esz = 2 if bf16 else 4                                  # bytes per stored node-matrix element
+    if bf16:                                                # features rounded to bfloat16 once (nearest even)
+        bits = wl.to_bf16_rne(X)
+        Xd = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+        X = wl.bf16_to_f32(bits)                            # what the oracle starts from
+    else:
+        Xd = dev(X)
+    Wd, yd, md = [dev(w) for w in Ws], dev(y), dev(mask)
     K = max(cfg.consensus_k, 1)
     copies = [dev(p) for p in wl.make_param_copies(dims, K)]
     torch.cuda.synchronize()
@@ -68,7 +77,7 @@ def main() -> int:
     build_ms = (time.perf_counter() - t0) * 1e3
     del src, dst
 
-    ws = gad.alloc_workspace(g, dims)
+    ws = gad.alloc_workspace(g, dims, dt)
     loss = torch.zeros(1, dtype=torch.float64, device="cuda")
     dW = [torch.empty_like(w) for w in Wd]
     G_last = torch.empty((g.n, dims[-1]), device="cuda")
@@ -82,9 +91,9 @@ def main() -> int:
     def step(record=None):
         e = [ev() for _ in range(4)] if record is not None else None
         if e: e[0].record()
-        gad.gcn_forward(g, Xd, dims, Wd, yd, md, c, ws, None, loss)
+        gad.gcn_forward(g, Xd, dims, Wd, yd, md, c, ws, None, loss, dt)
         if e: e[1].record()
-        gad.gcn_backward(g, Xd, dims, Wd, ws, dW, G_out)
+        gad.gcn_backward(g, Xd, dims, Wd, ws, dW, G_out, dt)
         if e: e[2].record()
         gad.subgraph_variance(g, G_last, 1.0, out3)
         gad.weighted_consensus(copies, zetas, consensus)
@@ -126,32 +135,33 @@ def main() -> int:
     spmm = {}
     for w in sorted(set(widths)):
         ld = (w + 15) // 16 * 16
-        T = torch.randn((g.n, ld), device="cuda")
+        T = torch.randn((g.n, ld), device="cuda").to(torch.bfloat16 if bf16 else torch.float32)
         O = torch.empty_like(T)
+        sws = gad.spmm_workspace(g, w)
         for _ in range(3):
-            gad.spmm(g, T, O, w)
+            gad.spmm(g, T, O, w, dt, sws)
         a, b = ev(), ev()
         a.record()
         for _ in range(args.kernel_reps):
-            gad.spmm(g, T, O, w)
+            gad.spmm(g, T, O, w, dt, sws)
         b.record()
         torch.cuda.synchronize()
         ms = a.elapsed_time(b) / args.kernel_reps
-        compulsory = 4 * g.nnz + 12 * g.n + 2 * g.n * w * 4
-        gather = g.nnz * (4 + w * 4) + g.n * (12 + w * 4)
+        compulsory = 4 * g.nnz + 12 * g.n + 2 * g.n * w * esz
+        gather = g.nnz * (4 + w * esz) + g.n * (12 + w * esz)
         spmm[w] = dict(ms=ms, launches_per_step=widths.count(w), edges_per_s=g.nnz / (ms * 1e-3),
                        compulsory_GBps=compulsory / ms * 1e-6, gather_model_GBps=gather / ms * 1e-6,
                        compulsory_bytes=compulsory, gather_model_bytes=gather)
-        del T, O
+        del T, O, sws
     dom = max(spmm, key=lambda w: spmm[w]["ms"] * spmm[w]["launches_per_step"])
     # Algorithmic bytes = per-edge and per-row figures of the gather model (4 B index + one w-wide row per edge;
     # rowptr + dinv + one written row per node) x the edges and rows of one launch.  The compulsory model (every
     # array touched once) is reported beside it: the gap between the two is what caches can save.
-    roofline = dict(bound="hbm", kernel=f"spmm_kernel (A~ T at width {dom}, f32)",
+    roofline = dict(bound="hbm", kernel=f"spmm_kernel (A~ T at width {dom}, {cfg.dtype} storage)",
                     achieved=spmm[dom]["gather_model_GBps"], peak=HBM_PEAK_GBPS, unit="GB/s",
                     frac=spmm[dom]["gather_model_GBps"] / HBM_PEAK_GBPS, traffic=None,
                     avg_launch_ms=spmm[dom]["ms"],
-                    model="gather: nnz*(4 + 4w) + n*(12 + 4w) bytes per launch",
+                    model=f"gather: nnz*(4 + {esz}w) + n*(12 + {esz}w) bytes per launch",
                     algorithmic_bytes=spmm[dom]["gather_model_bytes"],
                     compulsory_bytes=spmm[dom]["compulsory_bytes"], compulsory_GBps=spmm[dom]["compulsory_GBps"],
                     compulsory_frac=spmm[dom]["compulsory_GBps"] / HBM_PEAK_GBPS)
@@ -171,7 +181,7 @@ def main() -> int:
 
     out = dict(metric="GCN fwd+bwd edges/s per layer and epoch ms per subgraph; SpMM % of HBM peak",
                value=value, unit="edges/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step,
-               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32", data="synthetic",
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype=cfg.dtype, data="synthetic",
                config=dict(workload=f"{cfg.name}: n={g.n} ({cfg.n_local} local + {cfg.n_halo} halo), nnz={g.nnz}, "
                                     f"GCN {'-'.join(map(str, dims))}, consensus K={K}",
                            n=g.n, nnz=g.nnz, dims=dims),

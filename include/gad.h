@@ -10,8 +10,10 @@
  * Conventions
  *  - Every pointer is a DEVICE pointer unless its comment says "host".
  *  - Matrices are row-major.  "ld" is the leading dimension in elements.
- *  - The caller owns every buffer it passes in, including the workspace.  The library owns only
+ *  - The caller owns every buffer it passes in, including the workspaces.  The library owns only
  *    gad_graph objects (create / destroy pair) and scratch memory that lives inside one call.
+ *    A graph is read-only to every call except gad_subgraph_variance, which uses a reduction buffer inside
+ *    the graph: variance calls on ONE graph from different streams must not overlap.
  *  - All calls enqueue work on `hip_stream` (a hipStream_t, NULL = default stream) and return
  *    without synchronising, except gad_build_subgraph, which synchronises the stream.
  *  - Every function returns a gad_status.  Arguments are validated on the host before any kernel
@@ -127,10 +129,28 @@ int gad_gcn_activation(const gad_graph* g, const void* workspace, size_t workspa
                        const int32_t* dims, gad_dtype dtype, int layer, float* out, void* hip_stream);
 
 /* The normalised sparse product on its own (the A~ H of Eq. 7):  out = A~ T.
- *   T, out   [n x width] row-major with leading dimensions ldt, ldo (>= width); float32 or bfloat16.
+ *   T, out     [n x width] row-major with leading dimensions ldt, ldo (>= width); float32 or bfloat16.
+ *   workspace  device, 16-byte aligned, gad_spmm_workspace_bytes(g, width) bytes (may be NULL when that is 0): the
+ *              partial sums of the rows that are split over several waves.
  * out must not alias T.  Exposed so that the dominant kernel can be tested and timed directly. */
+int gad_spmm_workspace_bytes(const gad_graph* g, int32_t width, size_t* bytes);
 int gad_spmm(const gad_graph* g, const void* T, int64_t ldt, void* out, int64_t ldo, int32_t width,
-             gad_dtype dtype, void* hip_stream);
+             gad_dtype dtype, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The dense contractions of Eq. 7 and of its backward step on their own (the H W of the forward pass, the S W^T
+ * of the input gradient, and the weight gradient A^T G reduced over the nodes), exposed so that the matrix-core
+ * kernels can be tested and timed directly.  Node matrices (A, G, C of gad_gemm_w) are float32, or bfloat16 for
+ * GAD_BF16 (then W is rounded to bfloat16 for the product; accumulation is float32 in both cases).
+ *   gad_gemm_w:  C[M x N] (ldc) = A[M x K] (lda) op(W);  W float32 row-major [w_rows x w_cols];  op(W) = W
+ *                (K = w_rows, N = w_cols), or W^T when transpose_w != 0 (K = w_cols, N = w_rows).
+ *   gad_gemm_tn: C[K x N] (ld N, float32) = A[M x K]^T (lda) G[M x N] (ldg), summed over M in a fixed order.
+ *   workspace:   device, 256-byte aligned, gad_gemm_workspace_bytes(M, K, N) bytes (serves either call).
+ * Errors: K, N outside [1, 4096], M < 0 (M < 1 for gad_gemm_tn), leading dimension below the row length. */
+int gad_gemm_workspace_bytes(int64_t M, int32_t K, int32_t N, size_t* bytes);
+int gad_gemm_w(const void* A, int64_t lda, const float* W, int32_t w_rows, int32_t w_cols, int transpose_w, void* C,
+               int64_t ldc, int64_t M, gad_dtype dtype, void* workspace, size_t workspace_bytes, void* hip_stream);
+int gad_gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, float* C, int64_t M, int32_t K, int32_t N,
+                gad_dtype dtype, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
  * 4. Variance-based subgraph importance (Section 3.4.1, Eq. 14 and its worked example).

@@ -36,9 +36,10 @@ struct Plan {
   size_t agg[kMaxLayers];          // M_l = A~ H_l, kept for dW_l     (agg_first layers)      [n x pad(dims[l])]
   size_t act[kMaxLayers + 1];      // H_l for 1 <= l < L (post-ReLU), act[L] = Z               [n x pad(dims[l])]
   size_t g_a = 0, g_b = 0, tmp = 0;  // [n x max_ld] each
-  size_t wt = 0;                   // W^T scratch
+  size_t wt = 0;                   // scratch copy of one weight matrix (transposed and / or bfloat16)
   size_t tn = 0;                   // slab partials of the weight-gradient GEMM
   size_t sm = 0;                   // softmax block partials (doubles)
+  size_t sp = 0;                   // chunk sums of the long rows of the sparse product
   size_t total = 0;
   int64_t max_ld = 0;
 };
@@ -69,7 +70,7 @@ int make_plan(const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, P
     p->agg[l] = p->agg_first[l] ? take(n * pad_ld(dims[l]) * esz) : 0;
     p->act[l + 1] = take(n * pad_ld(dims[l + 1]) * (l + 1 == L ? sizeof(float) : esz));
     if (p->agg_first[l] && pad_ld(dims[l]) > p->max_ld) p->max_ld = pad_ld(dims[l]);
-    const size_t w = (size_t)dims[l] * dims[l + 1];
+    const size_t w = gemm_w_scratch_bytes(dims[l], dims[l + 1]);
     if (w > max_w) max_w = w;
     const size_t t = gemm_tn_partial_floats(g->n, dims[l], dims[l + 1]);
     if (t > max_tn) max_tn = t;
@@ -78,9 +79,10 @@ int make_plan(const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, P
   p->g_a = take(n * p->max_ld * esz);
   p->g_b = take(n * p->max_ld * esz);
   p->tmp = take(n * p->max_ld * esz);
-  p->wt = take(max_w * sizeof(float));
+  p->wt = take(max_w);
   p->tn = take(max_tn * sizeof(float));
   p->sm = take(softmax_partial_doubles(g->n) * sizeof(double));
+  p->sp = take(spmm_partial_floats(g, (int)p->max_ld) * sizeof(float));
   p->total = off;
   return GAD_OK;
 }
@@ -168,8 +170,8 @@ int gad_graph_info(const gad_graph* g, int64_t* n, int64_t* n_local, int64_t* nn
 
 int gad_graph_destroy(gad_graph* g) {
   if (!g) return GAD_OK;
-  void* ptrs[] = {g->rowptr,    g->colidx,      g->deg,     g->dinv,       g->long_row, g->long_first,
-                  g->chunk_row, g->chunk_begin, g->partial, g->red_scratch};
+  void* ptrs[] = {g->rowptr,    g->colidx,    g->deg,         g->dinv,       g->row_order, g->long_row,
+                  g->long_first, g->chunk_row, g->chunk_begin, g->chunk_perm, g->red_scratch};
   int st = GAD_OK;
   for (void* p : ptrs)
     if (p && hipFree(p) != hipSuccess) st = set_error(GAD_ERR_HIP, "hipFree failed in gad_graph_destroy");
@@ -209,6 +211,8 @@ int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, c
 
   const void* h = X;
   int64_t ldh = dims[0];
+  void* wsc = at(workspace, p.wt);
+  float* psum = static_cast<float*>(at(workspace, p.sp));
   for (int l = 0; l < L; ++l) {
     const bool last = l == L - 1;
     Epi act;                                             // sigma of Eq. 7 on every layer but the last
@@ -221,14 +225,14 @@ int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, c
     if (p.agg_first[l]) {
       void* m = at(workspace, p.agg[l]);
       const int64_t ldm = pad_ld(dims[l]);
-      if ((st = spmm(g, h, ldh, dtype, m, ldm, dtype, dims[l], none, s)) != GAD_OK) return st;
-      if ((st = gemm_nn(m, ldm, dtype, W[l], dims[l + 1], dst, ldd, t_dst, n, dims[l + 1], dims[l], act, s)) != GAD_OK)
+      if ((st = spmm(g, h, ldh, dtype, m, ldm, dtype, dims[l], none, psum, s)) != GAD_OK) return st;
+      if ((st = gemm_w(m, ldm, dtype, W[l], dims[l], dims[l + 1], false, dst, ldd, t_dst, n, act, wsc, s)) != GAD_OK)
         return st;
     } else {
       void* t = at(workspace, p.tmp);
-      if ((st = gemm_nn(h, ldh, dtype, W[l], dims[l + 1], t, ldd, dtype, n, dims[l + 1], dims[l], none, s)) != GAD_OK)
+      if ((st = gemm_w(h, ldh, dtype, W[l], dims[l], dims[l + 1], false, t, ldd, dtype, n, none, wsc, s)) != GAD_OK)
         return st;
-      if ((st = spmm(g, t, ldd, dtype, dst, ldd, t_dst, dims[l + 1], act, s)) != GAD_OK) return st;
+      if ((st = spmm(g, t, ldd, dtype, dst, ldd, t_dst, dims[l + 1], act, psum, s)) != GAD_OK) return st;
     }
     h = dst;
     ldh = ldd;
@@ -265,7 +269,8 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
   void* gcur = at(workspace, p.g_a);
   void* gnext = at(workspace, p.g_b);
   void* tmp = at(workspace, p.tmp);
-  float* wt = static_cast<float*>(at(workspace, p.wt));
+  void* wsc = at(workspace, p.wt);
+  float* psum = static_cast<float*>(at(workspace, p.sp));
   float* tn = static_cast<float*>(at(workspace, p.tn));
   for (int l = L - 1; l >= 0; --l) {
     const int fin = dims[l], fout = dims[l + 1];
@@ -284,16 +289,14 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
       if ((st = gemm_tn(at(workspace, p.agg[l]), ldi, gcur, ldg, dtype, dW[l], fout, n, fin, fout, tn, s)) != GAD_OK)
         return st;
       if (l > 0) {
-        if ((st = transpose_f32(W[l], fin, fout, wt, s)) != GAD_OK) return st;
-        if ((st = gemm_nn(gcur, ldg, dtype, wt, fin, tmp, ldi, dtype, n, fin, fout, none, s)) != GAD_OK) return st;
-        if ((st = spmm(g, tmp, ldi, dtype, gnext, ldi, dtype, fin, dact, s)) != GAD_OK) return st;
+        if ((st = gemm_w(gcur, ldg, dtype, W[l], fin, fout, true, tmp, ldi, dtype, n, none, wsc, s)) != GAD_OK) return st;
+        if ((st = spmm(g, tmp, ldi, dtype, gnext, ldi, dtype, fin, dact, psum, s)) != GAD_OK) return st;
       }
     } else {
-      if ((st = spmm(g, gcur, ldg, dtype, tmp, ldg, dtype, fout, none, s)) != GAD_OK) return st;
+      if ((st = spmm(g, gcur, ldg, dtype, tmp, ldg, dtype, fout, none, psum, s)) != GAD_OK) return st;
       if ((st = gemm_tn(hin, ldhin, tmp, ldg, dtype, dW[l], fout, n, fin, fout, tn, s)) != GAD_OK) return st;
       if (l > 0) {
-        if ((st = transpose_f32(W[l], fin, fout, wt, s)) != GAD_OK) return st;
-        if ((st = gemm_nn(tmp, ldg, dtype, wt, fin, gnext, ldi, dtype, n, fin, fout, dact, s)) != GAD_OK) return st;
+        if ((st = gemm_w(tmp, ldg, dtype, W[l], fin, fout, true, gnext, ldi, dtype, n, dact, wsc, s)) != GAD_OK) return st;
       }
     }
     void* t = gcur;
@@ -317,13 +320,67 @@ int gad_gcn_activation(const gad_graph* g, const void* workspace, size_t workspa
                    dims[layer], g->n, dims[layer], static_cast<hipStream_t>(hip_stream));
 }
 
+int gad_spmm_workspace_bytes(const gad_graph* g, int32_t width, size_t* bytes) {
+  if (!g || !bytes) return set_error(GAD_ERR_NULL, "graph or bytes is NULL");
+  if (width < 1 || width > kMaxWidth) return set_error(GAD_ERR_SHAPE, "width = %d outside [1, %d]", width, kMaxWidth);
+  *bytes = spmm_partial_floats(g, width) * sizeof(float);
+  return GAD_OK;
+}
+
 int gad_spmm(const gad_graph* g, const void* T, int64_t ldt, void* out, int64_t ldo, int32_t width, gad_dtype dtype,
-             void* hip_stream) {
+             void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!g || !T || !out) return set_error(GAD_ERR_NULL, "graph, T or out is NULL");
-  if (width < 1 || ldt < width || ldo < width) return set_error(GAD_ERR_SHAPE, "width < 1 or a leading dimension < width");
+  if (width < 1 || width > kMaxWidth || ldt < width || ldo < width)
+    return set_error(GAD_ERR_SHAPE, "width outside [1, %d] or a leading dimension < width", kMaxWidth);
   if (T == out) return set_error(GAD_ERR_SHAPE, "out must not alias T");
   if (dtype != GAD_F32 && dtype != GAD_BF16) return set_error(GAD_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
-  return spmm(g, T, ldt, dtype, out, ldo, dtype, width, Epi(), static_cast<hipStream_t>(hip_stream));
+  const size_t need = spmm_partial_floats(g, width) * sizeof(float);
+  if (need > 0 && (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0))
+    return set_error(GAD_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed (16-byte aligned)", workspace_bytes, need);
+  return spmm(g, T, ldt, dtype, out, ldo, dtype, width, Epi(), static_cast<float*>(workspace),
+              static_cast<hipStream_t>(hip_stream));
+}
+
+static int gemm_args(int64_t M, int32_t K, int32_t N, gad_dtype dtype) {
+  if (M < 0 || K < 1 || N < 1 || K > kMaxWidth || N > kMaxWidth)
+    return set_error(GAD_ERR_SHAPE, "M < 0, or K / N outside [1, %d]", kMaxWidth);
+  if (dtype != GAD_F32 && dtype != GAD_BF16) return set_error(GAD_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
+  return GAD_OK;
+}
+
+int gad_gemm_workspace_bytes(int64_t M, int32_t K, int32_t N, size_t* bytes) {
+  if (!bytes) return set_error(GAD_ERR_NULL, "bytes is NULL");
+  int st = gemm_args(M, K, N, GAD_F32);
+  if (st != GAD_OK) return st;
+  const size_t w = (gemm_w_scratch_bytes(K, N) + kAlign - 1) / kAlign * kAlign;
+  *bytes = w + gemm_tn_partial_floats(M, K, N) * sizeof(float);
+  return GAD_OK;
+}
+
+int gad_gemm_w(const void* A, int64_t lda, const float* W, int32_t w_rows, int32_t w_cols, int transpose_w, void* C,
+               int64_t ldc, int64_t M, gad_dtype dtype, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int32_t K = transpose_w ? w_cols : w_rows, N = transpose_w ? w_rows : w_cols;
+  int st = gemm_args(M, K, N, dtype);
+  if (st != GAD_OK) return st;
+  if (!A || !W || !C || !workspace) return set_error(GAD_ERR_NULL, "A, W, C or workspace is NULL");
+  if (lda < K || ldc < N) return set_error(GAD_ERR_SHAPE, "a leading dimension is smaller than its row");
+  if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 || workspace_bytes < gemm_w_scratch_bytes(w_rows, w_cols))
+    return set_error(GAD_ERR_WORKSPACE, "workspace too small or not %zu-byte aligned", kAlign);
+  return gemm_w(A, lda, dtype, W, w_rows, w_cols, transpose_w != 0, C, ldc, dtype, M, Epi(), workspace,
+                static_cast<hipStream_t>(hip_stream));
+}
+
+int gad_gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, float* C, int64_t M, int32_t K, int32_t N,
+                gad_dtype dtype, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = gemm_args(M, K, N, dtype);
+  if (st != GAD_OK) return st;
+  if (!A || !G || !C || !workspace) return set_error(GAD_ERR_NULL, "A, G, C or workspace is NULL");
+  if (lda < K || ldg < N) return set_error(GAD_ERR_SHAPE, "a leading dimension is smaller than its row");
+  if (M < 1) return set_error(GAD_ERR_SHAPE, "M must be positive");
+  if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 ||
+      workspace_bytes < gemm_tn_partial_floats(M, K, N) * sizeof(float))
+    return set_error(GAD_ERR_WORKSPACE, "workspace too small or not %zu-byte aligned", kAlign);
+  return gemm_tn(A, lda, G, ldg, dtype, C, N, M, K, N, static_cast<float*>(workspace), static_cast<hipStream_t>(hip_stream));
 }
 
 int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta, double* out3,

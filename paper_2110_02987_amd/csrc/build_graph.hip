@@ -270,34 +270,72 @@ __global__ void degree_norm(const int64_t* __restrict__ rowptr, int64_t n, int32
   dinv[i] = (float)(1.0 / sqrt((double)len));     // d~ = deg + 1 = row length
 }
 
-// counts[0] = number of long rows, counts[1] = number of chunks
-__global__ void count_long_rows(const int64_t* __restrict__ rowptr, int64_t n, uint32_t* __restrict__ counts) {
+// ------------------------------------------------------------------------------------------------
+// SpMM schedule (see gad_graph): classes of short rows, chunks of long rows
+// ------------------------------------------------------------------------------------------------
+// Short rows (1 .. kLongRow non-zeros) fall into classes by ceil(log2(length)), longest class first
+// (class 0); long rows form the last class.  key = class << 32 | row: one stable radix pass on the class
+// byte orders the rows by class and, inside a class, by row id.
+__global__ void classify_rows(const int64_t* __restrict__ rowptr, int64_t n, uint32_t* __restrict__ chunks_of,
+                              uint32_t* __restrict__ is_long, uint64_t* __restrict__ key) {
   int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
   if (i >= n) return;
   const int64_t len = rowptr[i + 1] - rowptr[i];
-  if (len > kLongRow) {
-    atomicAdd(&counts[0], 1u);
-    atomicAdd(&counts[1], (uint32_t)((len + kLongRow - 1) / kLongRow));
+  const bool lng = len > kLongRow;
+  chunks_of[i] = lng ? (uint32_t)((len + kLongRow - 1) / kLongRow) : 0u;
+  is_long[i] = lng ? 1u : 0u;
+  int lg = 0;
+  while ((1ll << lg) < len) ++lg;                 // ceil(log2(len)), len >= 1
+  int top = 0;
+  while ((1 << top) < kLongRow) ++top;            // class of the longest short rows
+  const uint64_t cls = lng ? (uint64_t)(top + 1) : (uint64_t)(top - lg);
+  key[i] = (cls << 32) | (uint64_t)i;
+}
+
+__global__ void take_low32(const uint64_t* __restrict__ key, int64_t n, int32_t* __restrict__ out) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i < n) out[i] = (int32_t)(uint32_t)key[i];
+}
+
+// chunk_first / long_slot: exclusive scans of chunks_of / is_long.
+__global__ void fill_long_rows(int64_t n, const uint32_t* __restrict__ chunk_first,
+                               const uint32_t* __restrict__ long_slot, const uint32_t* __restrict__ is_long,
+                               int32_t* __restrict__ long_row, int32_t* __restrict__ long_first) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= n || !is_long[i]) return;
+  long_row[long_slot[i]] = (int32_t)i;
+  long_first[long_slot[i]] = (int32_t)chunk_first[i];
+}
+
+// One block per long row: its chunks, and for each the key (first gathered column << 32 | chunk id).
+__global__ __launch_bounds__(256) void fill_chunks(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                                                   const int32_t* __restrict__ long_row,
+                                                   const int32_t* __restrict__ long_first,
+                                                   int32_t* __restrict__ chunk_row, int32_t* __restrict__ chunk_begin,
+                                                   uint64_t* __restrict__ chunk_key) {
+  const int64_t i = long_row[blockIdx.x];
+  const int64_t begin = rowptr[i], len = rowptr[i + 1] - begin;
+  const int64_t k = (len + kLongRow - 1) / kLongRow;
+  const int64_t first = long_first[blockIdx.x];
+  for (int64_t c = threadIdx.x; c < k; c += blockDim.x) {
+    chunk_row[first + c] = (int32_t)i;
+    chunk_begin[first + c] = (int32_t)(c * kLongRow);
+    chunk_key[first + c] = ((uint64_t)(uint32_t)colidx[begin + c * kLongRow] << 32) | (uint64_t)(first + c);
   }
 }
 
-__global__ void fill_long_rows(const int64_t* __restrict__ rowptr, int64_t n, uint32_t* __restrict__ cursors,
-                               int32_t* __restrict__ long_row, int32_t* __restrict__ long_first,
-                               int32_t* __restrict__ chunk_row, int32_t* __restrict__ chunk_begin) {
-  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  const int64_t len = rowptr[i + 1] - rowptr[i];
-  if (len > kLongRow) {
-    const uint32_t k = (uint32_t)((len + kLongRow - 1) / kLongRow);
-    const uint32_t slot = atomicAdd(&cursors[0], 1u);
-    const uint32_t first = atomicAdd(&cursors[1], k);
-    long_row[slot] = (int32_t)i;
-    long_first[slot] = (int32_t)first;
-    for (uint32_t c = 0; c < k; ++c) {
-      chunk_row[first + c] = (int32_t)i;
-      chunk_begin[first + c] = (int32_t)(c * kLongRow);
-    }
-  }
+// One stable pass of the LSD radix sort on the 8-bit digit at `shift`: in -> out.
+int radix_pass(const uint64_t* in, uint64_t* out, uint32_t n_keys, int shift, uint32_t* hist, uint32_t* tile_tmp,
+               uint32_t* total_out, hipStream_t s) {
+  const uint32_t n_tiles = (uint32_t)ceil_div(n_keys, kTile);
+  if (n_tiles == 0) return GAD_OK;
+  radix_histogram<<<n_tiles, kThreads, 0, s>>>(in, n_keys, shift, n_tiles, hist);
+  GAD_LAUNCH_CHECK();
+  int st = exclusive_scan_u32(hist, 256u * n_tiles, tile_tmp, total_out, s);
+  if (st != GAD_OK) return st;
+  radix_scatter<<<n_tiles, kThreads, 0, s>>>(in, out, n_keys, shift, n_tiles, hist);
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
 }
 
 struct Scratch {   // frees whatever was allocated when it goes out of scope
@@ -324,7 +362,7 @@ int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int6
 
   Scratch scratch;
   int32_t* lut = nullptr;
-  uint32_t* flags = nullptr;   // [0] range, [1] dup, [2] emitted key count, [3] nnz, [4] long rows, [5] chunks, [6..7] cursors
+  uint32_t* flags = nullptr;   // [0] range, [1] dup, [2] emitted key count, [3] scan totals (nnz), [4] long rows, [5] chunks
   uint64_t *keys_a = nullptr, *keys_b = nullptr;
   uint32_t *hist = nullptr, *tile_tmp = nullptr, *pos = nullptr;
   GAD_HIP(scratch.alloc(&lut, (size_t)n_global));
@@ -359,12 +397,8 @@ int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int6
   GAD_HIP(scratch.alloc(&pos, (size_t)n_keys));
   uint64_t *cur = keys_a, *alt = keys_b;
   for (int shift = 0; shift < 2 * bits; shift += 8) {
-    radix_histogram<<<n_tiles, kThreads, 0, s>>>(cur, n_keys, shift, n_tiles, hist);
-    GAD_LAUNCH_CHECK();
-    int st = exclusive_scan_u32(hist, (uint32_t)hist_len, tile_tmp, flags + 3, s);
+    int st = radix_pass(cur, alt, n_keys, shift, hist, tile_tmp, flags + 3, s);
     if (st != GAD_OK) return st;
-    radix_scatter<<<n_tiles, kThreads, 0, s>>>(cur, alt, n_keys, shift, n_tiles, hist);
-    GAD_LAUNCH_CHECK();
     uint64_t* t = cur;
     cur = alt;
     alt = t;
@@ -402,21 +436,61 @@ int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int6
   GAD_HIP_G(hipGetLastError());
   degree_norm<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(g->rowptr, n, g->deg, g->dinv);
   GAD_HIP_G(hipGetLastError());
-  count_long_rows<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(g->rowptr, n, flags + 4);
+  // SpMM schedule.  The sort buffers are free again (assemble_csr was their last reader on this stream).
+  uint32_t *chunks_of = nullptr, *is_long = nullptr;
+  GAD_HIP_G(scratch.alloc(&chunks_of, (size_t)n));
+  GAD_HIP_G(scratch.alloc(&is_long, (size_t)n));
+  uint64_t* row_key = alt;              // n <= n_keys entries
+  classify_rows<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(g->rowptr, n, chunks_of, is_long, row_key);
   GAD_HIP_G(hipGetLastError());
+  GAD_HIP_G(hipMalloc((void**)&g->row_order, sizeof(int32_t) * (size_t)n));
+  {
+    uint64_t* sorted = cur;             // the CSR no longer needs the sorted edge keys
+    int st = radix_pass(row_key, sorted, (uint32_t)n, 32, hist, tile_tmp, flags + 3, s);
+    if (st != GAD_OK) return fail(st);
+    take_low32<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(sorted, n, g->row_order);
+    GAD_HIP_G(hipGetLastError());
+  }
+  // chunks_of / is_long -> exclusive scans (first chunk id and slot of every long row), totals -> flags[5], flags[4]
+  uint32_t* chunk_first = pos;          // pos holds n_keys >= n entries and was last read by assemble_csr
+  GAD_HIP_G(hipMemcpyAsync(chunk_first, chunks_of, sizeof(uint32_t) * (size_t)n, hipMemcpyDeviceToDevice, s));
+  {
+    int st = exclusive_scan_u32(chunk_first, (uint32_t)n, tile_tmp, flags + 5, s);
+    if (st != GAD_OK) return fail(st);
+  }
+  uint32_t* long_slot = nullptr;
+  GAD_HIP_G(scratch.alloc(&long_slot, (size_t)n));
+  GAD_HIP_G(hipMemcpyAsync(long_slot, is_long, sizeof(uint32_t) * (size_t)n, hipMemcpyDeviceToDevice, s));
+  {
+    int st = exclusive_scan_u32(long_slot, (uint32_t)n, tile_tmp, flags + 4, s);
+    if (st != GAD_OK) return fail(st);
+  }
   GAD_HIP_G(hipMemcpyAsync(h_flags + 4, flags + 4, 2 * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
   GAD_HIP_G(hipStreamSynchronize(s));
   g->n_long = (int32_t)h_flags[4];
   g->n_chunks = (int32_t)h_flags[5];
+  g->n_short = n - g->n_long;
   if (g->n_long > 0) {
     GAD_HIP_G(hipMalloc((void**)&g->long_row, sizeof(int32_t) * (size_t)g->n_long));
     GAD_HIP_G(hipMalloc((void**)&g->long_first, sizeof(int32_t) * (size_t)g->n_long));
     GAD_HIP_G(hipMalloc((void**)&g->chunk_row, sizeof(int32_t) * (size_t)g->n_chunks));
     GAD_HIP_G(hipMalloc((void**)&g->chunk_begin, sizeof(int32_t) * (size_t)g->n_chunks));
-    g->partial_elems = (int64_t)g->n_chunks * kPartialWidth;
-    GAD_HIP_G(hipMalloc((void**)&g->partial, sizeof(float) * (size_t)g->partial_elems));
-    fill_long_rows<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(g->rowptr, n, flags + 6, g->long_row, g->long_first,
-                                                              g->chunk_row, g->chunk_begin);
+    GAD_HIP_G(hipMalloc((void**)&g->chunk_perm, sizeof(int32_t) * (size_t)g->n_chunks));
+    fill_long_rows<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(n, chunk_first, long_slot, is_long, g->long_row,
+                                                              g->long_first);
+    GAD_HIP_G(hipGetLastError());
+    uint64_t *ck = alt, *ck_alt = cur;  // n_chunks < n_keys entries each
+    fill_chunks<<<(unsigned)g->n_long, 256, 0, s>>>(g->rowptr, g->colidx, g->long_row, g->long_first, g->chunk_row,
+                                                    g->chunk_begin, ck);
+    GAD_HIP_G(hipGetLastError());
+    for (int shift = 32; shift < 32 + bits; shift += 8) {      // order the chunks by their first column
+      int st = radix_pass(ck, ck_alt, (uint32_t)g->n_chunks, shift, hist, tile_tmp, flags + 3, s);
+      if (st != GAD_OK) return fail(st);
+      uint64_t* t = ck;
+      ck = ck_alt;
+      ck_alt = t;
+    }
+    take_low32<<<(unsigned)ceil_div(g->n_chunks, 256), 256, 0, s>>>(ck, g->n_chunks, g->chunk_perm);
     GAD_HIP_G(hipGetLastError());
   }
   GAD_HIP_G(hipStreamSynchronize(s));

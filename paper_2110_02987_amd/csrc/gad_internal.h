@@ -43,9 +43,7 @@ struct Epi {
 
 // Rows longer than this many non-zeros are split into chunks of this size; each chunk is summed by
 // one wave into a partial row and the partials of a row are added in chunk order.
-constexpr int kLongRow = 1024;
-// Widest slab of columns one SpMM launch handles for long rows (floats per partial row).
-constexpr int kPartialWidth = 512;
+constexpr int kLongRow = 128;
 constexpr int kMaxWidth = 4096;      // widest feature / hidden dimension accepted
 constexpr int kMaxLayers = 16;
 constexpr int kMaxConsensus = 128;   // most buffers one consensus call averages
@@ -59,16 +57,20 @@ struct gad_graph {
   int32_t* colidx = nullptr;   // [nnz]
   int32_t* deg = nullptr;      // [n]
   float* dinv = nullptr;       // [n]
-  // long-row schedule (rows with more than kLongRow non-zeros)
-  int32_t n_long = 0;          // number of long rows
-  int32_t n_chunks = 0;        // total number of chunks over all long rows
-  int32_t* long_row = nullptr;       // [n_long] row id
-  int32_t* long_first = nullptr;     // [n_long] first chunk slot of the row
+  // SpMM schedule.  Rows with at most kLongRow non-zeros ("short") are summed by one wave each, in the order
+  // row_order[0 .. n_short): longest class first, so that waves running side by side do similar amounts of work.
+  // Longer rows are cut into chunks of kLongRow non-zeros; the chunks run in the order chunk_perm[], ascending in
+  // the first column they gather, so that chunks running side by side read the same region of the source matrix.
+  int64_t n_short = 0;
+  int32_t* row_order = nullptr;      // [n] short rows by class, then the long rows
+  int32_t n_long = 0;                // number of long rows
+  int32_t n_chunks = 0;              // total number of chunks over all long rows
+  int32_t* long_row = nullptr;       // [n_long] row id, ascending
+  int32_t* long_first = nullptr;     // [n_long] first chunk id of the row (its chunks are consecutive)
   int32_t* chunk_row = nullptr;      // [n_chunks] row id of the chunk
   int32_t* chunk_begin = nullptr;    // [n_chunks] offset of the chunk inside its row
-  float* partial = nullptr;          // [n_chunks x kPartialWidth] scratch for chunk sums; shared by all calls on this graph
-  int64_t partial_elems = 0;
-  double* red_scratch = nullptr;     // variance_scratch_doubles(n) doubles; shared by all calls on this graph
+  int32_t* chunk_perm = nullptr;     // [n_chunks] chunk ids in scheduling order
+  double* red_scratch = nullptr;     // variance_scratch_doubles(n) doubles; shared by all variance calls on this graph
   int device = 0;
 };
 
@@ -78,13 +80,24 @@ namespace gad {
 int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int64_t n_global, const int64_t* local_ids,
                    int64_t n_local, const int64_t* halo_ids, int64_t n_halo, hipStream_t s, gad_graph** out);
 // Node matrices are float32 or bfloat16 (gad_dtype); weights, partial sums and logits are float32.
-// out = A~ T with the epilogue applied; epi.aux (EPI_MASK) has T's storage type.
+// out = A~ T with the epilogue applied; epi.aux (EPI_MASK) has T's storage type.  `partial` holds the chunk sums
+// of the long rows: spmm_partial_floats(g, width) floats (may be NULL when that is 0).
+size_t spmm_partial_floats(const gad_graph* g, int width);
 int spmm(const gad_graph* g, const void* T, int64_t ldt, gad_dtype t_in, void* out, int64_t ldo, gad_dtype t_out,
-         int width, const Epi& epi, hipStream_t s);
+         int width, const Epi& epi, float* partial, hipStream_t s);
 
-// C[M x N] (ldc) = A[M x K] (lda) * B[K x N] (ldb) with the epilogue applied to C; epi.aux has A's storage type.
-int gemm_nn(const void* A, int64_t lda, gad_dtype ta, const float* B, int64_t ldb, void* C, int64_t ldc, gad_dtype tc,
-            int64_t M, int N, int K, const Epi& epi, hipStream_t s);
+// C[M x N] (ldc) = A[M x K] (lda) * op(W) with the epilogue applied to C; W is float32 row-major [w_rows x w_cols];
+// op(W) = W (K = w_rows, N = w_cols) or, with trans_w, W^T (K = w_cols, N = w_rows).  epi.aux has A's storage type.
+// `scratch` must hold gemm_w_scratch_bytes(w_rows, w_cols) bytes (a transposed or bfloat16 copy of W).
+size_t gemm_w_scratch_bytes(int w_rows, int w_cols);
+int gemm_w(const void* A, int64_t lda, gad_dtype ta, const float* W, int w_rows, int w_cols, bool trans_w, void* C,
+           int64_t ldc, gad_dtype tc, int64_t M, const Epi& epi, void* scratch, hipStream_t s);
+// bfloat16 storage: the same two contractions on the bfloat16 matrix instruction (gemm_bf16.hip)
+size_t bf16_weight_elems(int n_out, int k);      // elements of the bfloat16 copy of an [n_out x k] right operand
+int gemm_w_bf16(const void* A, int64_t lda, const float* W, int w_rows, int w_cols, bool trans_w, void* C, int64_t ldc,
+                gad_dtype tc, int64_t M, const Epi& epi, void* scratch, hipStream_t s);
+int gemm_tn_bf16(const void* A, int64_t lda, const void* G, int64_t ldg, float* partials, int64_t M, int K, int N,
+                 int n_slabs, int64_t slab_rows, hipStream_t s);
 // C[K x N] (ldc) = A[M x K]^T * G[M x N]; `partials` must hold gemm_tn_partial_floats(M, K, N) floats.
 size_t gemm_tn_partial_floats(int64_t M, int K, int N);
 int gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, gad_dtype t, float* C, int64_t ldc, int64_t M,

@@ -10,8 +10,7 @@
 // 2 x 2 MFMA 32x32 accumulators.  Both operands are staged through LDS with the reduction index
 // leading (As[kk][i], Bs[kk][j]) so that a fragment read is 64 consecutive floats; the next tile is
 // fetched from global memory into registers while the current one is multiplied (double-buffered LDS).
-// Node matrices (A, G, C of NN, the mask operand) may be stored as float32 or bfloat16; they are widened
-// to float32 when staged, products and sums are float32, weights are always float32.
+// This file holds the float32 storage path; bfloat16 storage runs on the bfloat16 matrix instruction (gemm_bf16.hip).
 #include "dtype.h"
 #include "gad_internal.h"
 
@@ -247,7 +246,7 @@ void tn_split(int64_t M, int K, int N, int* n_slabs, int64_t* slab_rows) {
   const int64_t max_slabs = ceil_div(M, 512);         // at least 512 reduction rows per slab
   if (want > max_slabs) want = max_slabs;
   if (want < 1) want = 1;
-  *slab_rows = round_up(ceil_div(M, want), BK);
+  *slab_rows = round_up(ceil_div(M, want), 64);       // whole tiles of either kernel (16 or 64 rows)
   *n_slabs = (int)ceil_div(M, *slab_rows);
 }
 
@@ -294,16 +293,26 @@ int gemm_tn_typed(const TA* A, int64_t lda, const TA* G, int64_t ldg, float* C, 
 
 }  // namespace
 
-int gemm_nn(const void* A, int64_t lda, gad_dtype ta, const float* B, int64_t ldb, void* C, int64_t ldc, gad_dtype tc,
-            int64_t M, int N, int K, const Epi& e, hipStream_t s) {
+size_t gemm_w_scratch_bytes(int w_rows, int w_cols) {
+  const size_t f32 = (size_t)w_rows * w_cols * sizeof(float);                       // transposed float32 copy
+  const size_t a = bf16_weight_elems(w_cols, w_rows) * sizeof(bf16_t);              // bfloat16 W^T, padded rows
+  const size_t b = bf16_weight_elems(w_rows, w_cols) * sizeof(bf16_t);              // bfloat16 W, padded rows
+  return f32 > a ? (f32 > b ? f32 : b) : (a > b ? a : b);
+}
+
+int gemm_w(const void* A, int64_t lda, gad_dtype ta, const float* W, int w_rows, int w_cols, bool trans_w, void* C,
+           int64_t ldc, gad_dtype tc, int64_t M, const Epi& e, void* scratch, hipStream_t s) {
+  const int N = trans_w ? w_rows : w_cols, K = trans_w ? w_cols : w_rows;
   if (M == 0 || N == 0) return GAD_OK;
-  if (ta == GAD_F32 && tc == GAD_F32)
-    return gemm_nn_typed<float, float>((const float*)A, lda, B, ldb, (float*)C, ldc, M, N, K, e, s);
-  if (ta == GAD_BF16 && tc == GAD_BF16)
-    return gemm_nn_typed<bf16_t, bf16_t>((const bf16_t*)A, lda, B, ldb, (bf16_t*)C, ldc, M, N, K, e, s);
-  if (ta == GAD_BF16 && tc == GAD_F32)
-    return gemm_nn_typed<bf16_t, float>((const bf16_t*)A, lda, B, ldb, (float*)C, ldc, M, N, K, e, s);
-  return set_error(GAD_ERR_UNSUPPORTED, "GEMM from float32 storage to bfloat16 storage is not implemented");
+  if (ta == GAD_BF16) return gemm_w_bf16(A, lda, W, w_rows, w_cols, trans_w, C, ldc, tc, M, e, scratch, s);
+  if (tc != GAD_F32) return set_error(GAD_ERR_UNSUPPORTED, "GEMM from float32 storage to bfloat16 storage is not implemented");
+  const float* B = W;
+  if (trans_w) {
+    int st = transpose_f32(W, w_rows, w_cols, static_cast<float*>(scratch), s);
+    if (st != GAD_OK) return st;
+    B = static_cast<const float*>(scratch);
+  }
+  return gemm_nn_typed<float, float>((const float*)A, lda, B, N, (float*)C, ldc, M, N, K, e, s);
 }
 
 size_t gemm_tn_partial_floats(int64_t M, int K, int N) {
@@ -317,7 +326,15 @@ int gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, gad_dtype t,
             int K, int N, float* partials, hipStream_t s) {
   if (K == 0 || N == 0) return GAD_OK;
   if (t == GAD_F32) return gemm_tn_typed<float>((const float*)A, lda, (const float*)G, ldg, C, ldc, M, K, N, partials, s);
-  return gemm_tn_typed<bf16_t>((const bf16_t*)A, lda, (const bf16_t*)G, ldg, C, ldc, M, K, N, partials, s);
+  int n_slabs;
+  int64_t slab_rows;
+  tn_split(M, K, N, &n_slabs, &slab_rows);
+  int st = gemm_tn_bf16(A, lda, G, ldg, partials, M, K, N, n_slabs, slab_rows, s);
+  if (st != GAD_OK) return st;
+  const int64_t elems = (int64_t)K * N;
+  reduce_slabs<<<(unsigned)ceil_div(elems, 256), 256, 0, s>>>(partials, n_slabs, elems, N, C, ldc);
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
 }
 
 int transpose_f32(const float* in, int rows, int cols, float* out, hipStream_t s) {

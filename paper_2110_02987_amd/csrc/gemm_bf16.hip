@@ -1,0 +1,365 @@
+// Dense contractions of the GCN step for bfloat16 storage on the gfx950 matrix cores
+// (v_mfma_f32_32x32x16_bf16: bfloat16 operands, float32 accumulation):
+//   NT:  C[M x N] = A[M x K] Bt[N x K]^T       -- the feature transform H W of Eq. 7 (Bt = W^T rounded to
+//                                                  bfloat16) and the input-gradient product S W^T (Bt = W)
+//   TN:  P[slab][K x N] = A[rows of slab]^T G  -- the weight gradient dW = (A~ H)^T G, a reduction over the
+//                                                  nodes, split into slabs that are added in slab order.
+// (arXiv 2110.02987, Section 3.3: Eq. 7 forward; backward step of Algorithm 2.)
+//
+// One MFMA consumes, per lane, 8 consecutive elements of the contraction index for one row of the left
+// operand and one column of the right operand.  Both operand tiles therefore sit in LDS with the contraction
+// index contiguous (16-byte fragment reads, row stride 144 bytes: conflict free).  For NT that is the layout
+// the operands already have in memory.  For TN the contraction index is the row index of both A and G, so
+// each thread fetches an 8 x 8 block (eight 16-byte row pieces), transposes it in registers with byte
+// permutes, and writes eight 16-byte column pieces; the 16-byte chunks of a tile row are XOR-swizzled so that
+// these writes are conflict free as well.  Because the same order of the contraction index is used for both
+// operands, the result does not depend on which 8 indices a lane holds.
+//
+// Four wave64s per block in a 2 x 2 arrangement; a wave owns TM x TN accumulators of 32 x 32.  The next tile
+// is fetched from global memory into registers while the current one is multiplied (double-buffered LDS, one
+// barrier per tile).  Blocks are renumbered so that the blocks sharing an operand tile run on the same XCD
+// (consecutive workgroup ids go to different XCDs, each with an L2 of its own).
+#include "dtype.h"
+#include "gad_internal.h"
+
+namespace gad {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kXcds = 8;
+
+// Workgroup id -> work item such that the items of one XCD are consecutive (bijection on [0, total)).
+__device__ __forceinline__ int64_t xcd_order(int64_t bid, int64_t total) {
+  const int64_t per = total / kXcds, rem = total % kXcds;
+  const int64_t x = bid % kXcds, slot = bid / kXcds;
+  return x * per + (x < rem ? x : rem) + slot;
+}
+
+// Row of accumulator register r of a 32x32 MFMA result held by `lane` (its column is lane % 32).
+__device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
+// 8 consecutive bfloat16 of row `row` from column `col`, zero outside [0, n_rows) x [0, n_cols).
+__device__ __forceinline__ uint4 load_piece(const bf16_t* __restrict__ base, int64_t ld, int64_t row, int64_t n_rows,
+                                            int col, int n_cols, bool vec_ok) {
+  uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  if (row < n_rows) {
+    const bf16_t* p = base + row * ld + col;
+    if (vec_ok && col + 8 <= n_cols) {
+      v = *reinterpret_cast<const uint4*>(p);
+    } else {
+      uint32_t e[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) e[q] = col + q < n_cols ? (uint32_t)p[q] : 0u;
+      v.x = e[0] | (e[1] << 16);
+      v.y = e[2] | (e[3] << 16);
+      v.z = e[4] | (e[5] << 16);
+      v.w = e[6] | (e[7] << 16);
+    }
+  }
+  return v;
+}
+
+// Offset (in elements) of 16-byte chunk `chunk` of tile row `row`; LDK = row stride.
+template <int LDK, bool SWZ>
+__device__ __forceinline__ int tile_off(int row, int chunk) {
+  return row * LDK + ((SWZ ? (chunk ^ ((row >> 4) & 7)) : chunk) << 3);
+}
+
+// acc[tm][tn] += L[wrow + 32 tm .., :] R[wcol + 32 tn .., :]^T over the BK contraction indices of one tile.
+template <int BK, int TM, int TN, bool SWZ>
+__device__ __forceinline__ void mma_tile(const bf16_t* __restrict__ Ls, const bf16_t* __restrict__ Rs, int wrow,
+                                         int wcol, v16f (&acc)[TM][TN]) {
+  constexpr int LDK = BK + 8;
+  const int lane = threadIdx.x & 63;
+  const int i = lane & 31, kg = lane >> 5;
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ++ks) {
+    const int chunk = ks * 2 + kg;
+    bf16x8 a[TM], b[TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+      a[tm] = *reinterpret_cast<const bf16x8*>(Ls + tile_off<LDK, SWZ>(wrow + tm * 32 + i, chunk));
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+      b[tn] = *reinterpret_cast<const bf16x8*>(Rs + tile_off<LDK, SWZ>(wcol + tn * 32 + i, chunk));
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+  }
+}
+
+template <int TM, int TN>
+__device__ __forceinline__ void zero_acc(v16f (&acc)[TM][TN]) {
+#pragma unroll
+  for (int x = 0; x < TM; ++x)
+#pragma unroll
+    for (int y = 0; y < TN; ++y)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
+}
+
+template <int EPI, int TM, int TN, typename TC>
+__device__ __forceinline__ void store_acc(const v16f (&acc)[TM][TN], TC* __restrict__ C, int64_t ldc, int64_t row0,
+                                          int col0, int64_t M, int N, float slope, const bf16_t* __restrict__ aux,
+                                          int64_t ldaux) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      const int col = col0 + tn * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t row = row0 + tm * 32 + acc_row(r, lane);
+        if (row < M && col < N) {
+          float v = acc[tm][tn][r];
+          if (EPI == EPI_RELU) v = leaky(v, v > 0.f, slope);
+          if (EPI == EPI_MASK) v = leaky(v, bf16_to_float(aux[row * ldaux + col]) > 0.f, slope);
+          C[row * ldc + col] = from_f32<TC>(v);
+        }
+      }
+    }
+}
+
+// ---- NT ----------------------------------------------------------------------------------------
+// Block tile 128 x (64 TN); work item = (row tile, column tile) with the column tile fastest, so the blocks
+// that share a row tile of A follow each other on one XCD.  Bt has ldb = K rounded up to BK, zero filled.
+template <int BK, int TN, int EPI, typename TC>
+__global__ __launch_bounds__(256) void gemm_nt_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                      const bf16_t* __restrict__ Bt, int64_t ldb,
+                                                      TC* __restrict__ C, int64_t ldc, int64_t M, int N, int K,
+                                                      bool a_vec, float slope, const bf16_t* __restrict__ aux,
+                                                      int64_t ldaux, int tiles_n, int64_t total) {
+  constexpr int BM = 128, BN = 64 * TN, LDK = BK + 8, CH = BK / 8;
+  constexpr int PA = BM * CH / 256, PB = BN * CH / 256;      // 16-byte pieces per thread and tile
+  constexpr int TILE = (BM + BN) * LDK;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);        // [2][TILE]: rows 0..BM-1 = A, then BN rows of Bt
+  const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
+  const int64_t item = xcd_order(blockIdx.x, total);
+  const int64_t row0 = (item / tiles_n) * BM;
+  const int col0 = (int)(item % tiles_n) * BN;
+  v16f acc[2][TN];
+  zero_acc<2, TN>(acc);
+
+  uint4 ra[PA], rb[PB];
+  auto fetch = [&](int k1) {
+#pragma unroll
+    for (int j = 0; j < PA; ++j) {
+      const int p = t + 256 * j;
+      ra[j] = load_piece(A, lda, row0 + p / CH, M, k1 + (p % CH) * 8, K, a_vec);
+    }
+#pragma unroll
+    for (int j = 0; j < PB; ++j) {
+      const int p = t + 256 * j;
+      const int r = col0 + p / CH;
+      rb[j] = r < N ? *reinterpret_cast<const uint4*>(Bt + (int64_t)r * ldb + k1 + (p % CH) * 8)
+                    : make_uint4(0u, 0u, 0u, 0u);
+    }
+  };
+  auto stage = [&](bf16_t* tile) {
+#pragma unroll
+    for (int j = 0; j < PA; ++j) {
+      const int p = t + 256 * j;
+      *reinterpret_cast<uint4*>(tile + (p / CH) * LDK + (p % CH) * 8) = ra[j];
+    }
+#pragma unroll
+    for (int j = 0; j < PB; ++j) {
+      const int p = t + 256 * j;
+      *reinterpret_cast<uint4*>(tile + (BM + p / CH) * LDK + (p % CH) * 8) = rb[j];
+    }
+  };
+  fetch(0);
+  stage(smem);
+  __syncthreads();
+  const int n_kt = (K + BK - 1) / BK;
+  for (int kt = 0; kt < n_kt; ++kt) {
+    bf16_t* cur = smem + (kt & 1) * TILE;
+    bf16_t* nxt = smem + ((kt & 1) ^ 1) * TILE;
+    if (kt + 1 < n_kt) fetch((kt + 1) * BK);
+    mma_tile<BK, 2, TN, false>(cur, cur + BM * LDK, wm * 64, wn * 32 * TN, acc);
+    if (kt + 1 < n_kt) stage(nxt);
+    __syncthreads();
+  }
+  store_acc<EPI, 2, TN, TC>(acc, C, ldc, row0 + wm * 64, col0 + wn * 32 * TN, M, N, slope, aux, ldaux);
+}
+
+// ---- TN ----------------------------------------------------------------------------------------
+// Output tile 128 x 128 of K x N; work item = (slab, output tile) with the output tile fastest, so the
+// blocks that read the same rows of A and G follow each other on one XCD.  Writes P[slab][K x N] (ld N).
+constexpr int TBK = 64;            // rows of A / G per tile (the contraction index)
+constexpr int TLDK = TBK + 8;
+
+__device__ __forceinline__ uint32_t dword_of(const uint4& v, int d) { return d == 0 ? v.x : d == 1 ? v.y : d == 2 ? v.z : v.w; }
+
+// in[r] = 8 consecutive columns of row r (r = 0..7)  ->  out[c] = rows 0..7 of column c.
+__device__ __forceinline__ void transpose8x8(const uint4 (&in)[8], uint4 (&out)[8]) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {        // dword d of a row holds its columns 2d (low half) and 2d+1 (high half)
+    uint32_t lo[4], hi[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t x = dword_of(in[2 * j], d), y = dword_of(in[2 * j + 1], d);
+      lo[j] = __builtin_amdgcn_perm(y, x, 0x05040100u);   // column 2d   of rows 2j (low half), 2j+1 (high half)
+      hi[j] = __builtin_amdgcn_perm(y, x, 0x07060302u);   // column 2d+1 of rows 2j, 2j+1
+    }
+    out[2 * d] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    out[2 * d + 1] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+  }
+}
+
+__global__ __launch_bounds__(256) void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                      const bf16_t* __restrict__ G, int64_t ldg,
+                                                      float* __restrict__ P, int64_t M, int K, int N,
+                                                      int64_t slab_rows, int tiles_n, int tiles, int64_t total,
+                                                      bool a_vec, bool g_vec) {
+  constexpr int TILE = 2 * 128 * TLDK;                         // 128 tile rows of A^T, then 128 of G^T
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);          // [2][TILE]
+  const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
+  const int64_t item = xcd_order(blockIdx.x, total);
+  const int tile = (int)(item % tiles);
+  const int64_t slab = item / tiles;
+  const int k0 = (tile / tiles_n) * 128;    // output row block (columns of A)
+  const int n0 = (tile % tiles_n) * 128;    // output column block (columns of G)
+  const int64_t m_begin = slab * slab_rows;
+  const int64_t m_end = m_begin + slab_rows < M ? m_begin + slab_rows : M;
+  v16f acc[2][2];
+  zero_acc<2, 2>(acc);
+
+  // threads 0..127 move A, 128..255 move G; unit u = (row group mb of 8 rows, column group cb of 8 columns)
+  const bool is_g = t >= 128;
+  const int u = t & 127, cb = u & 15, mb = u >> 4;
+  const bf16_t* src = is_g ? G : A;
+  const int64_t ld = is_g ? ldg : lda;
+  const int c0 = (is_g ? n0 : k0) + cb * 8;
+  const int n_cols = is_g ? N : K;
+  const bool vec = is_g ? g_vec : a_vec;
+  const int tile_row0 = (is_g ? 128 : 0) + cb * 8;
+  uint4 rin[8];
+  auto fetch = [&](int64_t m1) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) rin[r] = load_piece(src, ld, m1 + mb * 8 + r, m_end, c0, n_cols, vec);
+  };
+  auto stage = [&](bf16_t* tl) {
+    uint4 rout[8];
+    transpose8x8(rin, rout);
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+      *reinterpret_cast<uint4*>(tl + tile_off<TLDK, true>(tile_row0 + c, mb)) = rout[c];
+  };
+  fetch(m_begin);
+  stage(smem);
+  __syncthreads();
+  const int64_t n_mt = (m_end - m_begin + TBK - 1) / TBK;
+  for (int64_t mt = 0; mt < n_mt; ++mt) {
+    bf16_t* cur = smem + (mt & 1) * TILE;
+    bf16_t* nxt = smem + ((mt & 1) ^ 1) * TILE;
+    if (mt + 1 < n_mt) fetch(m_begin + (mt + 1) * TBK);
+    mma_tile<TBK, 2, 2, true>(cur, cur, wm * 64, 128 + wn * 64, acc);
+    if (mt + 1 < n_mt) stage(nxt);
+    __syncthreads();
+  }
+  float* Pslab = P + slab * (int64_t)K * N;
+  store_acc<EPI_NONE, 2, 2, float>(acc, Pslab, N, k0 + wm * 64, n0 + wn * 64, K, N, 0.f, nullptr, 0);
+}
+
+// out[r][c] (leading dimension ld_out) = transpose ? W[c][r] : W[r][c], rounded to bfloat16; zero for
+// out_cols <= c < ld_out.  W is row-major with w_cols columns.
+__global__ void weights_to_bf16(const float* __restrict__ W, int w_cols, bool transpose, bf16_t* __restrict__ out,
+                                int out_rows, int out_cols, int ld_out) {
+  const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (e >= (int64_t)out_rows * ld_out) return;
+  const int r = (int)(e / ld_out), c = (int)(e % ld_out);
+  float v = 0.f;
+  if (c < out_cols) v = transpose ? W[(int64_t)c * w_cols + r] : W[(int64_t)r * w_cols + c];
+  out[e] = float_to_bf16(v);
+}
+
+bool vec_ok(const bf16_t* p, int64_t ld) { return (ld % 8 == 0) && ((reinterpret_cast<uintptr_t>(p) & 15u) == 0); }
+
+constexpr int kNtBK = 64;
+
+template <int TN, typename TC>
+int launch_nt(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
+              const Epi& e, hipStream_t s) {
+  constexpr int BN = 64 * TN;
+  constexpr size_t smem = 2u * (128 + BN) * (kNtBK + 8) * sizeof(bf16_t);
+  const int tiles_n = (int)ceil_div(N, BN);
+  const int64_t total = ceil_div(M, 128) * tiles_n;
+  const bf16_t* aux = static_cast<const bf16_t*>(e.aux);
+  const bool av = vec_ok(A, lda);
+#define GAD_NT_LAUNCH(EPI)                                                                                          \
+  {                                                                                                                 \
+    auto kern = gemm_nt_kernel<kNtBK, TN, EPI, TC>;                                                                 \
+    static bool attr_set = false;                                                                                   \
+    if (!attr_set) {                                                                                                \
+      GAD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,  \
+                                  (int)smem));                                                                      \
+      attr_set = true;                                                                                              \
+    }                                                                                                               \
+    kern<<<(unsigned)total, 256, smem, s>>>(A, lda, Bt, ldb, C, ldc, M, N, K, av, e.slope, aux, e.ldaux, tiles_n,   \
+                                            total);                                                                 \
+  }
+  switch (e.kind) {
+    case EPI_NONE: GAD_NT_LAUNCH(EPI_NONE) break;
+    case EPI_RELU: GAD_NT_LAUNCH(EPI_RELU) break;
+    case EPI_MASK: GAD_NT_LAUNCH(EPI_MASK) break;
+    default: return set_error(GAD_ERR_UNSUPPORTED, "unknown epilogue %d", e.kind);
+  }
+#undef GAD_NT_LAUNCH
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
+}
+
+template <typename TC>
+int nt_typed(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
+             const Epi& e, hipStream_t s) {
+  if (N <= 64) return launch_nt<1, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+  if (N <= 128) return launch_nt<2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+  return launch_nt<4, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+}
+
+}  // namespace
+
+size_t bf16_weight_elems(int n_out, int k) { return (size_t)n_out * (size_t)round_up(k, kNtBK); }
+
+int gemm_w_bf16(const void* A, int64_t lda, const float* W, int w_rows, int w_cols, bool trans_w, void* C, int64_t ldc,
+                gad_dtype tc, int64_t M, const Epi& e, void* scratch, hipStream_t s) {
+  const int N = trans_w ? w_rows : w_cols, K = trans_w ? w_cols : w_rows;
+  if (M == 0 || N == 0) return GAD_OK;
+  // Bt[n][k] = op(W)[k][n]: W^T when op is the identity, W itself when op is the transpose.
+  bf16_t* Bt = static_cast<bf16_t*>(scratch);
+  const int ldb = (int)round_up(K, kNtBK);
+  weights_to_bf16<<<(unsigned)ceil_div((int64_t)N * ldb, 256), 256, 0, s>>>(W, w_cols, !trans_w, Bt, N, K, ldb);
+  GAD_LAUNCH_CHECK();
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  if (tc == GAD_BF16) return nt_typed<bf16_t>(a, lda, Bt, ldb, static_cast<bf16_t*>(C), ldc, M, N, K, e, s);
+  return nt_typed<float>(a, lda, Bt, ldb, static_cast<float*>(C), ldc, M, N, K, e, s);
+}
+
+int gemm_tn_bf16(const void* A, int64_t lda, const void* G, int64_t ldg, float* partials, int64_t M, int K, int N,
+                 int n_slabs, int64_t slab_rows, hipStream_t s) {
+  constexpr size_t smem = 2u * 2u * 128u * TLDK * sizeof(bf16_t);
+  static bool attr_set = false;
+  if (!attr_set) {
+    GAD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)smem));
+    attr_set = true;
+  }
+  const int tiles_n = (int)ceil_div(N, 128);
+  const int tiles = (int)ceil_div(K, 128) * tiles_n;
+  const int64_t total = (int64_t)tiles * n_slabs;
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* g = static_cast<const bf16_t*>(G);
+  gemm_tn_kernel<<<(unsigned)total, 256, smem, s>>>(a, lda, g, ldg, partials, M, K, N, slab_rows, tiles_n, tiles, total,
+                                                    vec_ok(a, lda), vec_ok(g, ldg));
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
+}
+
+}  // namespace gad

@@ -8,8 +8,14 @@
 // the end.  Accumulation is float32 whatever the storage type.  Only the 4-byte column index is read per
 // edge; dinv_j comes from a 4n-byte array that stays in L2.
 // Rows longer than kLongRow are cut into chunks, one wave per chunk (the first blocks of the same
-// launch), whose raw sums go to a partial buffer and are added in chunk order by a second kernel
+// launch), whose raw sums go to a partial buffer and are added in a fixed order by a second kernel
 // (deterministic: no floating-point atomics).
+// Scheduling (arrays prepared once per graph): the chunks run ordered by the first column they gather.  A
+// row's columns ascend, so chunks that run side by side read the same region of T and the rows of T that many
+// long rows share are fetched from HBM once and then found in the caches; on a power-law graph most
+// non-zeros sit in long rows, which is where this pays.  Short rows run longest class first, so that a
+// wave's neighbours in dispatch order do similar amounts of work and wave slots are not left idle behind a
+// few long waves.
 #include "dtype.h"
 #include "gad_internal.h"
 
@@ -73,43 +79,43 @@ __device__ __forceinline__ void store_elem(TO* __restrict__ out, int64_t ldo, in
 }
 
 // One launch covers the whole product.  grid.y: column slab of LPR*V columns.  grid.x: the first
-// `chunk_blocks` blocks take the chunks of the long rows (4 per block, one per wave; the longest work
-// starts first), the remaining blocks take 4 rows each (one per wave) and skip the long rows.
-// Chunk sums go to partial[chunk][column - col0] for columns in [col0, col0 + kPartialWidth).
+// `chunk_blocks` blocks take the chunks of the long rows in their scheduling order (4 per block, one per wave;
+// the longest work starts first), the remaining blocks take the short rows in class order (one per wave).
+// Chunk sums go to partial[chunk id][column] (leading dimension ldp).
 template <int LPR, int V, typename TI, typename TO>
 __global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
                                                    const float* __restrict__ dinv, const TI* __restrict__ T,
-                                                   int64_t ldt, TO* __restrict__ out, int64_t ldo, int width, int col0,
-                                                   int64_t n, int epi, float slope, const TI* __restrict__ aux,
-                                                   int64_t ldaux, int chunk_blocks, const int32_t* __restrict__ chunk_row,
+                                                   int64_t ldt, TO* __restrict__ out, int64_t ldo, int width,
+                                                   int64_t n_short, const int32_t* __restrict__ row_order, int epi,
+                                                   float slope, const TI* __restrict__ aux, int64_t ldaux,
+                                                   int chunk_blocks, const int32_t* __restrict__ chunk_perm,
+                                                   const int32_t* __restrict__ chunk_row,
                                                    const int32_t* __restrict__ chunk_begin, int n_chunks,
-                                                   float* __restrict__ partial) {
+                                                   float* __restrict__ partial, int64_t ldp) {
   const int lane = threadIdx.x & 63;
-  const int rel = blockIdx.y * (LPR * V) + (lane % LPR) * V;
-  const int c = col0 + rel;
+  const int c = blockIdx.y * (LPR * V) + (lane % LPR) * V;
+  const bool active = c < width;
   float acc[V];
   if ((int)blockIdx.x < chunk_blocks) {
-    const int ch = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (ch >= n_chunks) return;
+    const int e = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (e >= n_chunks) return;
+    const int ch = chunk_perm[e];
     const int64_t i = chunk_row[ch];
     const int64_t begin = rowptr[i] + chunk_begin[ch];
     const int64_t row_end = rowptr[i + 1];
     const int64_t end = begin + kLongRow < row_end ? begin + kLongRow : row_end;
-    const bool active = c < width && rel < kPartialWidth;
     gather_sum<LPR, V, TI>(colidx, dinv, T, ldt, begin, end, c, active, acc);
     if (active && lane < LPR) {
 #pragma unroll
       for (int k = 0; k < V; ++k)
-        if (c + k < width) partial[(int64_t)ch * kPartialWidth + rel + k] = acc[k];
+        if (c + k < width) partial[(int64_t)ch * ldp + c + k] = acc[k];
     }
     return;
   }
-  const int64_t i = (int64_t)(blockIdx.x - chunk_blocks) * 4 + (threadIdx.x >> 6);
-  if (i >= n) return;
-  const int64_t begin = rowptr[i], end = rowptr[i + 1];
-  if (end - begin > kLongRow) return;   // summed by the chunk blocks + spmm_long_reduce
-  const bool active = c < width;
-  gather_sum<LPR, V, TI>(colidx, dinv, T, ldt, begin, end, c, active, acc);
+  const int64_t slot = (int64_t)(blockIdx.x - chunk_blocks) * 4 + (threadIdx.x >> 6);
+  if (slot >= n_short) return;
+  const int64_t i = row_order[slot];
+  gather_sum<LPR, V, TI>(colidx, dinv, T, ldt, rowptr[i], rowptr[i + 1], c, active, acc);
   if (active && lane < LPR) {
     const float di = dinv[i];
 #pragma unroll
@@ -118,84 +124,92 @@ __global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ r
   }
 }
 
-// One thread per (long row, column): adds the row's partial sums in chunk order.
+// One block per long row: adds the row's chunk sums in a fixed order (four contiguous runs of chunks, one per
+// wave, each added in chunk order; then the four run sums in run order), 64 columns at a time.
 template <typename TI, typename TO>
 __global__ __launch_bounds__(256) void spmm_long_reduce(const int64_t* __restrict__ rowptr,
                                                         const float* __restrict__ dinv,
                                                         const int32_t* __restrict__ long_row,
                                                         const int32_t* __restrict__ long_first,
-                                                        const float* __restrict__ partial, int col0, int ncols,
+                                                        const float* __restrict__ partial, int64_t ldp, int width,
                                                         TO* __restrict__ out, int64_t ldo, int epi, float slope,
                                                         const TI* __restrict__ aux, int64_t ldaux) {
-  const int slot = blockIdx.x;
-  const int64_t i = long_row[slot];
-  const int first = long_first[slot];
-  const int k = (int)((rowptr[i + 1] - rowptr[i] + kLongRow - 1) / kLongRow);
+  __shared__ float run_sum[4][64];
+  const int64_t i = long_row[blockIdx.x];
+  const int64_t first = long_first[blockIdx.x];
+  const int64_t k = (rowptr[i + 1] - rowptr[i] + kLongRow - 1) / kLongRow;
+  const int lane = threadIdx.x & 63, run = threadIdx.x >> 6;
+  const int64_t q0 = first + run * k / 4, q1 = first + (run + 1) * k / 4;
   const float di = dinv[i];
-  for (int rel = threadIdx.x; rel < ncols; rel += blockDim.x) {
+  for (int c0 = 0; c0 < width; c0 += 64) {
+    const int c = c0 + lane;
     float s = 0.f;
-    for (int q = 0; q < k; ++q) s += partial[(int64_t)(first + q) * kPartialWidth + rel];
-    store_elem<TI, TO>(out, ldo, i, col0 + rel, di * s, epi, slope, aux, ldaux);
+    if (c < width)
+      for (int64_t q = q0; q < q1; ++q) s += partial[q * ldp + c];
+    run_sum[run][lane] = s;
+    __syncthreads();
+    if (run == 0 && c < width) {
+      const float v = ((run_sum[0][lane] + run_sum[1][lane]) + run_sum[2][lane]) + run_sum[3][lane];
+      store_elem<TI, TO>(out, ldo, i, c, di * v, epi, slope, aux, ldaux);
+    }
+    __syncthreads();
   }
 }
 
 template <int LPR, int V, typename TI, typename TO>
-int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, int width, const Epi& e, hipStream_t s) {
-  const int epi = e.kind;
-  const float slope = e.slope;
+int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, int width, const Epi& e, float* partial,
+           hipStream_t s) {
   const TI* aux = static_cast<const TI*>(e.aux);
-  const int64_t ldaux = e.ldaux;
-  constexpr int slab = LPR * V;
-  const unsigned row_blocks = (unsigned)ceil_div(g->n, 4);
+  const unsigned row_blocks = (unsigned)ceil_div(g->n_short, 4);
   const unsigned chunk_blocks = (unsigned)ceil_div(g->n_chunks, 4);
-  // Columns are covered kPartialWidth at a time: one pass for every width the GCN step uses.
-  for (int col0 = 0; col0 < width; col0 += kPartialWidth) {
-    const int ncols = width - col0 < kPartialWidth ? width - col0 : kPartialWidth;
-    const dim3 grid(chunk_blocks + row_blocks, (unsigned)ceil_div(ncols, slab));
-    spmm_kernel<LPR, V, TI, TO><<<grid, 256, 0, s>>>(g->rowptr, g->colidx, g->dinv, T, ldt, out, ldo, col0 + ncols, col0,
-                                                     g->n, epi, slope, aux, ldaux, (int)chunk_blocks, g->chunk_row,
-                                                     g->chunk_begin, g->n_chunks, g->partial);
+  const dim3 grid(chunk_blocks + row_blocks, (unsigned)ceil_div(width, LPR * V));
+  spmm_kernel<LPR, V, TI, TO><<<grid, 256, 0, s>>>(g->rowptr, g->colidx, g->dinv, T, ldt, out, ldo, width, g->n_short,
+                                                   g->row_order, e.kind, e.slope, aux, e.ldaux, (int)chunk_blocks,
+                                                   g->chunk_perm, g->chunk_row, g->chunk_begin, g->n_chunks, partial,
+                                                   (int64_t)width);
+  GAD_LAUNCH_CHECK();
+  if (g->n_long > 0) {
+    spmm_long_reduce<TI, TO><<<(unsigned)g->n_long, 256, 0, s>>>(g->rowptr, g->dinv, g->long_row, g->long_first, partial,
+                                                                 (int64_t)width, width, out, ldo, e.kind, e.slope, aux,
+                                                                 e.ldaux);
     GAD_LAUNCH_CHECK();
-    if (g->n_long > 0) {
-      spmm_long_reduce<TI, TO><<<(unsigned)g->n_long, 256, 0, s>>>(g->rowptr, g->dinv, g->long_row, g->long_first,
-                                                                   g->partial, col0, ncols, out, ldo, epi, slope, aux,
-                                                                   ldaux);
-      GAD_LAUNCH_CHECK();
-    }
   }
   return GAD_OK;
 }
 
 template <typename TI, typename TO>
 int spmm_typed(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, int width, const Epi& e,
-               hipStream_t s) {
+               float* partial, hipStream_t s) {
   constexpr int VEC = 16 / (int)sizeof(TI);      // elements per 16-byte load
   const bool vec = (ldt % VEC == 0) && ((reinterpret_cast<uintptr_t>(T) & 15u) == 0);
   const int lanes = vec ? (width + VEC - 1) / VEC : width;
 #define GAD_SPMM_CASE(L)                                                                                   \
   if (lanes <= L)                                                                                          \
-    return vec ? launch<L, VEC, TI, TO>(g, T, ldt, out, ldo, width, e, s)                  \
-               : launch<L, 1, TI, TO>(g, T, ldt, out, ldo, width, e, s);
+    return vec ? launch<L, VEC, TI, TO>(g, T, ldt, out, ldo, width, e, partial, s)                  \
+               : launch<L, 1, TI, TO>(g, T, ldt, out, ldo, width, e, partial, s);
   GAD_SPMM_CASE(4)
   GAD_SPMM_CASE(8)
   GAD_SPMM_CASE(16)
   GAD_SPMM_CASE(32)
 #undef GAD_SPMM_CASE
-  return vec ? launch<64, VEC, TI, TO>(g, T, ldt, out, ldo, width, e, s)
-             : launch<64, 1, TI, TO>(g, T, ldt, out, ldo, width, e, s);
+  return vec ? launch<64, VEC, TI, TO>(g, T, ldt, out, ldo, width, e, partial, s)
+             : launch<64, 1, TI, TO>(g, T, ldt, out, ldo, width, e, partial, s);
 }
 
 }  // namespace
 
+size_t spmm_partial_floats(const gad_graph* g, int width) { return (size_t)g->n_chunks * (size_t)width; }
+
 int spmm(const gad_graph* g, const void* T, int64_t ldt, gad_dtype t_in, void* out, int64_t ldo, gad_dtype t_out,
-         int width, const Epi& e, hipStream_t s) {
+         int width, const Epi& e, float* partial, hipStream_t s) {
   if (g->n == 0 || width == 0) return GAD_OK;
+  if (g->n_chunks > 0 && !partial) return set_error(GAD_ERR_NULL, "SpMM needs a buffer for the chunk sums of the long rows");
   if (t_in == GAD_F32 && t_out == GAD_F32)
-    return spmm_typed<float, float>(g, (const float*)T, ldt, (float*)out, ldo, width, e, s);
+    return spmm_typed<float, float>(g, (const float*)T, ldt, (float*)out, ldo, width, e, partial, s);
   if (t_in == GAD_BF16 && t_out == GAD_BF16)
-    return spmm_typed<bf16_t, bf16_t>(g, (const bf16_t*)T, ldt, (bf16_t*)out, ldo, width, e, s);
+    return spmm_typed<bf16_t, bf16_t>(g, (const bf16_t*)T, ldt, (bf16_t*)out, ldo, width, e, partial, s);
   if (t_in == GAD_BF16 && t_out == GAD_F32)
-    return spmm_typed<bf16_t, float>(g, (const bf16_t*)T, ldt, (float*)out, ldo, width, e, s);
+    return spmm_typed<bf16_t, float>(g, (const bf16_t*)T, ldt, (float*)out, ldo, width, e, partial, s);
   return set_error(GAD_ERR_UNSUPPORTED, "SpMM from float32 storage to bfloat16 storage is not implemented");
 }
 

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libgad.so")
 
 F32, BF16 = 0, 1
 SYMBOLS = ["gad_last_error", "gad_build_subgraph", "gad_graph_info", "gad_graph_destroy",
-           "gad_gcn_workspace_bytes", "gad_gcn_forward", "gad_gcn_backward", "gad_gcn_activation", "gad_spmm",
+           "gad_gcn_workspace_bytes", "gad_gcn_forward", "gad_gcn_backward", "gad_gcn_activation", "gad_spmm_workspace_bytes", "gad_spmm",
+           "gad_gemm_workspace_bytes", "gad_gemm_w", "gad_gemm_tn",
            "gad_subgraph_variance", "gad_weighted_consensus", "gad_consensus_update", "gad_train_round"]
 
 _lib = None
@@ -178,11 +179,56 @@ def gcn_activation(g: Graph, workspace: torch.Tensor, dims: Sequence[int], layer
                                     _dims(dims), C.c_int(dtype), C.c_int(layer), _ptr(out), _stream()))
 
 
-def spmm(g: Graph, T: torch.Tensor, out: torch.Tensor, width: Optional[int] = None, dtype: int = F32) -> None:
+def spmm_workspace(g: Graph, width: int) -> Optional[torch.Tensor]:
+    b = C.c_size_t()
+    _check(lib().gad_spmm_workspace_bytes(g.handle, C.c_int32(width), C.byref(b)))
+    return torch.empty(b.value, dtype=torch.uint8, device="cuda") if b.value else None
+
+
+def spmm(g: Graph, T: torch.Tensor, out: torch.Tensor, width: Optional[int] = None, dtype: int = F32,
+         workspace: Optional[torch.Tensor] = None) -> None:
     """out = A~ T for 2-D row-major T, out (leading dimensions = their second sizes)."""
     width = int(width if width is not None else T.shape[1])
+    ws = workspace if workspace is not None else spmm_workspace(g, width)
     _check(lib().gad_spmm(g.handle, _ptr(T), C.c_int64(T.shape[1]), _ptr(out), C.c_int64(out.shape[1]),
-                          C.c_int32(width), C.c_int(dtype), _stream()))
+                          C.c_int32(width), C.c_int(dtype), _ptr(ws), C.c_size_t(0 if ws is None else ws.numel()),
+                          _stream()))
+
+
+def gemm_workspace(M: int, K: int, N: int) -> torch.Tensor:
+    b = C.c_size_t()
+    _check(lib().gad_gemm_workspace_bytes(C.c_int64(M), C.c_int32(K), C.c_int32(N), C.byref(b)))
+    return torch.empty(max(b.value, 256), dtype=torch.uint8, device="cuda")
+
+
+def gemm_w(A: torch.Tensor, W: torch.Tensor, out: torch.Tensor, transpose_w: bool = False,
+           workspace: Optional[torch.Tensor] = None, K: Optional[int] = None) -> None:
+    """out = A[:, :K] W  (or A[:, :K] W^T); A and out are 2-D row-major float32 or bfloat16 (the same type), W float32."""
+    dtype = F32 if A.dtype == torch.float32 else BF16
+    _dev(A, torch.float32 if dtype == F32 else torch.bfloat16, "A")
+    _dev(out, A.dtype, "out")
+    _dev(W, torch.float32, "W")
+    k = W.shape[1] if transpose_w else W.shape[0]
+    n = W.shape[0] if transpose_w else W.shape[1]
+    ws = workspace if workspace is not None else gemm_workspace(A.shape[0], k, n)
+    _check(lib().gad_gemm_w(_ptr(A), C.c_int64(A.shape[1]), _ptr(W), C.c_int32(W.shape[0]), C.c_int32(W.shape[1]),
+                            C.c_int(1 if transpose_w else 0), _ptr(out), C.c_int64(out.shape[1]), C.c_int64(A.shape[0]),
+                            C.c_int(dtype), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+
+
+def gemm_tn(A: torch.Tensor, G: torch.Tensor, out: torch.Tensor, K: Optional[int] = None, N: Optional[int] = None,
+            workspace: Optional[torch.Tensor] = None) -> None:
+    """out[K x N] (float32) = A[:, :K]^T G[:, :N]; A and G are 2-D row-major float32 or bfloat16 (the same type)."""
+    dtype = F32 if A.dtype == torch.float32 else BF16
+    _dev(A, torch.float32 if dtype == F32 else torch.bfloat16, "A")
+    _dev(G, A.dtype, "G")
+    _dev(out, torch.float32, "out")
+    k = int(K if K is not None else A.shape[1])
+    n = int(N if N is not None else G.shape[1])
+    ws = workspace if workspace is not None else gemm_workspace(A.shape[0], k, n)
+    _check(lib().gad_gemm_tn(_ptr(A), C.c_int64(A.shape[1]), _ptr(G), C.c_int64(G.shape[1]), _ptr(out),
+                             C.c_int64(A.shape[0]), C.c_int32(k), C.c_int32(n), C.c_int(dtype), _ptr(ws),
+                             C.c_size_t(ws.numel()), _stream()))
 
 
 def subgraph_variance(g: Graph, V: torch.Tensor, beta: float, out3: torch.Tensor,

@@ -1,0 +1,123 @@
+"""The dense contractions of the GCN step on their own, through the C ABI (gad_gemm_w, gad_gemm_tn), against a
+float64 matrix product of the same inputs: ragged shapes that span several tiles and a tail, both storage types,
+unaligned leading dimensions (the element-wise loader), padding columns that hold NaN (must never be read into a
+result), several slabs of the reduction over the nodes.
+
+bfloat16 storage: the inputs are rounded to bfloat16 once and both sides start from those values.  Where the
+weights are themselves representable in bfloat16 the only error left is float32 accumulation (tight bound);
+with general float32 weights the kernel's own rounding of W to bfloat16 adds 2^-9 per weight (storage bound).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2110_02987_amd import workloads as wl
+from tests.test_gpu_parity import TOL, TOL_BF16, bf16_dev, dev, gad, rel_err  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+
+def _node_matrix(rng, m, width, ld, bf16):
+    """[m x ld] host float32 values (what both sides see) and the device tensor; columns >= width hold NaN."""
+    a = rng.standard_normal((m, ld)).astype(np.float32)
+    if bf16:
+        a = wl.bf16_to_f32(wl.to_bf16_rne(a))
+    full = a.copy()
+    full[:, width:] = np.nan
+    if bf16:
+        bits = wl.to_bf16_rne(np.nan_to_num(full, nan=0.0))
+        bits[:, width:] = 0x7FC0                                   # bfloat16 quiet NaN
+        d = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+    else:
+        d = dev(full)
+    return a[:, :width], d
+
+
+SHAPES_W = [  # M, K, N, lda, ldc
+    (1, 1, 1, 1, 1), (127, 5, 3, 5, 3), (129, 47, 65, 48, 80), (1000, 100, 256, 112, 256), (5000, 256, 47, 256, 48),
+    (777, 602, 200, 608, 208), (4096, 128, 512, 128, 512), (2500, 512, 64, 512, 64), (3001, 33, 130, 33, 130),
+    (640, 64, 600, 72, 600),
+]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("transpose_w", [False, True])
+@pytest.mark.parametrize("M,K,N,lda,ldc", SHAPES_W)
+def test_gemm_w(gad, M, K, N, lda, ldc, transpose_w, bf16):
+    rng = np.random.default_rng(M * 31 + K * 7 + N)
+    A, Ad = _node_matrix(rng, M, K, lda, bf16)
+    W = rng.uniform(-0.3, 0.3, (N, K) if transpose_w else (K, N)).astype(np.float32)
+    out = torch.full((M, ldc), float("nan"), device="cuda", dtype=torch.bfloat16 if bf16 else torch.float32)
+    gad.gemm_w(Ad, dev(W), out, transpose_w)
+    W64 = W.astype(np.float64)
+    exp = A.astype(np.float64) @ (W64.T if transpose_w else W64)
+    got = out.float().cpu().numpy()
+    assert rel_err(got[:, :N], exp) < (TOL_BF16 if bf16 else TOL)
+    assert np.all(np.isnan(got[:, N:]))                 # padding columns of the output are never written
+    if bf16:
+        # weights already representable in bfloat16: what remains is float32 accumulation and one output rounding
+        Wb = wl.bf16_to_f32(wl.to_bf16_rne(W))
+        gad.gemm_w(Ad, dev(Wb), out, transpose_w)
+        Wb64 = Wb.astype(np.float64)
+        exp = A.astype(np.float64) @ (Wb64.T if transpose_w else Wb64)
+        assert rel_err(out.float().cpu().numpy()[:, :N], exp) < 4e-3
+
+
+def test_gemm_w_bf16_is_float32_accumulation(gad):
+    """Exact check of the bfloat16 matrix instruction's use: small integers are exact in bfloat16 and their products
+    and sums are exact in float32, so the float32 output must equal the integer product bit for bit."""
+    rng = np.random.default_rng(0)
+    M, K, N = 300, 200, 136
+    A = rng.integers(-8, 9, (M, K)).astype(np.float32)
+    W = rng.integers(-8, 9, (K, N)).astype(np.float32)
+    Ad, _ = bf16_dev(A)
+    ws = gad.gemm_workspace(M, K, N)
+    # gad_gemm_tn writes float32: the integer product must come out exactly
+    out = torch.empty((K, N), device="cuda")
+    G = rng.integers(-8, 9, (M, N)).astype(np.float32)
+    Gd, _ = bf16_dev(G)
+    gad.gemm_tn(Ad, Gd, out, workspace=ws)
+    assert np.array_equal(out.cpu().numpy(), A.T @ G)
+    # gad_gemm_w writes bfloat16: the exact integer product rounded once
+    outb = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+    gad.gemm_w(Ad, dev(W), outb, False, ws)
+    exp = wl.bf16_to_f32(wl.to_bf16_rne(A @ W))
+    assert np.array_equal(outb.float().cpu().numpy(), exp)
+
+
+SHAPES_TN = [  # M, K, N, lda, ldg
+    (1, 1, 1, 1, 1), (63, 5, 3, 5, 3), (1000, 47, 65, 48, 80), (70_000, 100, 256, 112, 256), (33_333, 256, 47, 256, 48),
+    (5000, 602, 41, 608, 48), (20_000, 128, 512, 128, 512), (9001, 130, 129, 130, 129), (150_000, 64, 16, 64, 16),
+]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("M,K,N,lda,ldg", SHAPES_TN)
+def test_gemm_tn(gad, M, K, N, lda, ldg, bf16):
+    rng = np.random.default_rng(M + K * 13 + N * 5)
+    A, Ad = _node_matrix(rng, M, K, lda, bf16)
+    G, Gd = _node_matrix(rng, M, N, ldg, bf16)
+    out = torch.full((K, N), float("nan"), device="cuda")
+    gad.gemm_tn(Ad, Gd, out, K, N)
+    exp = A.astype(np.float64).T @ G.astype(np.float64)
+    got = out.cpu().numpy()
+    # inputs are identical on both sides, so only float32 accumulation separates them (either storage type)
+    assert rel_err(got, exp) < TOL
+    out2 = torch.empty_like(out)
+    gad.gemm_tn(Ad, Gd, out2, K, N)
+    assert torch.equal(out, out2)                        # fixed summation order: reproducible bit for bit
+
+
+def test_gemm_errors(gad):
+    A = torch.zeros((8, 8), device="cuda")
+    W = torch.zeros((8, 8), device="cuda")
+    ws = gad.gemm_workspace(8, 8, 8)
+    with pytest.raises(gad.GadError) as e:
+        gad.gemm_w(A, W, torch.zeros((8, 4), device="cuda"), False, ws)        # ldc < N
+    assert e.value.status == -2
+    with pytest.raises(gad.GadError) as e:
+        gad.gemm_tn(A, A, torch.zeros((8, 8), device="cuda"), 8, 8, ws[8:])    # misaligned workspace
+    assert e.value.status == -5
+    with pytest.raises(gad.GadError) as e:
+        gad.gemm_workspace(8, 0, 8)
+    assert e.value.status == -2
