@@ -7,10 +7,13 @@
 // (arXiv 2110.02987, Section 3.3: Eq. 7 forward; backward step of Algorithm 2.)
 //
 // Block tile 128 x 128, four wave64s in a 2 x 2 arrangement, each wave a 64 x 64 sub-tile made of
-// 2 x 2 MFMA 32x32 accumulators.  Both operands are staged through LDS with the reduction index
-// leading (As[kk][i], Bs[kk][j]) so that a fragment read is 64 consecutive floats; the next tile is
-// fetched from global memory into registers while the current one is multiplied (double-buffered LDS).
-// This file holds the float32 storage path; bfloat16 storage runs on the bfloat16 matrix instruction (gemm_bf16.hip).
+// 2 x 2 MFMA 32x32 accumulators; outputs of at most 64 columns (the class logits, their gradient) use a
+// 128 x 64 block tile (2 x 1 accumulators per wave) so that matrix instructions are not spent on padding.
+// Both operands are staged through LDS with the reduction index leading (As[kk][i], Bs[kk][j]) so that a
+// fragment read is 64 consecutive floats; the next tile is fetched from global memory into registers while
+// the current one is multiplied (double-buffered LDS).
+// This file holds the float32 storage path; bfloat16 storage runs on the bfloat16 matrix instruction
+// (gemm_bf16.hip).
 #include "dtype.h"
 #include "gad_internal.h"
 
@@ -19,32 +22,34 @@ namespace {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int BM = 128, BK = 16;          // block rows; depth of one LDS tile (block columns: 64 TNW)
 constexpr int LDS_LD = BM + 4;   // row stride of As / Bs in floats (16-byte aligned rows)
 
+// One k-slice of both operands; TNW = accumulators per wave along N (block tile 128 x 64 TNW).
+template <int TNW>
 struct Tile {
   float a[BK][LDS_LD];
-  float b[BK][LDS_LD];
+  float b[BK][64 * TNW + 4];
 };
 
 // acc[tm][tn] += As[:, 64*wm + 32*tm .. ]^T Bs[:, 64*wn + 32*tn ..]
 // (Reading all fragments of a tile ahead of the MFMAs, or a 32-deep tile at two blocks per CU, both measured
 // slower than this per-k-step form at three blocks per CU.)
-__device__ __forceinline__ void mma_tile(const Tile& t, int wm, int wn, v16f (&acc)[2][2]) {
+template <int TNW>
+__device__ __forceinline__ void mma_tile(const Tile<TNW>& t, int wm, int wn, v16f (&acc)[2][TNW]) {
   const int lane = threadIdx.x & 63;
   const int i = lane & 31, half = lane >> 5;
 #pragma unroll
   for (int k0 = 0; k0 < BK; k0 += 2) {
-    float a[2], b[2];
+    float a[2], b[TNW];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      a[q] = t.a[k0 + half][wm * 64 + q * 32 + i];
-      b[q] = t.b[k0 + half][wn * 64 + q * 32 + i];
-    }
+    for (int q = 0; q < 2; ++q) a[q] = t.a[k0 + half][wm * 64 + q * 32 + i];
+#pragma unroll
+    for (int q = 0; q < TNW; ++q) b[q] = t.b[k0 + half][wn * 32 * TNW + q * 32 + i];
 #pragma unroll
     for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
-      for (int tn = 0; tn < 2; ++tn)
+      for (int tn = 0; tn < TNW; ++tn)
         acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
   }
 }
@@ -75,7 +80,8 @@ __device__ __forceinline__ void load8(const T* __restrict__ base, int64_t ld, in
   }
 }
 
-__device__ __forceinline__ void store_direct(float (*dst)[LDS_LD], int kk, int seg, const float (&r)[8]) {
+template <int LD>
+__device__ __forceinline__ void store_direct(float (*dst)[LD], int kk, int seg, const float (&r)[8]) {
   *reinterpret_cast<float4*>(&dst[kk][seg]) = make_float4(r[0], r[1], r[2], r[3]);
   *reinterpret_cast<float4*>(&dst[kk][seg + 4]) = make_float4(r[4], r[5], r[6], r[7]);
 }
@@ -85,16 +91,16 @@ __device__ __forceinline__ void store_transposed(float (*dst)[LDS_LD], int i, in
   for (int q = 0; q < 8; ++q) dst[kseg + q][i] = r[q];
 }
 
-template <int EPI, typename TC, typename TX>
-__device__ __forceinline__ void store_acc(const v16f (&acc)[2][2], TC* __restrict__ C, int64_t ldc, int64_t row0,
+template <int EPI, int TNW, typename TC, typename TX>
+__device__ __forceinline__ void store_acc(const v16f (&acc)[2][TNW], TC* __restrict__ C, int64_t ldc, int64_t row0,
                                           int col0, int64_t M, int N, int wm, int wn, float slope,
                                           const TX* __restrict__ aux, int64_t ldaux) {
   const int lane = threadIdx.x & 63;
 #pragma unroll
   for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
-    for (int tn = 0; tn < 2; ++tn) {
-      const int col = col0 + wn * 64 + tn * 32 + (lane & 31);
+    for (int tn = 0; tn < TNW; ++tn) {
+      const int col = col0 + wn * 32 * TNW + tn * 32 + (lane & 31);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int64_t row = row0 + wm * 64 + tm * 32 + acc_row(r, lane);
@@ -108,44 +114,39 @@ __device__ __forceinline__ void store_acc(const v16f (&acc)[2][2], TC* __restric
     }
 }
 
-constexpr int NP = BK / 16;      // 8-element pieces each thread moves per operand and tile
+static_assert(BM * BK / 8 == 256, "one 8-float piece of A per thread and tile");
 
 // ---- NN ----------------------------------------------------------------------------------------
-// grid: x = row tile of C (128 rows), y = column tile (128 columns).
-template <int EPI, typename TA, typename TC>
+// grid: x = row tile of C (128 rows), y = column tile (64 TNW columns).
+template <int EPI, int TNW, typename TA, typename TC>
 __global__ __launch_bounds__(256) void gemm_nn_kernel(const TA* __restrict__ A, int64_t lda,
                                                       const float* __restrict__ B, int64_t ldb, TC* __restrict__ C,
                                                       int64_t ldc, int64_t M, int N, int K, bool a_vec, bool b_vec,
                                                       float slope, const TA* __restrict__ aux, int64_t ldaux) {
-  __shared__ Tile tiles[2];
+  constexpr int BNW = 64 * TNW, SEGB = BNW / 8;      // block columns; 8-float pieces per B row
+  __shared__ Tile<TNW> tiles[2];
   const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
   const int64_t row0 = (int64_t)blockIdx.x * BM;
-  const int col0 = blockIdx.y * BN;
-  v16f acc[2][2];
+  const int col0 = blockIdx.y * BNW;
+  v16f acc[2][TNW];
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int y = 0; y < 2; ++y)
+    for (int y = 0; y < TNW; ++y)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-  // piece pi = t + 256 j:  A: row pi / (BK/8), k segment (pi % (BK/8)) * 8;  B: k row pi / 16, column segment (pi % 16) * 8
-  float ra[NP][8], rb[NP][8];
+  // piece t of A: row t / (BK/8), k segment (t % (BK/8)) * 8;  piece t of B (t < BK * SEGB): k row t / SEGB,
+  // column segment (t % SEGB) * 8
+  const bool has_b = t < BK * SEGB;
+  float ra[8], rb[8];
   auto fetch = [&](int k1) {
-#pragma unroll
-    for (int j = 0; j < NP; ++j) {
-      const int pi = t + 256 * j;
-      load8<TA>(A, lda, row0 + pi / (BK / 8), M, k1 + (pi % (BK / 8)) * 8, K, a_vec, ra[j]);
-      load8<float>(B, ldb, k1 + pi / 16, K, col0 + (pi % 16) * 8, N, b_vec, rb[j]);
-    }
+    load8<TA>(A, lda, row0 + t / (BK / 8), M, k1 + (t % (BK / 8)) * 8, K, a_vec, ra);
+    if (has_b) load8<float>(B, ldb, k1 + t / SEGB, K, col0 + (t % SEGB) * 8, N, b_vec, rb);
   };
-  auto stage = [&](Tile& tile) {
-#pragma unroll
-    for (int j = 0; j < NP; ++j) {
-      const int pi = t + 256 * j;
-      store_transposed(tile.a, pi / (BK / 8), (pi % (BK / 8)) * 8, ra[j]);
-      store_direct(tile.b, pi / 16, (pi % 16) * 8, rb[j]);
-    }
+  auto stage = [&](Tile<TNW>& tile) {
+    store_transposed(tile.a, t / (BK / 8), (t % (BK / 8)) * 8, ra);
+    if (has_b) store_direct(tile.b, t / SEGB, (t % SEGB) * 8, rb);
   };
   fetch(0);
   stage(tiles[0]);
@@ -154,50 +155,44 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const TA* __restrict__ A, 
   for (int kt = 0; kt < n_kt; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < n_kt) fetch((kt + 1) * BK);
-    mma_tile(tiles[cur], wm, wn, acc);
+    mma_tile<TNW>(tiles[cur], wm, wn, acc);
     if (kt + 1 < n_kt) stage(tiles[cur ^ 1]);
     __syncthreads();
   }
-  store_acc<EPI, TC, TA>(acc, C, ldc, row0, col0, M, N, wm, wn, slope, aux, ldaux);
+  store_acc<EPI, TNW, TC, TA>(acc, C, ldc, row0, col0, M, N, wm, wn, slope, aux, ldaux);
 }
 
 // ---- TN ----------------------------------------------------------------------------------------
-// grid: x = output tile (tiles_k * tiles_n), y = slab of M.  Writes P[slab][K x N] (ld N).
-template <typename TA>
+// grid: x = output tile (tiles_k * tiles_n) of 128 x 64 TNW, y = slab of M.  Writes P[slab][K x N] (ld N).
+template <int TNW, typename TA>
 __global__ __launch_bounds__(256) void gemm_tn_kernel(const TA* __restrict__ A, int64_t lda, const TA* __restrict__ G,
                                                       int64_t ldg, float* __restrict__ P, int64_t M, int K, int N,
                                                       int64_t slab_rows, int tiles_n, bool a_vec, bool g_vec) {
-  __shared__ Tile tiles[2];
+  constexpr int BNW = 64 * TNW, SEGB = BNW / 8;
+  __shared__ Tile<TNW> tiles[2];
   const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
-  const int k0 = (blockIdx.x / tiles_n) * BM;   // output row block (columns of A)
-  const int n0 = (blockIdx.x % tiles_n) * BN;   // output column block (columns of G)
+  const int k0 = (blockIdx.x / tiles_n) * BM;    // output row block (columns of A)
+  const int n0 = (blockIdx.x % tiles_n) * BNW;   // output column block (columns of G)
   const int64_t m_begin = (int64_t)blockIdx.y * slab_rows;
   const int64_t m_end = m_begin + slab_rows < M ? m_begin + slab_rows : M;
-  v16f acc[2][2];
+  v16f acc[2][TNW];
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int y = 0; y < 2; ++y)
+    for (int y = 0; y < TNW; ++y)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-  // piece pi = t + 256 j: reduction row pi / 16, column segment (pi % 16) * 8, for both operands
-  float ra[NP][8], rb[NP][8];
+  // piece t: reduction row t / 16, column segment (t % 16) * 8 of A; row t / SEGB, segment (t % SEGB) * 8 of G
+  const bool has_b = t < BK * SEGB;
+  float ra[8], rb[8];
   auto fetch = [&](int64_t m1) {
-#pragma unroll
-    for (int j = 0; j < NP; ++j) {
-      const int pi = t + 256 * j;
-      load8<TA>(A, lda, m1 + pi / 16, m_end, k0 + (pi % 16) * 8, K, a_vec, ra[j]);
-      load8<TA>(G, ldg, m1 + pi / 16, m_end, n0 + (pi % 16) * 8, N, g_vec, rb[j]);
-    }
+    load8<TA>(A, lda, m1 + t / 16, m_end, k0 + (t % 16) * 8, K, a_vec, ra);
+    if (has_b) load8<TA>(G, ldg, m1 + t / SEGB, m_end, n0 + (t % SEGB) * 8, N, g_vec, rb);
   };
-  auto stage = [&](Tile& tile) {
-#pragma unroll
-    for (int j = 0; j < NP; ++j) {
-      const int pi = t + 256 * j;
-      store_direct(tile.a, pi / 16, (pi % 16) * 8, ra[j]);
-      store_direct(tile.b, pi / 16, (pi % 16) * 8, rb[j]);
-    }
+  auto stage = [&](Tile<TNW>& tile) {
+    store_direct(tile.a, t / 16, (t % 16) * 8, ra);
+    if (has_b) store_direct(tile.b, t / SEGB, (t % SEGB) * 8, rb);
   };
   fetch(m_begin);
   stage(tiles[0]);
@@ -206,12 +201,12 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const TA* __restrict__ A, 
   for (int64_t mt = 0; mt < n_mt; ++mt) {
     const int cur = (int)(mt & 1);
     if (mt + 1 < n_mt) fetch(m_begin + (mt + 1) * BK);
-    mma_tile(tiles[cur], wm, wn, acc);
+    mma_tile<TNW>(tiles[cur], wm, wn, acc);
     if (mt + 1 < n_mt) stage(tiles[cur ^ 1]);
     __syncthreads();
   }
   float* Pslab = P + (int64_t)blockIdx.y * K * N;
-  store_acc<EPI_NONE, float, float>(acc, Pslab, N, k0, n0, K, N, wm, wn, 0.f, nullptr, 0);
+  store_acc<EPI_NONE, TNW, float, float>(acc, Pslab, N, k0, n0, K, N, wm, wn, 0.f, nullptr, 0);
 }
 
 __global__ void reduce_slabs(const float* __restrict__ P, int n_slabs, int64_t elems, int N, float* __restrict__ C,
@@ -240,8 +235,12 @@ bool vec_ok(const T* p, int64_t ld) {
   return (ld % (16 / (int)sizeof(T)) == 0) && ((reinterpret_cast<uintptr_t>(p) & 15u) == 0);
 }
 
+// Block columns: 64 when the output has at most 64 columns (a 128-wide tile would spend most of its matrix
+// instructions on padding), else 128.
+inline int block_cols(int N) { return N <= 64 ? 64 : 128; }
+
 void tn_split(int64_t M, int K, int N, int* n_slabs, int64_t* slab_rows) {
-  const int64_t tiles = ceil_div(K, BM) * ceil_div(N, BN);
+  const int64_t tiles = ceil_div(K, BM) * ceil_div(N, block_cols(N));
   int64_t want = ceil_div(512, tiles);                // ~2 blocks per CU over the whole grid
   const int64_t max_slabs = ceil_div(M, 512);         // at least 512 reduction rows per slab
   if (want > max_slabs) want = max_slabs;
@@ -250,22 +249,22 @@ void tn_split(int64_t M, int K, int N, int* n_slabs, int64_t* slab_rows) {
   *n_slabs = (int)ceil_div(M, *slab_rows);
 }
 
-template <typename TA, typename TC>
-int gemm_nn_typed(const TA* A, int64_t lda, const float* B, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
-                  const Epi& e, hipStream_t s) {
+template <int TNW, typename TA, typename TC>
+int gemm_nn_launch(const TA* A, int64_t lda, const float* B, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
+                   const Epi& e, hipStream_t s) {
   const TA* aux = static_cast<const TA*>(e.aux);
   const int64_t ldaux = e.ldaux;
-  const dim3 grid((unsigned)ceil_div(M, BM), (unsigned)ceil_div(N, BN));
+  const dim3 grid((unsigned)ceil_div(M, BM), (unsigned)ceil_div(N, 64 * TNW));
   const bool av = vec_ok(A, lda), bv = vec_ok(B, ldb);
   switch (e.kind) {
     case EPI_NONE:
-      gemm_nn_kernel<EPI_NONE, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, e.slope, aux, ldaux);
+      gemm_nn_kernel<EPI_NONE, TNW, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, e.slope, aux, ldaux);
       break;
     case EPI_RELU:
-      gemm_nn_kernel<EPI_RELU, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, e.slope, aux, ldaux);
+      gemm_nn_kernel<EPI_RELU, TNW, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, e.slope, aux, ldaux);
       break;
     case EPI_MASK:
-      gemm_nn_kernel<EPI_MASK, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, e.slope, aux, ldaux);
+      gemm_nn_kernel<EPI_MASK, TNW, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, e.slope, aux, ldaux);
       break;
     default:
       return set_error(GAD_ERR_UNSUPPORTED, "unknown epilogue %d", e.kind);
@@ -274,16 +273,27 @@ int gemm_nn_typed(const TA* A, int64_t lda, const float* B, int64_t ldb, TC* C, 
   return GAD_OK;
 }
 
+template <typename TA, typename TC>
+int gemm_nn_typed(const TA* A, int64_t lda, const float* B, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
+                  const Epi& e, hipStream_t s) {
+  if (block_cols(N) == 64) return gemm_nn_launch<1, TA, TC>(A, lda, B, ldb, C, ldc, M, N, K, e, s);
+  return gemm_nn_launch<2, TA, TC>(A, lda, B, ldb, C, ldc, M, N, K, e, s);
+}
+
 template <typename TA>
 int gemm_tn_typed(const TA* A, int64_t lda, const TA* G, int64_t ldg, float* C, int64_t ldc, int64_t M, int K, int N,
                   float* partials, hipStream_t s) {
   int n_slabs;
   int64_t slab_rows;
   tn_split(M, K, N, &n_slabs, &slab_rows);
-  const int tiles_n = (int)ceil_div(N, BN);
+  const int tiles_n = (int)ceil_div(N, block_cols(N));
   const dim3 grid((unsigned)(ceil_div(K, BM) * tiles_n), (unsigned)n_slabs);
-  gemm_tn_kernel<TA><<<grid, 256, 0, s>>>(A, lda, G, ldg, partials, M, K, N, slab_rows, tiles_n, vec_ok(A, lda),
-                                          vec_ok(G, ldg));
+  if (block_cols(N) == 64)
+    gemm_tn_kernel<1, TA><<<grid, 256, 0, s>>>(A, lda, G, ldg, partials, M, K, N, slab_rows, tiles_n, vec_ok(A, lda),
+                                               vec_ok(G, ldg));
+  else
+    gemm_tn_kernel<2, TA><<<grid, 256, 0, s>>>(A, lda, G, ldg, partials, M, K, N, slab_rows, tiles_n, vec_ok(A, lda),
+                                               vec_ok(G, ldg));
   GAD_LAUNCH_CHECK();
   const int64_t elems = (int64_t)K * N;
   reduce_slabs<<<(unsigned)ceil_div(elems, 256), 256, 0, s>>>(partials, n_slabs, elems, N, C, ldc);
