@@ -180,3 +180,24 @@ double t1_deviation(const double* V, int64_t n, int64_t F, double* r /* [n] */) 
   free(mean);
   return n > 0 ? tot / (double)n : 0.0;
 }
+
+/* Eq. 14 with the distance inside the sum: sum_{i<j} deg_i deg_j / (||v_i - v_j||_2 + beta), to be divided by
+ * (sum deg)^2 by the caller.  Plain double loop over the pairs (rows of the pair matrix shared among threads);
+ * V: [n x F] float64. */
+double t1_pair_sum(const int32_t* deg, const double* V, int64_t n, int64_t F, double beta) {
+  double tot = 0.0;
+#pragma omp parallel for schedule(dynamic, 16) reduction(+ : tot)
+  for (int64_t i = 0; i < n; ++i) {
+    const double* vi = V + i * F;
+    double row = 0.0;
+    for (int64_t j = i + 1; j < n; ++j) {
+      const double* vj = V + j * F;
+      double d2 = 0.0;
+      for (int64_t f = 0; f < F; ++f) { double d = vi[f] - vj[f]; d2 += d * d; }
+      row += (double)deg[j] / (sqrt(d2) + beta);
+    }
+    tot += (double)deg[i] * row;
+  }
+  return tot;
+}
+

@@ -157,6 +157,18 @@ def zeta(g: Graph, V, beta=1.0):
     return spp / (D + beta), spp, float(var), r
 
 
+def zeta_pairs(g: Graph, V, beta=1.0):
+    """Eq. 14, per-pair reading: sum_{i<j} p_i p_j / (||v_i - v_j|| + beta), p_i = deg_i / sum(deg).  O(n^2 F)."""
+    s1 = int(g.deg.astype(np.int64).sum())
+    if s1 == 0:
+        return 0.0
+    V = np.ascontiguousarray(V, dtype=np.float64)
+    lib().t1_pair_sum.restype = C.c_double
+    tot = lib().t1_pair_sum(_p(g.deg, C.c_int32), _p(V, C.c_double), C.c_int64(V.shape[0]), C.c_int64(V.shape[1]),
+                            C.c_double(beta))
+    return float(tot) / (float(s1) * float(s1))
+
+
 def weighted_consensus(bufs, zetas):
     """Eq. 15."""
     z = np.asarray(zetas, dtype=np.float64)

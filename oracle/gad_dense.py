@@ -34,6 +34,7 @@ unless marked "parity unpinned"):
   separately"), which equals the root-mean-square Euclidean distance over all ordered pairs.
   zeta = S_pp / (D + beta).  (The choice aggregate-vs-per-pair distance is parity unpinned: the
   paper's only example has d = 0, where both agree.)
+  The per-pair reading, sum_{i<j} p_i p_j / (||v_i - v_j|| + beta), is `zeta_pairs`.
 * An edgeless subgraph (sum(deg) = 0) gets S_pp = 0 and zeta = 0 (convention; parity unpinned).
 * Eq. 15 is printed with a spurious outer sum; read as sum_i zeta_i B_i / sum_j zeta_j.
 """
@@ -167,6 +168,25 @@ def zeta(deg, V, beta=1.0):
     spp = pair_probability_sum(deg)
     var, D, r = aggregate_distance(V)
     return spp / (D + beta), spp, var, r
+
+
+def zeta_pairs(deg, V, beta=1.0):
+    """Eq. 14 under its other reading: the distance stays inside the sum, one term per unordered pair,
+        zeta_pair = sum_{i<j} p_i p_j / (||v_i - v_j||_2 + beta),   p_i = deg_i / sum(deg).
+    (The paper prints the sum over the numerator only and leaves i, j free in the denominator; with identical
+    node vectors, as in its worked example, this and the aggregate reading of `zeta` coincide.)
+    Literal double loop over the pairs, float64; O(n^2 F).  An edgeless subgraph gives 0."""
+    deg = np.asarray(deg, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    s = deg.sum()
+    if s == 0:
+        return 0.0
+    p = deg / s
+    tot = 0.0
+    for i in range(p.size - 1):
+        d = np.sqrt(((V[i + 1:] - V[i]) ** 2).sum(axis=1))
+        tot += p[i] * float(np.sum(p[i + 1:] / (d + beta)))
+    return float(tot)
 
 
 def weighted_consensus(bufs, zetas):

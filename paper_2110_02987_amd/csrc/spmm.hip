@@ -124,10 +124,50 @@ __global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ r
   }
 }
 
-// One block per long row: adds the row's chunk sums in a fixed order (four contiguous runs of chunks, one per
-// wave, each added in chunk order; then the four run sums in run order), 64 columns at a time.
+// Adds the chunk sums of the long rows; the order of the additions depends only on the row's chunk count k.
+// Rows with k <= kWaveReduce: one wave per (row, slab of 256 columns) adds the chunks in chunk order.
+// Rows with more chunks: one block per (row, slab of 64 columns); the chunks are cut into four contiguous runs,
+// one per wave, each added in chunk order, then the four run sums are added in run order.
+constexpr int kWaveReduce = 64;
+
 template <typename TI, typename TO>
-__global__ __launch_bounds__(256) void spmm_long_reduce(const int64_t* __restrict__ rowptr,
+__global__ __launch_bounds__(256) void spmm_reduce_few(const int64_t* __restrict__ rowptr,
+                                                       const float* __restrict__ dinv,
+                                                       const int32_t* __restrict__ long_row,
+                                                       const int32_t* __restrict__ long_first, int n_long,
+                                                       const float* __restrict__ partial, int64_t ldp, int width,
+                                                       TO* __restrict__ out, int64_t ldo, int epi, float slope,
+                                                       const TI* __restrict__ aux, int64_t ldaux) {
+  const int slot = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (slot >= n_long) return;
+  const int64_t i = long_row[slot];
+  const int64_t k = (rowptr[i + 1] - rowptr[i] + kLongRow - 1) / kLongRow;
+  if (k > kWaveReduce) return;
+  const int c = blockIdx.y * 256 + (threadIdx.x & 63) * 4;
+  if (c >= width) return;
+  const float* p = partial + (int64_t)long_first[slot] * ldp + c;      // ldp is a multiple of 4: 16-byte aligned
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  int64_t q = 0;
+  for (; q + 8 <= k; q += 8) {
+    float4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4*>(p + (q + u) * ldp);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+  }
+  for (; q < k; ++q) {
+    const float4 v = *reinterpret_cast<const float4*>(p + q * ldp);
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  const float di = dinv[i];
+  const float r[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (c + u < width) store_elem<TI, TO>(out, ldo, i, c + u, di * r[u], epi, slope, aux, ldaux);
+}
+
+template <typename TI, typename TO>
+__global__ __launch_bounds__(256) void spmm_reduce_many(const int64_t* __restrict__ rowptr,
                                                         const float* __restrict__ dinv,
                                                         const int32_t* __restrict__ long_row,
                                                         const int32_t* __restrict__ long_first,
@@ -136,23 +176,30 @@ __global__ __launch_bounds__(256) void spmm_long_reduce(const int64_t* __restric
                                                         const TI* __restrict__ aux, int64_t ldaux) {
   __shared__ float run_sum[4][64];
   const int64_t i = long_row[blockIdx.x];
-  const int64_t first = long_first[blockIdx.x];
   const int64_t k = (rowptr[i + 1] - rowptr[i] + kLongRow - 1) / kLongRow;
+  if (k <= kWaveReduce) return;                       // block-uniform
+  const int64_t first = long_first[blockIdx.x];
   const int lane = threadIdx.x & 63, run = threadIdx.x >> 6;
   const int64_t q0 = first + run * k / 4, q1 = first + (run + 1) * k / 4;
-  const float di = dinv[i];
-  for (int c0 = 0; c0 < width; c0 += 64) {
-    const int c = c0 + lane;
-    float s = 0.f;
-    if (c < width)
-      for (int64_t q = q0; q < q1; ++q) s += partial[q * ldp + c];
-    run_sum[run][lane] = s;
-    __syncthreads();
-    if (run == 0 && c < width) {
-      const float v = ((run_sum[0][lane] + run_sum[1][lane]) + run_sum[2][lane]) + run_sum[3][lane];
-      store_elem<TI, TO>(out, ldo, i, c, di * v, epi, slope, aux, ldaux);
+  const int c = blockIdx.y * 64 + lane;
+  float s = 0.f;
+  if (c < width) {
+    const float* p = partial + c;
+    int64_t q = q0;
+    for (; q + 8 <= q1; q += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = p[(q + u) * ldp];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
     }
-    __syncthreads();
+    for (; q < q1; ++q) s += p[q * ldp];
+  }
+  run_sum[run][lane] = s;
+  __syncthreads();
+  if (run == 0 && c < width) {
+    const float v = ((run_sum[0][lane] + run_sum[1][lane]) + run_sum[2][lane]) + run_sum[3][lane];
+    store_elem<TI, TO>(out, ldo, i, c, dinv[i] * v, epi, slope, aux, ldaux);
   }
 }
 
@@ -160,18 +207,22 @@ template <int LPR, int V, typename TI, typename TO>
 int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, int width, const Epi& e, float* partial,
            hipStream_t s) {
   const TI* aux = static_cast<const TI*>(e.aux);
+  const int64_t ldp = round_up(width, 4);
   const unsigned row_blocks = (unsigned)ceil_div(g->n_short, 4);
   const unsigned chunk_blocks = (unsigned)ceil_div(g->n_chunks, 4);
   const dim3 grid(chunk_blocks + row_blocks, (unsigned)ceil_div(width, LPR * V));
   spmm_kernel<LPR, V, TI, TO><<<grid, 256, 0, s>>>(g->rowptr, g->colidx, g->dinv, T, ldt, out, ldo, width, g->n_short,
                                                    g->row_order, e.kind, e.slope, aux, e.ldaux, (int)chunk_blocks,
                                                    g->chunk_perm, g->chunk_row, g->chunk_begin, g->n_chunks, partial,
-                                                   (int64_t)width);
+                                                   ldp);
   GAD_LAUNCH_CHECK();
   if (g->n_long > 0) {
-    spmm_long_reduce<TI, TO><<<(unsigned)g->n_long, 256, 0, s>>>(g->rowptr, g->dinv, g->long_row, g->long_first, partial,
-                                                                 (int64_t)width, width, out, ldo, e.kind, e.slope, aux,
-                                                                 e.ldaux);
+    spmm_reduce_few<TI, TO><<<dim3((unsigned)ceil_div(g->n_long, 4), (unsigned)ceil_div(width, 256)), 256, 0, s>>>(
+        g->rowptr, g->dinv, g->long_row, g->long_first, g->n_long, partial, ldp, width, out, ldo, e.kind, e.slope, aux,
+        e.ldaux);
+    GAD_LAUNCH_CHECK();
+    spmm_reduce_many<TI, TO><<<dim3((unsigned)g->n_long, (unsigned)ceil_div(width, 64)), 256, 0, s>>>(
+        g->rowptr, g->dinv, g->long_row, g->long_first, partial, ldp, width, out, ldo, e.kind, e.slope, aux, e.ldaux);
     GAD_LAUNCH_CHECK();
   }
   return GAD_OK;
@@ -198,7 +249,7 @@ int spmm_typed(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ld
 
 }  // namespace
 
-size_t spmm_partial_floats(const gad_graph* g, int width) { return (size_t)g->n_chunks * (size_t)width; }
+size_t spmm_partial_floats(const gad_graph* g, int width) { return (size_t)g->n_chunks * (size_t)round_up(width, 4); }
 
 int spmm(const gad_graph* g, const void* T, int64_t ldt, gad_dtype t_in, void* out, int64_t ldo, gad_dtype t_out,
          int width, const Epi& e, float* partial, hipStream_t s) {

@@ -149,6 +149,62 @@ def test_aggregate_distance_is_rms_pairwise_distance():
     assert T0.zeta(np.zeros(4, dtype=int), V[:4], 1.0)[0] == 0.0          # edgeless convention
 
 
+def test_zeta_pairs_pins():
+    """Per-pair reading of Eq. 14, sum_{i<j} p_i p_j / (||v_i - v_j|| + beta): the paper's example (d = 0),
+    closed forms where every pair is at the same distance, scipy's pdist as an independent route to the
+    distances, and the invariances a pair sum must have."""
+    from scipy.spatial.distance import pdist
+    # (1) the worked example: identical vectors, beta = 0.1 -> 3.75 / 3.61 / 3.59, for both tiers
+    for name, pairs, printed in _load_example():
+        src, dst, n, loc, halo = _graph_from_pairs(pairs, 4)
+        V = np.full((4, 5), -1.3)
+        deg = T0.degrees(T0.adjacency_dense(src, dst, n, loc, halo))
+        assert round(T0.zeta_pairs(deg, V, beta=0.1), 2) == printed
+        assert round(T1.zeta_pairs(T1.build(src, dst, n, loc, halo), V, beta=0.1), 2) == printed
+        # with d = 0 the two readings of Eq. 14 agree
+        assert T0.zeta_pairs(deg, V, 0.1) == pytest.approx(T0.zeta(deg, V, 0.1)[0], rel=1e-12)
+    rng = np.random.default_rng(11)
+    # (2) regular simplex: v_i = (d0 / sqrt 2) e_i puts every pair at distance d0 -> S_pp / (d0 + beta)
+    for n, d0, beta in ((3, 2.0, 1.0), (12, 0.37, 0.5), (40, 5.0, 2.0)):
+        V = np.eye(n) * d0 / np.sqrt(2.0)
+        deg = rng.integers(1, 9, n)
+        assert T0.zeta_pairs(deg, V, beta) == pytest.approx(T0.pair_probability_sum(deg) / (d0 + beta), rel=1e-12)
+    # (3) two nodes: one term p_0 p_1 / (|a - b| + beta); a 3-4-5 triangle by hand
+    assert T0.zeta_pairs([3, 1], [[0.0, 0.0], [3.0, 4.0]], 1.0) == pytest.approx((3 / 4) * (1 / 4) / 6.0, rel=1e-14)
+    V = np.array([[0.0, 0.0], [3.0, 0.0], [0.0, 4.0]])
+    hand = (1 * 2 / (3 + 1) + 1 * 3 / (4 + 1) + 2 * 3 / (5 + 1)) / 36.0
+    assert T0.zeta_pairs([1, 2, 3], V, 1.0) == pytest.approx(hand, rel=1e-14)
+    # (4) random vectors: distances from scipy's pdist (condensed order = pairs i<j in row-major order)
+    for n, F in ((7, 1), (60, 9), (500, 33)):
+        V = rng.standard_normal((n, F)) * 2 - 0.5
+        deg = rng.integers(0, 20, n)
+        deg[0] = 3
+        p = deg / deg.sum()
+        iu = np.triu_indices(n, 1)
+        ref = float(np.sum(p[iu[0]] * p[iu[1]] / (pdist(V) + 0.7)))
+        z = T0.zeta_pairs(deg, V, 0.7)
+        assert z == pytest.approx(ref, rel=1e-11)
+        # invariances: node order, translation, and joint scaling of vectors and beta
+        perm = rng.permutation(n)
+        assert T0.zeta_pairs(deg[perm], V[perm], 0.7) == pytest.approx(z, rel=1e-11)
+        assert T0.zeta_pairs(deg, V + 3.25, 0.7) == pytest.approx(z, rel=1e-10)
+        assert T0.zeta_pairs(deg, 4.0 * V, 4.0 * 0.7) == pytest.approx(z / 4.0, rel=1e-11)
+        # bounds: every distance >= 0, so zeta_pair <= S_pp / beta; spreading the vectors lowers it
+        assert z < T0.pair_probability_sum(deg) / 0.7
+        assert T0.zeta_pairs(deg, 3.0 * V, 0.7) < z
+        # Jensen (1 / (x + beta) is convex, mean <= RMS): with equal degrees the pair sum is at least S_pp over
+        # (RMS pair distance + beta)
+        eq = np.full(n, 4)
+        rms = float(np.sqrt(np.mean(pdist(V) ** 2)))
+        assert T0.zeta_pairs(eq, V, 0.7) >= T0.pair_probability_sum(eq) / (rms + 0.7) * (1 - 1e-12)
+    # (5) edgeless convention and the C tier against the numpy tier
+    assert T0.zeta_pairs(np.zeros(5, dtype=int), rng.standard_normal((5, 2)), 1.0) == 0.0
+    gr, X, _, _, _ = _random_problem(300, 1500, (6, 3), 9, n_halo=40)
+    g = T1.build(**gr)
+    deg = T0.degrees(T0.adjacency_dense(**gr))
+    assert T1.zeta_pairs(g, X, 1.0) == pytest.approx(T0.zeta_pairs(deg, X, 1.0), rel=1e-11)
+
+
 # --------------------------------------------------------------------------- graph build
 
 def test_csr_hand_example():
