@@ -168,6 +168,20 @@ int gad_gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, float* C
 int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta,
                           double* out3, float* per_node_out, void* hip_stream);
 
+/* Eq. 14 read with the distance inside the sum (the formula as printed sums only its numerator and leaves i, j
+ * free in the denominator; with identical node vectors, as in the paper's worked example, both readings agree):
+ *
+ *   zeta_pair = sum_{i<j} p_i p_j / (||v_i - v_j||_2 + beta),   p_i as above.
+ *
+ * All n (n - 1) / 2 pairs are visited: the cost is O(n^2 F).
+ *   V          [n x F] node vectors, ld = F; float32 or bfloat16.
+ *   out2       device double[2]: zeta_pair, S_pp.
+ *   workspace  device, 256-byte aligned, gad_pair_importance_workspace_bytes(g, F) bytes.
+ * Errors: as gad_subgraph_variance; n above about 5.9 million (more pair tiles than one launch holds). */
+int gad_pair_importance_workspace_bytes(const gad_graph* g, int32_t F, size_t* bytes);
+int gad_pair_importance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta, double* out2,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ---------------------------------------------------------------------------------------------
  * 5. Weighted global consensus (Section 3.4.2, Eq. 15; Eq. 11 is the case of equal zeta).
  *

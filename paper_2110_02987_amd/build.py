@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgad.so")
-SOURCES = ["api.hip", "build_graph.hip", "spmm.hip", "gemm.hip", "gemm_bf16.hip", "loss.hip", "optimizer.hip"]
+SOURCES = ["api.hip", "build_graph.hip", "spmm.hip", "gemm.hip", "gemm_bf16.hip", "loss.hip", "optimizer.hip", "optimizer_pairs.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
          "-Wall", "-Wno-unused-function",
@@ -25,7 +25,7 @@ def _compile(src: str) -> str:
 
 def build_native(verbose: bool = True) -> str:
     """Compile every HIP source and link libgad.so next to this file.  Always recompiles."""
-    with cf.ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
+    with cf.ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB])
     if verbose:

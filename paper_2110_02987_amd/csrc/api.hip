@@ -392,6 +392,25 @@ int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtyp
   return subgraph_variance(g, V, F, dtype, beta, out3, per_node_out, static_cast<hipStream_t>(hip_stream));
 }
 
+int gad_pair_importance_workspace_bytes(const gad_graph* g, int32_t F, size_t* bytes) {
+  if (!g || !bytes) return set_error(GAD_ERR_NULL, "graph or bytes is NULL");
+  if (F < 1 || F > kMaxWidth) return set_error(GAD_ERR_SHAPE, "F = %d outside [1, %d]", F, kMaxWidth);
+  *bytes = pair_importance_workspace_bytes(g->n, F);
+  return GAD_OK;
+}
+
+int gad_pair_importance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta, double* out2,
+                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!g || !V || !out2 || !workspace) return set_error(GAD_ERR_NULL, "graph, V, out2 or workspace is NULL");
+  if (F < 1 || F > kMaxWidth) return set_error(GAD_ERR_SHAPE, "F = %d outside [1, %d]", F, kMaxWidth);
+  if (!(beta > 0.0) || !isfinite(beta)) return set_error(GAD_ERR_SHAPE, "beta must be positive and finite");
+  if (dtype != GAD_F32 && dtype != GAD_BF16) return set_error(GAD_ERR_UNSUPPORTED, "unknown dtype");
+  if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 ||
+      workspace_bytes < pair_importance_workspace_bytes(g->n, F))
+    return set_error(GAD_ERR_WORKSPACE, "workspace too small or not %zu-byte aligned", kAlign);
+  return pair_importance(g, V, F, dtype, beta, out2, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
 // Validates the importance weights and forms zeta_k / sum_j zeta_j in float64.
 static int consensus_weights(const float* const* bufs, int K, const double* zeta, int64_t n_elems, double* w) {
   if (!bufs || !zeta) return set_error(GAD_ERR_NULL, "bufs or zeta is NULL");

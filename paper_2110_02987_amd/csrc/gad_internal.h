@@ -110,6 +110,12 @@ int softmax_xent(const float* Z, int64_t ldz, const int32_t* labels, const uint8
                  void* G, int64_t ldg, gad_dtype tg, double* block_partials, double* loss_out, hipStream_t s);
 int copy_rows(const void* in, int64_t ldi, gad_dtype ti, float* out, int64_t ldo, int64_t n, int width, hipStream_t s);
 size_t variance_scratch_doubles(int64_t n);
+// mean[c] = (1/n) sum_i V[i][c] in float64 (ordered sums); part: kVarBlocks x F doubles of scratch.
+int column_means_f64(const void* V, int64_t n, int F, gad_dtype dtype, double* part, double* mean, hipStream_t s);
+// Eq. 14 with the distance inside the pair sum (optimizer_pairs.hip).
+size_t pair_importance_workspace_bytes(int64_t n, int F);
+int pair_importance(const gad_graph* g, const void* V, int F, gad_dtype dtype, double beta, double* out2, void* ws,
+                    hipStream_t s);
 int subgraph_variance(const gad_graph* g, const void* V, int F, gad_dtype dtype, double beta, double* out3,
                       float* per_node, hipStream_t s);
 int weighted_consensus(const float* const* bufs, int K, const double* w, int64_t n, float* out, hipStream_t s);

@@ -177,22 +177,14 @@ template <typename T>
 int variance_t(const gad_graph* g, const T* V, int F, double beta, double* out3, float* per_node, hipStream_t s) {
   const int64_t n = g->n;
   // scratch layout (8-byte words): part[kVarBlocks x F] | mean[F] | block_r[nb] | block_d1[nb] | block_d2[nb], nb = ceil(n/16)
-  int n_blocks = (int)(n < kVarBlocks ? n : kVarBlocks);
-  const int64_t slab = ceil_div(n, n_blocks);
-  n_blocks = (int)ceil_div(n, slab);
   double* part = g->red_scratch;
   double* mean = part + (int64_t)kVarBlocks * F;
   double* block_r = mean + F;
   const int64_t r_blocks = ceil_div(n, 16);
   unsigned long long* block_d1 = reinterpret_cast<unsigned long long*>(block_r + r_blocks);
   unsigned long long* block_d2 = block_d1 + r_blocks;
-  if (F <= 32) column_sums<T, 32><<<n_blocks, 256, 0, s>>>(V, n, F, slab, part);
-  else if (F <= 64) column_sums<T, 64><<<n_blocks, 256, 0, s>>>(V, n, F, slab, part);
-  else if (F <= 128) column_sums<T, 128><<<n_blocks, 256, 0, s>>>(V, n, F, slab, part);
-  else column_sums<T, 256><<<n_blocks, 256, 0, s>>>(V, n, F, slab, part);
-  GAD_LAUNCH_CHECK();
-  column_means<<<(unsigned)ceil_div(F, 256), 256, 0, s>>>(part, n_blocks, F, n, mean);
-  GAD_LAUNCH_CHECK();
+  int st = column_means_f64(V, n, F, sizeof(T) == 4 ? GAD_F32 : GAD_BF16, part, mean, s);
+  if (st != GAD_OK) return st;
   deviations<T><<<(unsigned)r_blocks, 256, 0, s>>>(V, n, F, mean, g->deg, per_node, block_r, block_d1, block_d2);
   GAD_LAUNCH_CHECK();
   finalize_zeta<<<1, 256, 0, s>>>(block_r, r_blocks, n, block_d1, block_d2, beta, out3);
@@ -201,6 +193,25 @@ int variance_t(const gad_graph* g, const T* V, int F, double beta, double* out3,
 }
 
 }  // namespace
+
+int column_means_f64(const void* V, int64_t n, int F, gad_dtype dtype, double* part, double* mean, hipStream_t s) {
+  int n_blocks = (int)(n < kVarBlocks ? n : kVarBlocks);
+  const int64_t slab = ceil_div(n, n_blocks);
+  n_blocks = (int)ceil_div(n, slab);
+#define GAD_COLSUM(T, CW) column_sums<T, CW><<<n_blocks, 256, 0, s>>>(static_cast<const T*>(V), n, F, slab, part)
+  if (dtype == GAD_F32) {
+    if (F <= 32) GAD_COLSUM(float, 32); else if (F <= 64) GAD_COLSUM(float, 64);
+    else if (F <= 128) GAD_COLSUM(float, 128); else GAD_COLSUM(float, 256);
+  } else {
+    if (F <= 32) GAD_COLSUM(uint16_t, 32); else if (F <= 64) GAD_COLSUM(uint16_t, 64);
+    else if (F <= 128) GAD_COLSUM(uint16_t, 128); else GAD_COLSUM(uint16_t, 256);
+  }
+#undef GAD_COLSUM
+  GAD_LAUNCH_CHECK();
+  column_means<<<(unsigned)ceil_div(F, 256), 256, 0, s>>>(part, n_blocks, F, n, mean);
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
+}
 
 size_t variance_scratch_doubles(int64_t n) {
   return (size_t)kVarBlocks * kMaxWidth + kMaxWidth + 3 * (size_t)ceil_div(n, 16) + 4;

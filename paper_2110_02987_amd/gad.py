@@ -19,7 +19,8 @@ F32, BF16 = 0, 1
 SYMBOLS = ["gad_last_error", "gad_build_subgraph", "gad_graph_info", "gad_graph_destroy",
            "gad_gcn_workspace_bytes", "gad_gcn_forward", "gad_gcn_backward", "gad_gcn_activation", "gad_spmm_workspace_bytes", "gad_spmm",
            "gad_gemm_workspace_bytes", "gad_gemm_w", "gad_gemm_tn",
-           "gad_subgraph_variance", "gad_weighted_consensus", "gad_consensus_update", "gad_train_round"]
+           "gad_subgraph_variance", "gad_pair_importance_workspace_bytes", "gad_pair_importance",
+           "gad_weighted_consensus", "gad_consensus_update", "gad_train_round"]
 
 _lib = None
 _hip = None
@@ -238,6 +239,20 @@ def subgraph_variance(g: Graph, V: torch.Tensor, beta: float, out3: torch.Tensor
     _dev(out3, torch.float64, "out3")
     _check(lib().gad_subgraph_variance(g.handle, _ptr(V), C.c_int32(V.shape[1]), C.c_int(dtype), C.c_double(beta),
                                        _ptr(out3), _ptr(per_node_out), _stream()))
+
+
+def pair_importance(g: Graph, V: torch.Tensor, beta: float, out2: torch.Tensor,
+                    workspace: Optional[torch.Tensor] = None) -> None:
+    """out2 = (zeta_pair, S_pp): Eq. 14 with the distance inside the pair sum.  O(n^2 F)."""
+    dtype = F32 if V.dtype == torch.float32 else BF16
+    _dev(V, torch.float32 if dtype == F32 else torch.bfloat16, "V")
+    _dev(out2, torch.float64, "out2")
+    if workspace is None:
+        b = C.c_size_t()
+        _check(lib().gad_pair_importance_workspace_bytes(g.handle, C.c_int32(V.shape[1]), C.byref(b)))
+        workspace = torch.empty(b.value, dtype=torch.uint8, device="cuda")
+    _check(lib().gad_pair_importance(g.handle, _ptr(V), C.c_int32(V.shape[1]), C.c_int(dtype), C.c_double(beta),
+                                     _ptr(out2), _ptr(workspace), C.c_size_t(workspace.numel()), _stream()))
 
 
 def weighted_consensus(bufs: List[torch.Tensor], zeta: Sequence[float], out: torch.Tensor) -> None:

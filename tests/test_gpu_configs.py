@@ -43,6 +43,14 @@ def test_reddit_shaped_partition(gad):
     cfg, g, ref, X, f = _step(gad, "reddit_part")
     assert g.n == 69_000 and g.n_local == 60_000
     assert 3.0e6 < g.nnz < 3.7e6                       # ~ n * (avg degree 50) after dropping repeats
+    # per-pair reading of Eq. 14 over all 2.4e9 node pairs of the partition (41-dimensional node vectors: the
+    # float64 double loop of the oracle takes about ten seconds on the host cores)
+    V = wl.make_features(cfg.n, 41, sub=7)
+    out2 = torch.zeros(2, dtype=torch.float64, device="cuda")
+    gad.pair_importance(g, dev(V), 1.0, out2)
+    z = T1.zeta_pairs(ref, V, 1.0)
+    assert abs(out2[0].item() - z) <= TOL * z
+    progress(f"[reddit_part] pair importance ok: {out2[0].item():.6e}")
 
 
 def test_products_shaped_partition_with_variance_and_consensus(gad):

@@ -384,6 +384,61 @@ def test_variance_edgeless_and_errors(gad):
         assert e.value.status == -2
 
 
+@pytest.mark.parametrize("name,F,bf16", [("tiny", 128, False), ("products_small", 100, False), ("products_small", 7, False),
+                                         ("tiny", 1, False), ("products_small", 47, True), ("tiny", 300, False)])
+def test_pair_importance(gad, name, F, bf16):
+    """Eq. 14 with the distance inside the pair sum, all n (n - 1) / 2 pairs, against the float64 double loop."""
+    cfg = wl.CONFIGS[name]
+    g, ref = build_both(gad, wl.make_graph(cfg))
+    V = wl.make_features(cfg.n, F, sub=3) * 1.3 + 0.4
+    if bf16:
+        Vd, V = bf16_dev(V)
+    else:
+        Vd = dev(V)
+    out2 = torch.zeros(2, dtype=torch.float64, device="cuda")
+    gad.pair_importance(g, Vd, 1.0, out2)
+    z = T1.zeta_pairs(ref, V, 1.0)
+    got = out2.cpu().numpy()
+    assert abs(got[0] - z) <= TOL * z
+    assert abs(got[1] - T1.zeta(ref, V, 1.0)[1]) <= 1e-12
+    out2b = torch.zeros_like(out2)
+    gad.pair_importance(g, Vd, 1.0, out2b)
+    assert torch.equal(out2, out2b)                              # fixed summation order
+    gad.pair_importance(g, Vd, 0.1, out2b)
+    zb = T1.zeta_pairs(ref, V, 0.1)
+    assert abs(out2b[0].item() - zb) <= TOL * zb
+
+
+def test_pair_importance_close_and_identical_vectors(gad):
+    """Pairs that are close compared with their norms (the difference of norms and inner product cancels) and
+    exact duplicates: clusters of near-identical vectors far from the origin; and the paper's example (d = 0)."""
+    cfg = wl.CONFIGS["tiny"]
+    g, ref = build_both(gad, wl.make_graph(cfg))
+    rng = np.random.default_rng(2)
+    centres = rng.standard_normal((8, 24)) * 5 + 40.0
+    V = (centres[rng.integers(0, 8, cfg.n)] + 1e-3 * rng.standard_normal((cfg.n, 24))).astype(np.float32)
+    V[100:200] = V[100]                                          # exact duplicates
+    out2 = torch.zeros(2, dtype=torch.float64, device="cuda")
+    for beta in (1.0, 1e-2):
+        gad.pair_importance(g, dev(V), beta, out2)
+        z = T1.zeta_pairs(ref, V, beta)
+        assert abs(out2[0].item() - z) <= TOL * z, beta
+    for pairs, printed in (([(0, 1), (1, 2), (2, 3), (3, 0)], 3.75), ([(0, 1), (1, 2), (2, 3)], 3.61),
+                           ([(0, 1), (0, 2), (0, 3), (1, 2)], 3.59)):
+        src = dev(np.array([a for a, _ in pairs], dtype=np.int64))
+        dst = dev(np.array([b for _, b in pairs], dtype=np.int64))
+        g4 = gad.build_subgraph(src, dst, 4, dev(np.arange(4, dtype=np.int64)), dev(np.zeros(0, dtype=np.int64)))
+        gad.pair_importance(g4, torch.full((4, 3), 0.7, device="cuda"), 0.1, out2)
+        assert round(out2[0].item(), 2) == printed
+    none = dev(np.zeros(0, dtype=np.int64))
+    g0 = gad.build_subgraph(none, none, 3, dev(np.arange(3, dtype=np.int64)), none)      # edgeless: zeta = 0
+    gad.pair_importance(g0, torch.randn(3, 5, device="cuda"), 1.0, out2)
+    assert out2[0].item() == 0.0 and out2[1].item() == 0.0
+    with pytest.raises(gad.GadError) as e:
+        gad.pair_importance(g0, torch.randn(3, 5, device="cuda"), 0.0, out2)
+    assert e.value.status == -2
+
+
 @pytest.mark.parametrize("K,P", [(4, 103_168), (1, 17), (7, 1_000_003), (128, 4096)])
 def test_weighted_consensus(gad, K, P):
     rng = np.random.default_rng(K)
