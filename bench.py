@@ -179,6 +179,36 @@ def main() -> int:
                     roofline["traffic_GBps"] = nbytes / spmm[dom]["ms"] * 1e-6
                     roofline["traffic_frac_of_peak"] = roofline["traffic_GBps"] / HBM_PEAK_GBPS
 
+    # ---- the dense contractions of each layer, timed alone (MFMA kernels): H W forward and the weight gradient
+    mfma_peak = 2500.0 if bf16 else 157.3                  # published dense TFLOP/s of the instruction's type
+    gemm = {}
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    for l in range(L):
+        K_, N_ = dims[l], dims[l + 1]
+        if f"{K_}x{N_}" in gemm:
+            continue
+        A_ = torch.randn((g.n, K_), device="cuda").to(tdt)
+        G_ = torch.randn((g.n, N_), device="cuda").to(tdt)
+        C_ = torch.empty((g.n, N_), device="cuda", dtype=tdt)
+        dW_ = torch.empty((K_, N_), device="cuda")
+        gws = gad.gemm_workspace(g.n, K_, N_)
+        res = {}
+        for tag, fn in (("forward", lambda: gad.gemm_w(A_, Wd[l], C_, False, gws)),
+                        ("weight_grad", lambda: gad.gemm_tn(A_, G_, dW_, K_, N_, gws))):
+            for _ in range(2):
+                fn()
+            a, b = ev(), ev()
+            a.record()
+            for _ in range(args.kernel_reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / args.kernel_reps
+            tf = 2.0 * g.n * K_ * N_ / ms * 1e-9
+            res[tag] = dict(ms=ms, TFLOPs=tf, frac_of_mfma_peak=tf / mfma_peak)
+        gemm[f"{K_}x{N_}"] = res
+        del A_, G_, C_, dW_, gws
+
     out = dict(metric="GCN fwd+bwd edges/s per layer and epoch ms per subgraph; SpMM % of HBM peak",
                value=value, unit="edges/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step,
                higher_is_better=True, scaling="weak", vs_baseline=None, dtype=cfg.dtype, data="synthetic",
@@ -186,7 +216,8 @@ def main() -> int:
                                     f"GCN {'-'.join(map(str, dims))}, consensus K={K}",
                            n=g.n, nnz=g.nnz, dims=dims),
                epoch_ms=epoch_ms, forward_ms=fwd_ms, backward_ms=bwd_ms, variance_consensus_ms=tail_ms,
-               build_ms=build_ms, spmm={str(k): v for k, v in spmm.items()}, roofline=roofline)
+               build_ms=build_ms, spmm={str(k): v for k, v in spmm.items()}, gemm=gemm,
+               mfma_peak_TFLOPs=mfma_peak, roofline=roofline)
 
     # ---- the oracle, as it stands, on the host cores (reported baseline, not a target)
     if not args.no_cpu_baseline:

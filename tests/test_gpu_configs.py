@@ -20,7 +20,7 @@ from tests.test_gpu_parity import (TOL, TOL_BF16, assert_csr_equal, bf16_dev, bu
 pytestmark = pytest.mark.gpu
 
 
-def _step(gad, name):
+def _step(gad, name, bf16=False):
     cfg = wl.CONFIGS[name]
     t0 = time.time()
     progress(f"[{name}] generating graph")
@@ -34,8 +34,8 @@ def _step(gad, name):
     Ws = wl.make_weights(dims)
     y = wl.make_labels(cfg.n, dims[-1])
     mask = wl.make_mask(cfg)
-    f = check_step(gad, g, ref, X, Ws, y, mask, 1.0 / mask.sum(), dims)
-    progress(f"[{name}] step parity ok in {time.time() - t0:.1f}s, loss={f['loss']:.6f}")
+    f = check_step(gad, g, ref, X, Ws, y, mask, 1.0 / mask.sum(), dims, bf16=bf16)
+    progress(f"[{name}] step parity ok in {time.time() - t0:.1f}s, loss={f['loss']:.6f}, bf16={bf16}")
     return cfg, g, ref, X, f
 
 
@@ -51,6 +51,13 @@ def test_reddit_shaped_partition(gad):
     z = T1.zeta_pairs(ref, V, 1.0)
     assert abs(out2[0].item() - z) <= TOL * z
     progress(f"[reddit_part] pair importance ok: {out2[0].item():.6e}")
+
+
+@pytest.mark.parametrize("name", ["reddit_part", "products_part"])
+def test_partitions_in_bf16_storage(gad, name):
+    """The second and third workloads with bfloat16 storage of features and activations (bf16 matrix instruction for
+    the GEMMs, float32 accumulation), whole step against the float64 oracle at the bf16 tolerance."""
+    _step(gad, name, bf16=True)
 
 
 def test_products_shaped_partition_with_variance_and_consensus(gad):
