@@ -84,6 +84,31 @@ int gad_graph_info(const gad_graph* g, int64_t* n, int64_t* n_local, int64_t* nn
 
 int gad_graph_destroy(gad_graph* g);
 
+/* Importance-based augmentation of one partition (Section 3.2.2; Algorithm 1): which nodes of the original graph
+ * to replicate into the partition.  This is the step that produces the halo_ids of gad_build_subgraph.
+ *
+ *   G           the ORIGINAL graph as a gad_graph (e.g. gad_build_subgraph with all its nodes as local_ids); the
+ *               walks run on it, nodes are its rows.
+ *   part_rows   [n_part] int64, distinct rows of G: the partition v_i.
+ *   walk_len    l, the number of GCN layers (Property 1: walks of that length reach exactly the candidates of
+ *               Definition 2); 1 <= l <= 16.
+ *   budget      n(g_i) of Eq. 6, the number of replication nodes wanted (the caller evaluates Eq. 5 / Eq. 6).
+ *   seed        walk j is a pure function of (seed, j): start = uniformly drawn boundary node, l uniform steps.
+ *   max_walks   cap on the number of walks (<= 2^26).
+ *   halo_rows_out  device int64[budget]: the chosen rows of G in selection order;  n_halo_out (host): how many
+ *               (fewer than budget when the walks met fewer candidates);  n_walks_out (host, may be NULL).
+ * Steps: boundary nodes B (a neighbour outside the partition); a first batch of sum_{v in B} deg(v) walks
+ * (Algorithm 1: average boundary degree times |B|); visit counts c_v of the nodes outside the partition, once
+ * per walk (Eq. 3, I(v) = c_v / n); total number of walks n = ceil((1.96 / 0.05)^2 (m S2 - S1^2) / S1^2) from
+ * Eq. 4 with the mean and population variance of I(v) over the m visited candidates (S1 = sum c, S2 = sum c^2),
+ * at least the first batch; walks scored by the sum of I(v) over their steps, taken in descending score (ties:
+ * walk number), their nodes added in step order until the budget is met (depth-first selection: no dangling node).
+ * Integer arithmetic throughout: the result is exact and reproducible.  Synchronises hip_stream.
+ * Errors: rows out of range (GAD_ERR_ID_RANGE) or listed twice (GAD_ERR_ID_DUP), sizes out of range. */
+int gad_augment_subgraph(const gad_graph* G, const int64_t* part_rows, int64_t n_part, int32_t walk_len, int64_t budget,
+                         uint64_t seed, int64_t max_walks, int64_t* halo_rows_out, int64_t* n_halo_out,
+                         int64_t* n_walks_out, void* hip_stream);
+
 /* ---------------------------------------------------------------------------------------------
  * 2./3. Forward and backward propagation (Section 3.3; Algorithm 2, forward and backward steps).
  *

@@ -81,7 +81,8 @@ def mc_walk_count(counts) -> int:
     if len(c) == 0:
         return 0
     m, s1, s2 = len(c), int(sum(c)), int(sum(x * x for x in c))
-    return int(math.ceil((Z_C / E_MC) ** 2 * float(m * s2 - s1 * s1) / float(s1 * s1)))
+    q = Z_C / E_MC
+    return int(math.ceil(q * q * float(m * s2 - s1 * s1) / float(s1 * s1)))
 
 
 def augment(rowptr, colidx, part, l, budget, seed, max_walks=1 << 22):

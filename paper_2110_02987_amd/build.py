@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgad.so")
-SOURCES = ["api.hip", "build_graph.hip", "spmm.hip", "gemm.hip", "gemm_bf16.hip", "loss.hip", "optimizer.hip", "optimizer_pairs.hip"]
+SOURCES = ["api.hip", "build_graph.hip", "augment.hip", "spmm.hip", "gemm.hip", "gemm_bf16.hip", "loss.hip", "optimizer.hip", "optimizer_pairs.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
          "-Wall", "-Wno-unused-function",

@@ -184,6 +184,21 @@ int gad_graph_destroy(gad_graph* g) {
   return st;
 }
 
+int gad_augment_subgraph(const gad_graph* G, const int64_t* part_rows, int64_t n_part, int32_t walk_len, int64_t budget,
+                         uint64_t seed, int64_t max_walks, int64_t* halo_rows_out, int64_t* n_halo_out,
+                         int64_t* n_walks_out, void* hip_stream) {
+  if (!G || !n_halo_out) return set_error(GAD_ERR_NULL, "graph or n_halo_out is NULL");
+  *n_halo_out = 0;
+  if (n_part < 1 || n_part > G->n) return set_error(GAD_ERR_SHAPE, "n_part = %lld outside [1, n]", (long long)n_part);
+  if (!part_rows) return set_error(GAD_ERR_NULL, "part_rows is NULL");
+  if (walk_len < 1 || walk_len > 16) return set_error(GAD_ERR_SHAPE, "walk_len = %d outside [1, 16]", walk_len);
+  if (budget < 0 || (budget > 0 && !halo_rows_out)) return set_error(GAD_ERR_NULL, "budget < 0, or halo_rows_out is NULL");
+  if (max_walks < 1 || max_walks > (1ll << 26))
+    return set_error(GAD_ERR_SHAPE, "max_walks = %lld outside [1, 2^26]", (long long)max_walks);
+  return augment_subgraph(G, part_rows, n_part, walk_len, budget, seed, max_walks, halo_rows_out, n_halo_out, n_walks_out,
+                          static_cast<hipStream_t>(hip_stream));
+}
+
 int gad_gcn_workspace_bytes(const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, size_t* bytes) {
   if (!bytes) return set_error(GAD_ERR_NULL, "bytes is NULL");
   Plan p;

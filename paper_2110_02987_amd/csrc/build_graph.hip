@@ -353,6 +353,17 @@ struct Scratch {   // frees whatever was allocated when it goes out of scope
 
 }  // namespace
 
+// The scan and the radix pass are also used by the augmentation (augment.hip).
+int scan_u32(uint32_t* data, uint32_t n, uint32_t* tile_tmp, uint32_t* total_out, hipStream_t s) {
+  return exclusive_scan_u32(data, n, tile_tmp, total_out, s);
+}
+int sort_pass_u64(const uint64_t* in, uint64_t* out, uint32_t n_keys, int shift, uint32_t* hist, uint32_t* tile_tmp,
+                  uint32_t* total_out, hipStream_t s) {
+  return radix_pass(in, out, n_keys, shift, hist, tile_tmp, total_out, s);
+}
+size_t sort_hist_len(uint32_t n_keys) { return (size_t)256 * (size_t)ceil_div(n_keys, kTile); }
+size_t scan_tmp_len(size_t n) { return (size_t)ceil_div((int64_t)n, kTile) + 1; }
+
 int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int64_t n_global, const int64_t* local_ids,
                    int64_t n_local, const int64_t* halo_ids, int64_t n_halo, hipStream_t s, gad_graph** out) {
   const int64_t n = n_local + n_halo;

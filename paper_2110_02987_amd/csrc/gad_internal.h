@@ -79,6 +79,17 @@ namespace gad {
 // ---- kernels' host entry points (each enqueues on `s` and returns a gad_status) -------------
 int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int64_t n_global, const int64_t* local_ids,
                    int64_t n_local, const int64_t* halo_ids, int64_t n_halo, hipStream_t s, gad_graph** out);
+// data[0..n) <- exclusive scan (uint32), total_out[0] <- sum; tile_tmp: scan_tmp_len(n) words.
+int scan_u32(uint32_t* data, uint32_t n, uint32_t* tile_tmp, uint32_t* total_out, hipStream_t s);
+// One stable LSD radix pass on the 8-bit digit at `shift`; hist: sort_hist_len(n_keys) words,
+// tile_tmp: scan_tmp_len(sort_hist_len(n_keys)) words.
+int sort_pass_u64(const uint64_t* in, uint64_t* out, uint32_t n_keys, int shift, uint32_t* hist, uint32_t* tile_tmp,
+                  uint32_t* total_out, hipStream_t s);
+size_t sort_hist_len(uint32_t n_keys);
+size_t scan_tmp_len(size_t n);
+// Importance-based augmentation (Section 3.2.2, Algorithm 1); augment.hip.
+int augment_subgraph(const gad_graph* G, const int64_t* part, int64_t n_part, int walk_len, int64_t budget, uint64_t seed,
+                     int64_t max_walks, int64_t* halo_out, int64_t* n_halo_out, int64_t* n_walks_out, hipStream_t s);
 // Node matrices are float32 or bfloat16 (gad_dtype); weights, partial sums and logits are float32.
 // out = A~ T with the epilogue applied; epi.aux (EPI_MASK) has T's storage type.  `partial` holds the chunk sums
 // of the long rows: spmm_partial_floats(g, width) floats (may be NULL when that is 0).

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgad.so")
 
 F32, BF16 = 0, 1
-SYMBOLS = ["gad_last_error", "gad_build_subgraph", "gad_graph_info", "gad_graph_destroy",
+SYMBOLS = ["gad_last_error", "gad_build_subgraph", "gad_graph_info", "gad_graph_destroy", "gad_augment_subgraph",
            "gad_gcn_workspace_bytes", "gad_gcn_forward", "gad_gcn_backward", "gad_gcn_activation", "gad_spmm_workspace_bytes", "gad_spmm",
            "gad_gemm_workspace_bytes", "gad_gemm_w", "gad_gemm_tn",
            "gad_subgraph_variance", "gad_pair_importance_workspace_bytes", "gad_pair_importance",
@@ -121,6 +121,18 @@ def build_subgraph(src: torch.Tensor, dst: torch.Tensor, n_global: int, local_id
                                     _ptr(halo_ids if halo_ids.numel() else None), C.c_int64(halo_ids.numel()),
                                     _stream(), C.byref(h)))
     return Graph(h)
+
+
+def augment_subgraph(G: Graph, part_rows: torch.Tensor, walk_len: int, budget: int, seed: int,
+                     max_walks: int = 1 << 22):
+    """Replication nodes of one partition (Algorithm 1).  Returns (rows of G in selection order, number of walks)."""
+    _dev(part_rows, torch.int64, "part_rows")
+    out = torch.empty(max(budget, 1), dtype=torch.int64, device="cuda")
+    n_halo, n_walks = C.c_int64(), C.c_int64()
+    _check(lib().gad_augment_subgraph(G.handle, _ptr(part_rows), C.c_int64(part_rows.numel()), C.c_int32(walk_len),
+                                      C.c_int64(budget), C.c_uint64(seed), C.c_int64(max_walks), _ptr(out),
+                                      C.byref(n_halo), C.byref(n_walks), _stream()))
+    return out[: n_halo.value], n_walks.value
 
 
 def _dims(dims: Sequence[int]):
