@@ -84,6 +84,12 @@ int gad_graph_info(const gad_graph* g, int64_t* n, int64_t* n_local, int64_t* nn
 
 int gad_graph_destroy(gad_graph* g);
 
+/* Block-diagonal union of K graphs: the subgraphs one processor holds (Algorithm 2: "each batch g_k in p_i") as
+ * ONE graph, so that a forward / backward pass over all of them is one set of launches.  Row i of graphs[k]
+ * becomes row (n_0 + .. + n_{k-1}) + i; no edge joins two blocks; degrees and normalisation are the blocks' own.
+ * The inputs stay valid and independent.  graphs: host array of K handles, 1 <= K <= 65536.  Synchronises hip_stream. */
+int gad_graph_concat(const gad_graph* const* graphs, int K, void* hip_stream, gad_graph** out);
+
 /* Importance-based augmentation of one partition (Section 3.2.2; Algorithm 1): which nodes of the original graph
  * to replicate into the partition.  This is the step that produces the halo_ids of gad_build_subgraph.
  *
@@ -125,6 +131,9 @@ int gad_augment_subgraph(const gad_graph* G, const int64_t* part_rows, int64_t n
  *   dims       host, int32[L+1]: F_0 .. F_L (F_L = number of classes); 1 <= L <= 16, 1 <= F <= 4096.
  *   W          host array of L device pointers; W[l] is float32 [dims[l] x dims[l+1]], ld dims[l+1].
  *   labels     int32[n] in [0, F_L); mask uint8[n] (NULL = all ones).
+ *   row_scale  float32[n] or NULL: per-node weight of the loss; node i then carries loss_scale * row_scale[i].
+ *              With the blocks of a gad_graph_concat union weighted by c_k * zeta_k / sum_j zeta_j, the gradient
+ *              of the pass IS the weighted consensus of Eq. 15 (gradients are linear in these weights).
  *   workspace  device, 256-byte aligned, at least gad_gcn_workspace_bytes(); keeps the activations
  *              between forward and backward.  Its contents are private to the library.
  *   logits_out float32 [n x F_L] (ld F_L) or NULL;  loss_out device double[1] or NULL.
@@ -140,8 +149,8 @@ int gad_gcn_workspace_bytes(const gad_graph* g, int L, const int32_t* dims, gad_
 
 int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
                     const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
-                    float negative_slope, void* workspace, size_t workspace_bytes, float* logits_out,
-                    double* loss_out, void* hip_stream);
+                    const float* row_scale, float negative_slope, void* workspace, size_t workspace_bytes,
+                    float* logits_out, double* loss_out, void* hip_stream);
 
 int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
                      const float* const* W, float negative_slope, void* workspace, size_t workspace_bytes,
@@ -235,6 +244,15 @@ int gad_weighted_consensus(const float* const* bufs, int K, const double* zeta, 
  *   Nothing is launched if the weights are invalid. */
 int gad_consensus_update(const float* const* grads, int K, const double* zeta, int64_t n_elems, float eta,
                          float* params, float* avg_out, void* hip_stream);
+
+/* One synchronous round of Algorithm 2 over the blocks of a gad_graph_concat union in one pass: forward with
+ * row_scale[i] = c_k * zeta_k / sum_j zeta_j on the rows of block k (c_k = the block's own loss scale), backward
+ * into `grad` (float32[n_params], the layout of `params`) -- which is the weighted consensus gradient of Eq. 15 --
+ * then params <- params - eta * grad (Eq. 16).  loss (device double[1] or NULL) receives the weighted loss
+ * sum_k (zeta_k / sum zeta) loss_k.  Other arguments as gad_gcn_forward / gad_train_round. */
+int gad_train_round_batched(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims, float* params,
+                            const int32_t* labels, const uint8_t* mask, const float* row_scale, float negative_slope,
+                            void* workspace, size_t workspace_bytes, float* grad, float eta, double* loss, void* hip_stream);
 
 int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X, gad_dtype dtype, int L,
                     const int32_t* dims, float* params, const int32_t* const* labels, const uint8_t* const* masks,

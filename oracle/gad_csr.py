@@ -102,7 +102,8 @@ def spmm_rows(g: Graph, T32, rows, width=None) -> np.ndarray:
 
 
 def forward(g: Graph, X, Ws, labels, mask, c=1.0, slope=0.0):
-    """Eq. 7-9.  Keeps AH[l] = A~ H_l for the backward.  sigma = ReLU (slope 0) or LeakyReLU (Eq. 7 names both)."""
+    """Eq. 7-9.  Keeps AH[l] = A~ H_l for the backward.  sigma = ReLU (slope 0) or LeakyReLU (Eq. 7 names both).
+    c: the scale of the loss, a scalar or one weight per node."""
     H = [np.asarray(X, dtype=np.float64)]
     AH, P = [], []
     L = len(Ws)
@@ -118,7 +119,10 @@ def forward(g: Graph, X, Ws, labels, mask, c=1.0, slope=0.0):
     yhat = e / se
     lse = np.log(se[:, 0]) + zmax[:, 0]
     m = np.asarray(mask).astype(bool)
-    loss = c * np.sum((lse - Z[np.arange(Z.shape[0]), labels])[m])
+    if np.ndim(c) == 0:
+        loss = c * np.sum((lse - Z[np.arange(Z.shape[0]), labels])[m])
+    else:                                   # per-node weights c_i (e.g. the importance weights of Eq. 15 per block)
+        loss = np.sum((np.asarray(c, dtype=np.float64) * (lse - Z[np.arange(Z.shape[0]), labels]))[m])
     return dict(Z=Z, loss=float(loss), H=H, P=P, AH=AH, yhat=yhat)
 
 
@@ -132,7 +136,7 @@ def backward(g: Graph, Ws, fwd, labels, mask, c=1.0, relu_on=None, slope=0.0):
     n, K = fwd["Z"].shape
     G = fwd["yhat"].copy()
     G[np.arange(n), labels] -= 1.0
-    G *= c * np.asarray(mask, dtype=np.float64)[:, None]
+    G *= (np.asarray(c, dtype=np.float64) * np.asarray(mask, dtype=np.float64))[:, None]
     dW = [None] * L
     Gs = [None] * L
     for l in range(L - 1, -1, -1):
@@ -142,6 +146,17 @@ def backward(g: Graph, Ws, fwd, labels, mask, c=1.0, relu_on=None, slope=0.0):
             on = fwd["P"][l - 1] > 0 if relu_on is None else relu_on[l - 1]
             G = (spmm(g, G) @ np.asarray(Ws[l], dtype=np.float64).T) * np.where(on, 1.0, slope)
     return dW, Gs
+
+
+def concat(graphs) -> Graph:
+    """Block-diagonal union: the rows of graphs[k] follow those of graphs[0..k-1]; no edge joins two blocks."""
+    rowptr, colidx, row_off, nnz_off = [np.zeros(1, dtype=np.int64)], [], 0, 0
+    for g in graphs:
+        rowptr.append(g.rowptr[1:] + nnz_off)
+        colidx.append(g.colidx + np.int32(row_off))
+        row_off += g.n
+        nnz_off += g.nnz
+    return Graph(np.concatenate(rowptr), np.concatenate(colidx).astype(np.int32))
 
 
 def zeta(g: Graph, V, beta=1.0):

@@ -111,7 +111,10 @@ def forward(At, X, Ws, labels, mask, c=1.0, slope=0.0):
     lse = np.log(e.sum(axis=1)) + zmax[:, 0]
     m = np.asarray(mask).astype(bool)
     idx = np.arange(Z.shape[0])
-    loss = c * np.sum((lse - Z[idx, labels])[m])                    # Eq. 9 read as softmax-CE (sum)
+    if np.ndim(c) == 0:
+        loss = c * np.sum((lse - Z[idx, labels])[m])                # Eq. 9 read as softmax-CE (sum)
+    else:                                                           # per-node weights c_i
+        loss = np.sum((np.asarray(c, dtype=np.float64) * (lse - Z[idx, labels]))[m])
     return dict(Z=Z, loss=float(loss), H=H, P=P, yhat=yhat)
 
 
@@ -124,7 +127,8 @@ def backward(At, Ws, fwd, labels, mask, c=1.0, relu_on=None, slope=0.0):
     n, C = fwd["Z"].shape
     onehot = np.zeros((n, C))
     onehot[np.arange(n), labels] = 1.0
-    G = c * (fwd["yhat"] - onehot) * np.asarray(mask, dtype=np.float64)[:, None]   # Eq. 10 w.r.t. logits
+    cm = np.asarray(c, dtype=np.float64) * np.asarray(mask, dtype=np.float64)      # scalar or per-node weight
+    G = (fwd["yhat"] - onehot) * (cm[:, None] if np.ndim(cm) else cm)                # Eq. 10 w.r.t. logits
     dW = [None] * L
     Gs = [None] * L
     for l in range(L - 1, -1, -1):

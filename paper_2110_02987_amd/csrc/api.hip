@@ -168,6 +168,16 @@ int gad_graph_info(const gad_graph* g, int64_t* n, int64_t* n_local, int64_t* nn
   return GAD_OK;
 }
 
+int gad_graph_concat(const gad_graph* const* graphs, int K, void* hip_stream, gad_graph** out) {
+  if (!out) return set_error(GAD_ERR_NULL, "out is NULL");
+  *out = nullptr;
+  if (!graphs) return set_error(GAD_ERR_NULL, "graphs is NULL");
+  if (K < 1 || K > 65536) return set_error(GAD_ERR_SHAPE, "K = %d outside [1, 65536]", K);
+  for (int k = 0; k < K; ++k)
+    if (!graphs[k]) return set_error(GAD_ERR_NULL, "graphs[%d] is NULL", k);
+  return graph_concat(graphs, K, static_cast<hipStream_t>(hip_stream), out);
+}
+
 int gad_graph_destroy(gad_graph* g) {
   if (!g) return GAD_OK;
   void* ptrs[] = {g->rowptr,    g->colidx,    g->deg,         g->dinv,       g->row_order, g->long_row,
@@ -210,8 +220,8 @@ int gad_gcn_workspace_bytes(const gad_graph* g, int L, const int32_t* dims, gad_
 
 int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
                     const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
-                    float negative_slope, void* workspace, size_t workspace_bytes, float* logits_out,
-                    double* loss_out, void* hip_stream) {
+                    const float* row_scale, float negative_slope, void* workspace, size_t workspace_bytes,
+                    float* logits_out, double* loss_out, void* hip_stream) {
   Plan p;
   int st = make_plan(g, L, dims, dtype, &p);
   if (st != GAD_OK) return st;
@@ -255,7 +265,7 @@ int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, c
   const int C = dims[L];
   const int64_t ldz = pad_ld(C);
   const float* Z = static_cast<const float*>(h);
-  st = softmax_xent(Z, ldz, labels, mask, loss_scale, n, C, at(workspace, p.g_a), ldz, dtype,
+  st = softmax_xent(Z, ldz, labels, mask, loss_scale, row_scale, n, C, at(workspace, p.g_a), ldz, dtype,
                     static_cast<double*>(at(workspace, p.sm)), loss_out, s);
   if (st != GAD_OK) return st;
   if (logits_out && (st = copy_rows(Z, ldz, GAD_F32, logits_out, C, n, C, s)) != GAD_OK) return st;
@@ -490,13 +500,41 @@ int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X,
     float* dW[kMaxLayers];
     for (int l = 0; l < L; ++l) dW[l] = grads + (int64_t)k * P + off[l];
     st = gad_gcn_forward(graphs[k], X[k], dtype, L, dims, W, labels[k], masks ? masks[k] : nullptr, loss_scales[k],
-                         negative_slope, workspaces[k], workspace_bytes[k], nullptr, losses ? losses + k : nullptr, hip_stream);
+                         nullptr, negative_slope, workspaces[k], workspace_bytes[k], nullptr, losses ? losses + k : nullptr, hip_stream);
     if (st != GAD_OK) return st;
     st = gad_gcn_backward(graphs[k], X[k], dtype, L, dims, W, negative_slope, workspaces[k], workspace_bytes[k], dW,
                           nullptr, hip_stream);
     if (st != GAD_OK) return st;
   }
   return consensus_update(gptr, K, w, P, eta, params, nullptr, static_cast<hipStream_t>(hip_stream));
+}
+
+int gad_train_round_batched(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims, float* params,
+                            const int32_t* labels, const uint8_t* mask, const float* row_scale, float negative_slope,
+                            void* workspace, size_t workspace_bytes, float* grad, float eta, double* loss, void* hip_stream) {
+  if (!dims || !params || !grad) return set_error(GAD_ERR_NULL, "dims, params or grad is NULL");
+  if (L < 1 || L > kMaxLayers) return set_error(GAD_ERR_SHAPE, "L = %d outside [1, %d]", L, kMaxLayers);
+  if (!isfinite(eta)) return set_error(GAD_ERR_SHAPE, "eta is not finite");
+  int64_t off[kMaxLayers + 1];
+  off[0] = 0;
+  for (int l = 0; l < L; ++l) {
+    if (dims[l] < 1 || dims[l + 1] < 1) return set_error(GAD_ERR_SHAPE, "dims must be positive");
+    off[l + 1] = off[l] + (int64_t)dims[l] * dims[l + 1];
+  }
+  const float* W[kMaxLayers];
+  float* dW[kMaxLayers];
+  for (int l = 0; l < L; ++l) {
+    W[l] = params + off[l];
+    dW[l] = grad + off[l];
+  }
+  int st = gad_gcn_forward(g, X, dtype, L, dims, W, labels, mask, 1.f, row_scale, negative_slope, workspace, workspace_bytes,
+                           nullptr, loss, hip_stream);
+  if (st != GAD_OK) return st;
+  st = gad_gcn_backward(g, X, dtype, L, dims, W, negative_slope, workspace, workspace_bytes, dW, nullptr, hip_stream);
+  if (st != GAD_OK) return st;
+  const float* gp[1] = {grad};
+  const double one[1] = {1.0};
+  return consensus_update(gp, 1, one, off[L], eta, params, nullptr, static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"

@@ -364,6 +364,140 @@ int sort_pass_u64(const uint64_t* in, uint64_t* out, uint32_t n_keys, int shift,
 size_t sort_hist_len(uint32_t n_keys) { return (size_t)256 * (size_t)ceil_div(n_keys, kTile); }
 size_t scan_tmp_len(size_t n) { return (size_t)ceil_div((int64_t)n, kTile) + 1; }
 
+// SpMM schedule of a graph whose rowptr / colidx are in place (see gad_graph).  Allocates the schedule arrays of
+// `g` (freed by gad_graph_destroy, also after a failure here) and synchronises the stream.
+int build_schedule(gad_graph* g, hipStream_t s) {
+  const int64_t n = g->n;
+  int bits = 1;
+  while ((1ll << bits) < n) ++bits;
+  Scratch scratch;
+  uint32_t *chunks_of = nullptr, *is_long = nullptr, *chunk_first = nullptr, *long_slot = nullptr;
+  uint32_t *flags = nullptr, *hist = nullptr, *tile_tmp = nullptr;      // flags: [0] scan totals, [1] long rows, [2] chunks
+  uint64_t *key_a = nullptr, *key_b = nullptr;
+  // keys: one per row, or one per chunk (a long row of len entries has at most len / kLongRow + 1 <= 2 len / kLongRow)
+  const size_t max_chunks = (size_t)(2 * g->nnz / kLongRow + 1);
+  const size_t max_keys = (size_t)n > max_chunks ? (size_t)n : max_chunks;
+  GAD_HIP(scratch.alloc(&chunks_of, (size_t)n));
+  GAD_HIP(scratch.alloc(&is_long, (size_t)n));
+  GAD_HIP(scratch.alloc(&chunk_first, (size_t)n));
+  GAD_HIP(scratch.alloc(&long_slot, (size_t)n));
+  GAD_HIP(scratch.alloc(&flags, 4));
+  GAD_HIP(scratch.alloc(&key_a, max_keys));
+  GAD_HIP(scratch.alloc(&key_b, max_keys));
+  const size_t hist_len = (size_t)256 * (size_t)ceil_div((int64_t)max_keys, kTile);
+  GAD_HIP(scratch.alloc(&hist, hist_len));
+  GAD_HIP(scratch.alloc(&tile_tmp, (size_t)ceil_div((int64_t)(hist_len > (size_t)n ? hist_len : (size_t)n), kTile) + 1));
+  GAD_HIP(hipMemsetAsync(flags, 0, 4 * sizeof(uint32_t), s));
+  classify_rows<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(g->rowptr, n, chunks_of, is_long, key_a);
+  GAD_LAUNCH_CHECK();
+  GAD_HIP(hipMalloc((void**)&g->row_order, sizeof(int32_t) * (size_t)n));
+  int st = radix_pass(key_a, key_b, (uint32_t)n, 32, hist, tile_tmp, flags, s);
+  if (st != GAD_OK) return st;
+  take_low32<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(key_b, n, g->row_order);
+  GAD_LAUNCH_CHECK();
+  // exclusive scans: first chunk id and slot of every long row; totals -> flags[2], flags[1]
+  GAD_HIP(hipMemcpyAsync(chunk_first, chunks_of, sizeof(uint32_t) * (size_t)n, hipMemcpyDeviceToDevice, s));
+  if ((st = exclusive_scan_u32(chunk_first, (uint32_t)n, tile_tmp, flags + 2, s)) != GAD_OK) return st;
+  GAD_HIP(hipMemcpyAsync(long_slot, is_long, sizeof(uint32_t) * (size_t)n, hipMemcpyDeviceToDevice, s));
+  if ((st = exclusive_scan_u32(long_slot, (uint32_t)n, tile_tmp, flags + 1, s)) != GAD_OK) return st;
+  uint32_t h[4];
+  GAD_HIP(hipMemcpyAsync(h, flags, 4 * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  GAD_HIP(hipStreamSynchronize(s));
+  g->n_long = (int32_t)h[1];
+  g->n_chunks = (int32_t)h[2];
+  g->n_short = n - g->n_long;
+  if (g->n_long > 0) {
+    GAD_HIP(hipMalloc((void**)&g->long_row, sizeof(int32_t) * (size_t)g->n_long));
+    GAD_HIP(hipMalloc((void**)&g->long_first, sizeof(int32_t) * (size_t)g->n_long));
+    GAD_HIP(hipMalloc((void**)&g->chunk_row, sizeof(int32_t) * (size_t)g->n_chunks));
+    GAD_HIP(hipMalloc((void**)&g->chunk_begin, sizeof(int32_t) * (size_t)g->n_chunks));
+    GAD_HIP(hipMalloc((void**)&g->chunk_perm, sizeof(int32_t) * (size_t)g->n_chunks));
+    fill_long_rows<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(n, chunk_first, long_slot, is_long, g->long_row,
+                                                              g->long_first);
+    GAD_LAUNCH_CHECK();
+    uint64_t *ck = key_a, *ck_alt = key_b;
+    fill_chunks<<<(unsigned)g->n_long, 256, 0, s>>>(g->rowptr, g->colidx, g->long_row, g->long_first, g->chunk_row,
+                                                    g->chunk_begin, ck);
+    GAD_LAUNCH_CHECK();
+    for (int shift = 32; shift < 32 + bits; shift += 8) {      // order the chunks by their first column
+      if ((st = radix_pass(ck, ck_alt, (uint32_t)g->n_chunks, shift, hist, tile_tmp, flags, s)) != GAD_OK) return st;
+      uint64_t* t = ck;
+      ck = ck_alt;
+      ck_alt = t;
+    }
+    take_low32<<<(unsigned)ceil_div(g->n_chunks, 256), 256, 0, s>>>(ck, g->n_chunks, g->chunk_perm);
+    GAD_LAUNCH_CHECK();
+  }
+  GAD_HIP(hipStreamSynchronize(s));
+  return GAD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Block-diagonal union of graphs: block k keeps its rows, shifted by the rows of the blocks before it.
+// ------------------------------------------------------------------------------------------------
+namespace {
+__global__ void shift_block(const int64_t* __restrict__ rowptr_in, const int32_t* __restrict__ colidx_in,
+                            const int32_t* __restrict__ deg_in, const float* __restrict__ dinv_in, int64_t n, int64_t nnz,
+                            int64_t row_off, int64_t nnz_off, int64_t* __restrict__ rowptr, int32_t* __restrict__ colidx,
+                            int32_t* __restrict__ deg, float* __restrict__ dinv) {
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i < n) {
+    rowptr[row_off + i] = rowptr_in[i] + nnz_off;
+    deg[row_off + i] = deg_in[i];
+    dinv[row_off + i] = dinv_in[i];
+  }
+  if (i < nnz) colidx[nnz_off + i] = colidx_in[i] + (int32_t)row_off;
+}
+__global__ void set_i64(int64_t* p, int64_t v) { *p = v; }
+}  // namespace
+
+int graph_concat(const gad_graph* const* graphs, int K, hipStream_t s, gad_graph** out) {
+  int64_t n = 0, nnz = 0, n_local = 0;
+  for (int k = 0; k < K; ++k) {
+    n += graphs[k]->n;
+    nnz += graphs[k]->nnz;
+    n_local += graphs[k]->n_local;
+  }
+  if (n > 2147483646ll || nnz >= 2147483648ll)
+    return set_error(GAD_ERR_SHAPE, "the union has %lld rows and %lld non-zeros: beyond 31 bits", (long long)n, (long long)nnz);
+  gad_graph* g = new gad_graph();
+  g->n = n;
+  g->n_local = n_local;
+  g->nnz = nnz;
+  auto fail = [&](int st) {
+    gad_graph_destroy(g);
+    return st;
+  };
+#define GAD_HIP_G(expr)                                                                                    \
+  do {                                                                                                     \
+    hipError_t _e = (expr);                                                                                \
+    if (_e != hipSuccess) return fail(set_error(GAD_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(_e))); \
+  } while (0)
+  GAD_HIP_G(hipGetDevice(&g->device));
+  GAD_HIP_G(hipMalloc((void**)&g->rowptr, sizeof(int64_t) * (size_t)(n + 1)));
+  GAD_HIP_G(hipMalloc((void**)&g->colidx, sizeof(int32_t) * (size_t)nnz));
+  GAD_HIP_G(hipMalloc((void**)&g->deg, sizeof(int32_t) * (size_t)n));
+  GAD_HIP_G(hipMalloc((void**)&g->dinv, sizeof(float) * (size_t)n));
+  GAD_HIP_G(hipMalloc((void**)&g->red_scratch, sizeof(double) * variance_scratch_doubles(n)));
+  int64_t row_off = 0, nnz_off = 0;
+  for (int k = 0; k < K; ++k) {
+    const gad_graph* b = graphs[k];
+    const int64_t work = b->nnz > b->n ? b->nnz : b->n;
+    shift_block<<<(unsigned)ceil_div(work, 256), 256, 0, s>>>(b->rowptr, b->colidx, b->deg, b->dinv, b->n, b->nnz, row_off,
+                                                              nnz_off, g->rowptr, g->colidx, g->deg, g->dinv);
+    GAD_HIP_G(hipGetLastError());
+    row_off += b->n;
+    nnz_off += b->nnz;
+  }
+  set_i64<<<1, 1, 0, s>>>(g->rowptr + n, nnz);
+  GAD_HIP_G(hipGetLastError());
+#undef GAD_HIP_G
+  int st = build_schedule(g, s);
+  if (st != GAD_OK) return fail(st);
+  *out = g;
+  return GAD_OK;
+}
+
 int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int64_t n_global, const int64_t* local_ids,
                    int64_t n_local, const int64_t* halo_ids, int64_t n_halo, hipStream_t s, gad_graph** out) {
   const int64_t n = n_local + n_halo;
@@ -447,64 +581,10 @@ int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int6
   GAD_HIP_G(hipGetLastError());
   degree_norm<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(g->rowptr, n, g->deg, g->dinv);
   GAD_HIP_G(hipGetLastError());
-  // SpMM schedule.  The sort buffers are free again (assemble_csr was their last reader on this stream).
-  uint32_t *chunks_of = nullptr, *is_long = nullptr;
-  GAD_HIP_G(scratch.alloc(&chunks_of, (size_t)n));
-  GAD_HIP_G(scratch.alloc(&is_long, (size_t)n));
-  uint64_t* row_key = alt;              // n <= n_keys entries
-  classify_rows<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(g->rowptr, n, chunks_of, is_long, row_key);
-  GAD_HIP_G(hipGetLastError());
-  GAD_HIP_G(hipMalloc((void**)&g->row_order, sizeof(int32_t) * (size_t)n));
   {
-    uint64_t* sorted = cur;             // the CSR no longer needs the sorted edge keys
-    int st = radix_pass(row_key, sorted, (uint32_t)n, 32, hist, tile_tmp, flags + 3, s);
-    if (st != GAD_OK) return fail(st);
-    take_low32<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(sorted, n, g->row_order);
-    GAD_HIP_G(hipGetLastError());
-  }
-  // chunks_of / is_long -> exclusive scans (first chunk id and slot of every long row), totals -> flags[5], flags[4]
-  uint32_t* chunk_first = pos;          // pos holds n_keys >= n entries and was last read by assemble_csr
-  GAD_HIP_G(hipMemcpyAsync(chunk_first, chunks_of, sizeof(uint32_t) * (size_t)n, hipMemcpyDeviceToDevice, s));
-  {
-    int st = exclusive_scan_u32(chunk_first, (uint32_t)n, tile_tmp, flags + 5, s);
+    int st = build_schedule(g, s);       // synchronises the stream
     if (st != GAD_OK) return fail(st);
   }
-  uint32_t* long_slot = nullptr;
-  GAD_HIP_G(scratch.alloc(&long_slot, (size_t)n));
-  GAD_HIP_G(hipMemcpyAsync(long_slot, is_long, sizeof(uint32_t) * (size_t)n, hipMemcpyDeviceToDevice, s));
-  {
-    int st = exclusive_scan_u32(long_slot, (uint32_t)n, tile_tmp, flags + 4, s);
-    if (st != GAD_OK) return fail(st);
-  }
-  GAD_HIP_G(hipMemcpyAsync(h_flags + 4, flags + 4, 2 * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
-  GAD_HIP_G(hipStreamSynchronize(s));
-  g->n_long = (int32_t)h_flags[4];
-  g->n_chunks = (int32_t)h_flags[5];
-  g->n_short = n - g->n_long;
-  if (g->n_long > 0) {
-    GAD_HIP_G(hipMalloc((void**)&g->long_row, sizeof(int32_t) * (size_t)g->n_long));
-    GAD_HIP_G(hipMalloc((void**)&g->long_first, sizeof(int32_t) * (size_t)g->n_long));
-    GAD_HIP_G(hipMalloc((void**)&g->chunk_row, sizeof(int32_t) * (size_t)g->n_chunks));
-    GAD_HIP_G(hipMalloc((void**)&g->chunk_begin, sizeof(int32_t) * (size_t)g->n_chunks));
-    GAD_HIP_G(hipMalloc((void**)&g->chunk_perm, sizeof(int32_t) * (size_t)g->n_chunks));
-    fill_long_rows<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(n, chunk_first, long_slot, is_long, g->long_row,
-                                                              g->long_first);
-    GAD_HIP_G(hipGetLastError());
-    uint64_t *ck = alt, *ck_alt = cur;  // n_chunks < n_keys entries each
-    fill_chunks<<<(unsigned)g->n_long, 256, 0, s>>>(g->rowptr, g->colidx, g->long_row, g->long_first, g->chunk_row,
-                                                    g->chunk_begin, ck);
-    GAD_HIP_G(hipGetLastError());
-    for (int shift = 32; shift < 32 + bits; shift += 8) {      // order the chunks by their first column
-      int st = radix_pass(ck, ck_alt, (uint32_t)g->n_chunks, shift, hist, tile_tmp, flags + 3, s);
-      if (st != GAD_OK) return fail(st);
-      uint64_t* t = ck;
-      ck = ck_alt;
-      ck_alt = t;
-    }
-    take_low32<<<(unsigned)ceil_div(g->n_chunks, 256), 256, 0, s>>>(ck, g->n_chunks, g->chunk_perm);
-    GAD_HIP_G(hipGetLastError());
-  }
-  GAD_HIP_G(hipStreamSynchronize(s));
 #undef GAD_HIP_G
   *out = g;
   return GAD_OK;

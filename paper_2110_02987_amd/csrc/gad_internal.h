@@ -90,6 +90,9 @@ size_t scan_tmp_len(size_t n);
 // Importance-based augmentation (Section 3.2.2, Algorithm 1); augment.hip.
 int augment_subgraph(const gad_graph* G, const int64_t* part, int64_t n_part, int walk_len, int64_t budget, uint64_t seed,
                      int64_t max_walks, int64_t* halo_out, int64_t* n_halo_out, int64_t* n_walks_out, hipStream_t s);
+int build_schedule(gad_graph* g, hipStream_t s);
+// Block-diagonal union of K graphs (rows of block k shifted by the rows before it) with a schedule of its own.
+int graph_concat(const gad_graph* const* graphs, int K, hipStream_t s, gad_graph** out);
 // Node matrices are float32 or bfloat16 (gad_dtype); weights, partial sums and logits are float32.
 // out = A~ T with the epilogue applied; epi.aux (EPI_MASK) has T's storage type.  `partial` holds the chunk sums
 // of the long rows: spmm_partial_floats(g, width) floats (may be NULL when that is 0).
@@ -117,8 +120,8 @@ int transpose_f32(const float* in, int rows, int cols, float* out, hipStream_t s
 
 // Z [n x C] (ldz, float32) -> G [n x C] (ldg, storage type tg), loss (double, device).
 size_t softmax_partial_doubles(int64_t n);
-int softmax_xent(const float* Z, int64_t ldz, const int32_t* labels, const uint8_t* mask, float scale, int64_t n, int C,
-                 void* G, int64_t ldg, gad_dtype tg, double* block_partials, double* loss_out, hipStream_t s);
+int softmax_xent(const float* Z, int64_t ldz, const int32_t* labels, const uint8_t* mask, float scale,
+                 const float* row_scale /* [n] or NULL */, int64_t n, int C, void* G, int64_t ldg, gad_dtype tg, double* block_partials, double* loss_out, hipStream_t s);
 int copy_rows(const void* in, int64_t ldi, gad_dtype ti, float* out, int64_t ldo, int64_t n, int width, hipStream_t s);
 size_t variance_scratch_doubles(int64_t n);
 // mean[c] = (1/n) sum_i V[i][c] in float64 (ordered sums); part: kVarBlocks x F doubles of scratch.

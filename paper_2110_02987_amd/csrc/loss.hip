@@ -29,8 +29,9 @@ __device__ __forceinline__ float group_sum(float v) {
 template <typename TG>
 __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restrict__ Z, int64_t ldz,
                                                            const int32_t* __restrict__ labels,
-                                                           const uint8_t* __restrict__ mask, float scale, int64_t n,
-                                                           int C, TG* __restrict__ G, int64_t ldg,
+                                                           const uint8_t* __restrict__ mask, float scale,
+                                                           const float* __restrict__ row_scale, int64_t n, int C,
+                                                           TG* __restrict__ G, int64_t ldg,
                                                            double* __restrict__ block_partials) {
   __shared__ double row_loss[kRowsPerBlock];
   const int grp = threadIdx.x / kGroup, l = threadIdx.x % kGroup;
@@ -46,13 +47,14 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restri
     se = group_sum(se);
     const int32_t y = labels[i];
     const bool on = (mask == nullptr || mask[i] != 0) && y >= 0 && y < C;
-    const float g_scale = on ? scale : 0.f;
+    const float sc = row_scale ? scale * row_scale[i] : scale;       // per-node weight of the loss (NULL = 1)
+    const float g_scale = on ? sc : 0.f;
     const float inv = 1.f / se;
     for (int c = l; c < C; c += kGroup) {
       const float p = expf(z[c] - m) * inv;
       G[i * ldg + c] = from_f32<TG>(g_scale * (p - (c == y ? 1.f : 0.f)));
     }
-    if (on && l == 0) my_loss = (double)scale * ((double)logf(se) + (double)m - (double)z[y]);
+    if (on && l == 0) my_loss = (double)sc * ((double)logf(se) + (double)m - (double)z[y]);
   }
   if (l == 0) row_loss[grp] = my_loss;
   __syncthreads();
@@ -92,16 +94,16 @@ __global__ void copy_rows_kernel(const TI* __restrict__ in, int64_t ldi, float* 
 
 size_t softmax_partial_doubles(int64_t n) { return (size_t)ceil_div(n, kRowsPerBlock) + 1; }
 
-int softmax_xent(const float* Z, int64_t ldz, const int32_t* labels, const uint8_t* mask, float scale, int64_t n, int C,
-                 void* G, int64_t ldg, gad_dtype tg, double* block_partials, double* loss_out, hipStream_t s) {
+int softmax_xent(const float* Z, int64_t ldz, const int32_t* labels, const uint8_t* mask, float scale,
+                 const float* row_scale, int64_t n, int C, void* G, int64_t ldg, gad_dtype tg, double* block_partials, double* loss_out, hipStream_t s) {
   if (n == 0) return GAD_OK;
   const int64_t blocks = ceil_div(n, kRowsPerBlock);
   if (tg == GAD_F32)
-    softmax_xent_kernel<float><<<(unsigned)blocks, 256, 0, s>>>(Z, ldz, labels, mask, scale, n, C, (float*)G, ldg,
-                                                                block_partials);
+    softmax_xent_kernel<float><<<(unsigned)blocks, 256, 0, s>>>(Z, ldz, labels, mask, scale, row_scale, n, C, (float*)G,
+                                                                ldg, block_partials);
   else
-    softmax_xent_kernel<bf16_t><<<(unsigned)blocks, 256, 0, s>>>(Z, ldz, labels, mask, scale, n, C, (bf16_t*)G, ldg,
-                                                                 block_partials);
+    softmax_xent_kernel<bf16_t><<<(unsigned)blocks, 256, 0, s>>>(Z, ldz, labels, mask, scale, row_scale, n, C,
+                                                                 (bf16_t*)G, ldg, block_partials);
   GAD_LAUNCH_CHECK();
   if (loss_out) {
     sum_doubles<<<1, 256, 0, s>>>(block_partials, blocks, loss_out);

@@ -16,11 +16,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgad.so")
 
 F32, BF16 = 0, 1
-SYMBOLS = ["gad_last_error", "gad_build_subgraph", "gad_graph_info", "gad_graph_destroy", "gad_augment_subgraph",
+SYMBOLS = ["gad_last_error", "gad_build_subgraph", "gad_graph_info", "gad_graph_destroy", "gad_graph_concat", "gad_augment_subgraph",
            "gad_gcn_workspace_bytes", "gad_gcn_forward", "gad_gcn_backward", "gad_gcn_activation", "gad_spmm_workspace_bytes", "gad_spmm",
            "gad_gemm_workspace_bytes", "gad_gemm_w", "gad_gemm_tn",
            "gad_subgraph_variance", "gad_pair_importance_workspace_bytes", "gad_pair_importance",
-           "gad_weighted_consensus", "gad_consensus_update", "gad_train_round"]
+           "gad_weighted_consensus", "gad_consensus_update", "gad_train_round", "gad_train_round_batched"]
 
 _lib = None
 _hip = None
@@ -135,6 +135,14 @@ def augment_subgraph(G: Graph, part_rows: torch.Tensor, walk_len: int, budget: i
     return out[: n_halo.value], n_walks.value
 
 
+def graph_concat(graphs: List[Graph]) -> Graph:
+    """Block-diagonal union of the graphs (rows of graphs[k] follow those of graphs[0..k-1])."""
+    gh = (C.c_void_p * len(graphs))(*[g.handle.value for g in graphs])
+    h = C.c_void_p()
+    _check(lib().gad_graph_concat(gh, C.c_int(len(graphs)), _stream(), C.byref(h)))
+    return Graph(h)
+
+
 def _dims(dims: Sequence[int]):
     return (C.c_int32 * len(dims))(*dims)
 
@@ -156,7 +164,7 @@ def alloc_workspace(g: Graph, dims: Sequence[int], dtype: int = F32) -> torch.Te
 def gcn_forward(g: Graph, X: torch.Tensor, dims: Sequence[int], W: List[torch.Tensor], labels: torch.Tensor,
                 mask: Optional[torch.Tensor], loss_scale: float, workspace: torch.Tensor,
                 logits_out: Optional[torch.Tensor] = None, loss_out: Optional[torch.Tensor] = None,
-                dtype: int = F32, negative_slope: float = 0.0) -> None:
+                dtype: int = F32, negative_slope: float = 0.0, row_scale: Optional[torch.Tensor] = None) -> None:
     _dev(X, torch.float32 if dtype == F32 else torch.bfloat16, "X")
     _dev(labels, torch.int32, "labels")
     if mask is not None:
@@ -167,8 +175,10 @@ def gcn_forward(g: Graph, X: torch.Tensor, dims: Sequence[int], W: List[torch.Te
         _dev(logits_out, torch.float32, "logits_out")
     if loss_out is not None:
         _dev(loss_out, torch.float64, "loss_out")
+    if row_scale is not None:
+        _dev(row_scale, torch.float32, "row_scale")
     _check(lib().gad_gcn_forward(g.handle, _ptr(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims), _ptr_array(W),
-                                 _ptr(labels), _ptr(mask), C.c_float(loss_scale), C.c_float(negative_slope), _ptr(workspace),
+                                 _ptr(labels), _ptr(mask), C.c_float(loss_scale), _ptr(row_scale), C.c_float(negative_slope), _ptr(workspace),
                                  C.c_size_t(workspace.numel()), _ptr(logits_out), _ptr(loss_out), _stream()))
 
 
@@ -303,3 +313,17 @@ def train_round(graphs: List[Graph], X: List[torch.Tensor], dims: Sequence[int],
                                  _ptr(params), _ptr_array(labels), mk, ls, C.c_float(negative_slope), _ptr_array(workspaces), wb,
                                  _ptr(grads), z,
                                  C.c_float(eta), _ptr(losses), _stream()))
+
+
+def train_round_batched(g: Graph, X: torch.Tensor, dims: Sequence[int], params: torch.Tensor, labels: torch.Tensor,
+                        mask: Optional[torch.Tensor], row_scale: torch.Tensor, workspace: torch.Tensor, grad: torch.Tensor,
+                        eta: float, loss: Optional[torch.Tensor] = None, dtype: int = F32,
+                        negative_slope: float = 0.0) -> None:
+    _dev(params, torch.float32, "params")
+    _dev(grad, torch.float32, "grad")
+    _dev(row_scale, torch.float32, "row_scale")
+    _dev(labels, torch.int32, "labels")
+    _check(lib().gad_train_round_batched(g.handle, _ptr(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims),
+                                         _ptr(params), _ptr(labels), _ptr(mask), _ptr(row_scale),
+                                         C.c_float(negative_slope), _ptr(workspace), C.c_size_t(workspace.numel()),
+                                         _ptr(grad), C.c_float(eta), _ptr(loss), _stream()))

@@ -553,3 +553,62 @@ def test_train_rounds_match_oracle(gad):
     with pytest.raises(gad.GadError) as e:
         gad.train_round(graphs, Xd, dims, params, yd, md, cs, wss, grads, [0.0] * K, eta, losses)
     assert e.value.status == -6 and torch.equal(before, params)
+
+
+def test_batched_round_on_union_matches_looped_round_and_oracle(gad):
+    """Several subgraphs of one processor as ONE block-diagonal graph (gad_graph_concat): a forward / backward pass
+    with per-node loss weights c_k zeta_k / sum zeta yields the weighted consensus gradient of Eq. 15 directly.
+    Checked against the oracle's loop over the subgraphs and against gad_train_round on the same inputs."""
+    dims, K, eta, rounds = (32, 48, 24, 6), 5, 0.5, 4
+    import dataclasses
+    cfgs = [dataclasses.replace(wl.CONFIGS["products_small"], n_local=2000 + 700 * k, n_halo=300, max_degree=900)
+            for k in range(K)]
+    graphs, refs, Xs, ys, ms, cs = [], [], [], [], [], []
+    for k, cfg in enumerate(cfgs):
+        g, ref = build_both(gad, wl.make_graph(cfg, seed=10 + k))
+        X = wl.make_features(cfg.n, dims[0], seed=10 + k)
+        graphs.append(g); refs.append(ref); Xs.append(X)
+        ys.append(wl.make_planted_labels(X, dims[-1]))
+        ms.append(wl.make_mask(cfg)); cs.append(1.0 / ms[-1].sum())
+    U = gad.graph_concat(graphs)
+    Uref = T1.concat(refs)
+    assert_csr_equal(U, Uref)                                   # rows, columns, degrees and normalisation of the union
+    assert max(r.deg.max() for r in refs) > 128                 # the union has long rows: its own chunk schedule is used
+    zeta = [0.9, 0.2, 1.4, 0.6, 1.1]
+    w = np.asarray(zeta) / np.sum(zeta)
+    row_scale = np.concatenate([np.full(r.n, c * wk, dtype=np.float32) for r, c, wk in zip(refs, cs, w)])
+    Xu, yu, mu = np.concatenate(Xs), np.concatenate(ys), np.concatenate(ms)
+    Ws = wl.make_weights(dims)
+    flat = np.concatenate([w_.ravel() for w_ in Ws])
+    P = flat.size
+    # one pass: SpMM on the union equals the per-block products
+    T = np.random.default_rng(0).standard_normal((U.n, 40)).astype(np.float32)
+    out = torch.empty((U.n, 40), device="cuda")
+    gad.spmm(U, dev(T), out)
+    assert rel_err(out.cpu().numpy(), T1.spmm(Uref, T.astype(np.float64))) < TOL
+    # batched rounds
+    params_b, grad_b = dev(flat), torch.empty(P, device="cuda")
+    loss_b = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ws_u = gad.alloc_workspace(U, dims)
+    # looped rounds (gad_train_round) and the oracle
+    params_l, grads_l = dev(flat), torch.empty(K * P, device="cuda")
+    losses_l = torch.zeros(K, dtype=torch.float64, device="cuda")
+    wss = [gad.alloc_workspace(g, dims) for g in graphs]
+    Xd, yd, md = [dev(x) for x in Xs], [dev(y) for y in ys], [dev(m) for m in ms]
+    Xud, yud, mud, rsd = dev(Xu), dev(yu), dev(mu), dev(row_scale)
+    W_ref = [w_.astype(np.float64) for w_ in Ws]
+    for r in range(rounds):
+        gad.train_round_batched(U, Xud, dims, params_b, yud, mud, rsd, ws_u, grad_b, eta, loss_b)
+        gad.train_round(graphs, Xd, dims, params_l, yd, md, cs, wss, grads_l, zeta, eta, losses_l)
+        W_ref, l_ref, g_ref = T1.train_round(refs, Xs, W_ref, ys, ms, cs, zeta, eta)
+        assert abs(loss_b.item() - float(np.dot(w, l_ref))) <= 2e-4 * abs(float(np.dot(w, l_ref))), f"round {r}"
+        if r == 0:
+            assert rel_err(grad_b.cpu().numpy(), np.concatenate([g_.ravel() for g_ in g_ref])) < TOL
+    flat_ref = np.concatenate([w_.ravel() for w_ in W_ref])
+    got_b, got_l = params_b.cpu().numpy().astype(np.float64), params_l.cpu().numpy().astype(np.float64)
+    assert rel_err(got_b, flat_ref) < TOL and rel_err(got_l, flat_ref) < TOL
+    assert rel_err(got_b - flat, flat_ref - flat) < 2e-3 and rel_err(got_b - flat, got_l - flat) < 2e-3
+    with pytest.raises(gad.GadError) as e:
+        gad.graph_concat([])
+    assert e.value.status == -2
+

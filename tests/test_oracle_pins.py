@@ -601,3 +601,59 @@ def test_train_round_weighted_consensus_properties():
         tot = sum(zk * lk for zk, lk in zip(z, losses)) / sum(z)
         assert prev is None or tot < prev
         prev = tot
+
+
+def test_weighted_loss_on_block_diagonal_union_is_the_weighted_consensus():
+    """Eq. 15 through linearity: the gradient of sum_k w_k L_k, taken in ONE pass over the block-diagonal union of
+    the subgraphs with per-node loss weights c_k w_k, equals the weighted consensus sum_k w_k grad_k of the
+    per-subgraph gradients; and per-node weights agree with torch's weighted cross-entropy."""
+    dims, K = (5, 7, 4), 3
+    probs = [_random_problem(40 + 10 * k, 160, dims, seed=20 + k, n_halo=6) for k in range(K)]
+    Ws = [np.random.default_rng(1).standard_normal((dims[l], dims[l + 1])) * 0.4 for l in range(2)]
+    graphs = [T1.build(**p[0]) for p in probs]
+    zeta = np.array([0.7, 0.1, 1.9])
+    w = zeta / zeta.sum()
+    cs = [1.0 / p[4].sum() for p in probs]
+    grads, losses = [], []
+    for g, (_, X, _, y, m), c in zip(graphs, probs, cs):
+        f = T1.forward(g, X, Ws, y, m, c)
+        grads.append(T1.backward(g, Ws, f, y, m, c)[0])
+        losses.append(f["loss"])
+    U = T1.concat(graphs)
+    assert U.n == sum(g.n for g in graphs) and U.nnz == sum(g.nnz for g in graphs)
+    assert np.array_equal(U.deg, np.concatenate([g.deg for g in graphs]))
+    X = np.concatenate([p[1] for p in probs])
+    y = np.concatenate([p[3] for p in probs])
+    m = np.concatenate([p[4] for p in probs])
+    c_rows = np.concatenate([np.full(g.n, c * wk) for g, c, wk in zip(graphs, cs, w)])
+    f = T1.forward(U, X, Ws, y, m, c_rows)
+    dW, _ = T1.backward(U, Ws, f, y, m, c_rows)
+    assert f["loss"] == pytest.approx(float(np.dot(w, losses)), rel=1e-12)
+    for l in range(2):
+        assert np.allclose(dW[l], T1.weighted_consensus([g[l] for g in grads], zeta), rtol=1e-11, atol=1e-14)
+    # a constant weight vector is the scalar scale; the dense tier agrees
+    g0, (gr0, X0, _, y0, m0) = graphs[0], probs[0]
+    f_s, f_v = T1.forward(g0, X0, Ws, y0, m0, 0.25), T1.forward(g0, X0, Ws, y0, m0, np.full(g0.n, 0.25))
+    assert f_v["loss"] == pytest.approx(f_s["loss"], rel=1e-13)
+    for a, b in zip(T1.backward(g0, Ws, f_s, y0, m0, 0.25)[0], T1.backward(g0, Ws, f_v, y0, m0, np.full(g0.n, 0.25))[0]):
+        assert np.allclose(a, b, rtol=1e-13, atol=0)
+    At = T0.normalized_adjacency(T0.adjacency_dense(**gr0))
+    cv = np.random.default_rng(2).random(g0.n) + 0.1
+    fd = T0.forward(At, X0, Ws, y0, m0, cv)
+    fc = T1.forward(g0, X0, Ws, y0, m0, cv)
+    assert fd["loss"] == pytest.approx(fc["loss"], rel=1e-12)
+    for a, b in zip(T0.backward(At, Ws, fd, y0, m0, cv)[0], T1.backward(g0, Ws, fc, y0, m0, cv)[0]):
+        assert np.allclose(a, b, rtol=1e-10, atol=1e-13)
+    # torch: cross-entropy per node, weighted, through autograd
+    Wt = [torch.tensor(W_, dtype=torch.float64, requires_grad=True) for W_ in Ws]
+    A_t = torch.tensor(At)
+    H = torch.tensor(X0)
+    H = torch.relu(A_t @ H @ Wt[0])
+    Z = A_t @ H @ Wt[1]
+    per = torch.nn.functional.cross_entropy(Z, torch.tensor(y0, dtype=torch.long), reduction="none")
+    loss = (per * torch.tensor(cv * m0)).sum()
+    loss.backward()
+    assert loss.item() == pytest.approx(fd["loss"], rel=1e-12)
+    for a, b in zip(T0.backward(At, Ws, fd, y0, m0, cv)[0], Wt):
+        assert np.allclose(a, b.grad.numpy(), rtol=1e-9, atol=1e-12)
+
