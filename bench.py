@@ -209,6 +209,29 @@ def main() -> int:
         gemm[f"{K_}x{N_}"] = res
         del A_, G_, C_, dW_, gws
 
+    # ---- the rows built beyond the per-iteration step, each timed once on this workload's graph (not part of `value`)
+    extras = {}
+    if not args.kernels_only:
+        def timed(fn):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            r = fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3, r
+        # Algorithm 1 with this graph in the role of the original graph: partition = the first half of its rows
+        part = torch.arange(g.n // 2, dtype=torch.int64, device="cuda")
+        ms, (halo, n_walks) = timed(lambda: gad.augment_subgraph(g, part, L, g.n // 20, 1))
+        extras["augment_subgraph"] = dict(ms=ms, n_part=int(part.numel()), walk_len=L, budget=g.n // 20,
+                                          n_walks=int(n_walks), n_halo=int(halo.numel()))
+        # Eq. 14 with the distance inside the pair sum, all pairs, on the last layer's per-node gradients
+        out2 = torch.zeros(2, dtype=torch.float64, device="cuda")
+        ms, _ = timed(lambda: gad.pair_importance(g, G_last, 1.0, out2))
+        pairs = g.n * (g.n - 1) / 2
+        extras["pair_importance"] = dict(ms=ms, pairs=pairs, F=int(G_last.shape[1]), pairs_per_s=pairs / (ms * 1e-3),
+                                         zeta_pair=float(out2[0].item()))
+        del part, halo
+
     out = dict(metric="GCN fwd+bwd edges/s per layer and epoch ms per subgraph; SpMM % of HBM peak",
                value=value, unit="edges/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step,
                higher_is_better=True, scaling="weak", vs_baseline=None, dtype=cfg.dtype, data="synthetic",
@@ -216,7 +239,7 @@ def main() -> int:
                                     f"GCN {'-'.join(map(str, dims))}, consensus K={K}",
                            n=g.n, nnz=g.nnz, dims=dims),
                epoch_ms=epoch_ms, forward_ms=fwd_ms, backward_ms=bwd_ms, variance_consensus_ms=tail_ms,
-               build_ms=build_ms, spmm={str(k): v for k, v in spmm.items()}, gemm=gemm,
+               build_ms=build_ms, spmm={str(k): v for k, v in spmm.items()}, gemm=gemm, extras=extras,
                mfma_peak_TFLOPs=mfma_peak, roofline=roofline)
 
     # ---- the oracle, as it stands, on the host cores (reported baseline, not a target)

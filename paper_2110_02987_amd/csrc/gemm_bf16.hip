@@ -21,21 +21,13 @@
 // (consecutive workgroup ids go to different XCDs, each with an L2 of its own).
 #include "dtype.h"
 #include "gad_internal.h"
+#include "xcd.h"
 
 namespace gad {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
-
-constexpr int kXcds = 8;
-
-// Workgroup id -> work item such that the items of one XCD are consecutive (bijection on [0, total)).
-__device__ __forceinline__ int64_t xcd_order(int64_t bid, int64_t total) {
-  const int64_t per = total / kXcds, rem = total % kXcds;
-  const int64_t x = bid % kXcds, slot = bid / kXcds;
-  return x * per + (x < rem ? x : rem) + slot;
-}
 
 // Row of accumulator register r of a 32x32 MFMA result held by `lane` (its column is lane % 32).
 __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }

@@ -6,8 +6,9 @@
 //     ||v_i - v_j||^2 = ||v_i||^2 + ||v_j||^2 - 2 v_i . v_j,
 // taken on vectors that were first centred on the subgraph mean (identical vectors then give exactly 0, which the
 // paper's worked example needs, and the magnitudes that cancel are as small as they can be).  The difference of
-// large numbers loses accuracy only for pairs that are close compared with their norms; for those
-// (d^2 < kNear (||v_i||^2 + ||v_j||^2)) the squared distance is recomputed from the coordinate differences.
+// large numbers loses accuracy only for pairs that are close compared with their norms; where that loss could
+// show in the pair's term (see kGramErr / kTermTol) the squared distance is recomputed from the coordinate
+// differences.
 // The tile epilogue applies 1 / (sqrt(d^2) + beta) and the degree product; tile sums are float64 and are added
 // in a fixed order (per block, then over blocks), so the result is reproducible bit for bit.
 #include <math.h>
@@ -18,7 +19,11 @@
 namespace gad {
 namespace {
 
-constexpr float kNear = 1e-2f;
+// A squared distance from the Gram tile carries an absolute error of about kGramErr (||v_i||^2 + ||v_j||^2); it is
+// recomputed from coordinate differences when that error could move the pair's term by more than kTermTol of
+// its value (the error of d is at most delta / (d + sqrt(delta)); the term is 1 / (d + beta)).
+constexpr float kGramErr = 1e-6f;
+constexpr float kTermTol = 2e-5f;
 
 // Vc[i][c] = float(v_ic - mean_c) for c < F, 0 for F <= c < ldv;  nrm[i] = sum_c Vc[i][c]^2 (of the rounded
 // values, so that the norm and the matrix product describe the same vectors);  degf[i] = float(deg_i).
@@ -148,17 +153,23 @@ __global__ __launch_bounds__(256) void pair_tiles(const float* __restrict__ Vc, 
         if (gi < gj && gj < n) {
           const float ni = info[0][rl];
           float d2 = fmaxf(ni + nj - 2.f * acc[tm][tn][r], 0.f);
-          if (d2 < kNear * (ni + nj)) {   // close pair: the difference of norms and product has lost its digits
-            const float* a = Vc + gi * ldv;
-            const float* b = Vc + gj * ldv;
+          float d = sqrtf(d2);
+          const float delta = kGramErr * (ni + nj);
+          if (delta > kTermTol * (d + sqrtf(delta)) * (d + beta)) {   // close pair whose lost digits would show
+            const float4* a = reinterpret_cast<const float4*>(Vc + gi * ldv);
+            const float4* b = reinterpret_cast<const float4*>(Vc + gj * ldv);
             float e = 0.f;
-            for (int c = 0; c < K; ++c) {
-              const float d = a[c] - b[c];
-              e = fmaf(d, d, e);
+            for (int c = 0; c < K / 4; ++c) {
+              const float4 x = a[c], y = b[c];
+              const float d0 = x.x - y.x, d1 = x.y - y.y, d2_ = x.z - y.z, d3 = x.w - y.w;
+              e = fmaf(d0, d0, e);
+              e = fmaf(d1, d1, e);
+              e = fmaf(d2_, d2_, e);
+              e = fmaf(d3, d3, e);
             }
-            d2 = e;
+            d = sqrtf(e);
           }
-          sum += info[1][rl] * dj / (sqrtf(d2) + beta);
+          sum += info[1][rl] * dj / (d + beta);
         }
       }
     }

@@ -423,6 +423,13 @@ def test_pair_importance_close_and_identical_vectors(gad):
         gad.pair_importance(g, dev(V), beta, out2)
         z = T1.zeta_pairs(ref, V, beta)
         assert abs(out2[0].item() - z) <= TOL * z, beta
+    # the same clusters at the scale of per-node gradients: against beta = 1 no distance needs its lost digits
+    # back, against a beta of the vectors' own scale the close ones do
+    Vs = (V * np.float32(1e-6)).astype(np.float32)
+    for beta in (1.0, 1e-4, 1e-8):
+        gad.pair_importance(g, dev(Vs), beta, out2)
+        z = T1.zeta_pairs(ref, Vs, beta)
+        assert abs(out2[0].item() - z) <= TOL * z, beta
     for pairs, printed in (([(0, 1), (1, 2), (2, 3), (3, 0)], 3.75), ([(0, 1), (1, 2), (2, 3)], 3.61),
                            ([(0, 1), (0, 2), (0, 3), (1, 2)], 3.59)):
         src = dev(np.array([a for a, _ in pairs], dtype=np.int64))
@@ -611,4 +618,56 @@ def test_batched_round_on_union_matches_looped_round_and_oracle(gad):
     with pytest.raises(gad.GadError) as e:
         gad.graph_concat([])
     assert e.value.status == -2
+
+
+def test_training_step_under_hip_graph_capture(gad):
+    """The per-iteration calls enqueue kernels only (no allocation, no synchronisation, no memset node), so a whole
+    round can be captured into a HIP graph and replayed.  Every replay is checked against the eager result, with
+    eager work and synchronisations between the replays."""
+    import dataclasses
+    dims, eta = (24, 40, 8), 0.3
+    cfg = dataclasses.replace(wl.CONFIGS["products_small"], n_local=5000, n_halo=600, max_degree=700)
+    g, ref = build_both(gad, wl.make_graph(cfg, seed=3))
+    assert ref.deg.max() > 128                                   # chunked rows and their reduction are in the graph too
+    X = wl.make_features(cfg.n, dims[0], seed=3)
+    y = wl.make_planted_labels(X, dims[-1])
+    m = wl.make_mask(cfg)
+    flat = np.concatenate([w_.ravel() for w_ in wl.make_weights(dims)])
+    Xd, yd, md = dev(X), dev(y), dev(m)
+    rs = dev(np.full(cfg.n, 1.0 / m.sum(), dtype=np.float32))
+    ws = gad.alloc_workspace(g, dims)
+    out3 = torch.zeros(3, dtype=torch.float64, device="cuda")
+
+    def round_(params, grad, loss):
+        gad.train_round_batched(g, Xd, dims, params, yd, md, rs, ws, grad, eta, loss)
+        gad.subgraph_variance(g, Xd, 1.0, out3)
+
+    # eager reference: three rounds
+    p_e, g_e, l_e = dev(flat), torch.empty(flat.size, device="cuda"), torch.zeros(1, dtype=torch.float64, device="cuda")
+    eager = []
+    for _ in range(3):
+        round_(p_e, g_e, l_e)
+        torch.cuda.synchronize()
+        eager.append((p_e.clone(), l_e.item(), out3[0].item()))
+    # captured: warm up on a side stream (first-use set-up happens outside the capture), capture one round, replay
+    p_c, g_c, l_c = dev(flat), torch.empty(flat.size, device="cuda"), torch.zeros(1, dtype=torch.float64, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        round_(p_c.clone(), g_c, l_c)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        round_(p_c, g_c, l_c)
+    p_c.copy_(dev(flat))                                         # the capture itself does not run the kernels
+    for r in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(p_c, eager[r][0]), f"replay {r}"      # same kernels, same order: bit-identical
+        assert l_c.item() == eager[r][1] and out3[0].item() == eager[r][2]
+        scratch = torch.randn(1 << 20, device="cuda").sum().item()       # eager work between the replays
+        gad.spmm(g, Xd, torch.empty_like(Xd))
+        torch.cuda.synchronize()
+        assert np.isfinite(scratch)
 
