@@ -48,18 +48,42 @@ __global__ void mark_part(const int64_t* __restrict__ part, int64_t n_part, int6
   if (atomicExch(&mark[v], 1u) != 0u) flags[1] = 1u;
 }
 
-// is_b[p] = 1 iff part[p] has a neighbour outside the partition; deg_b[p] = its degree then (else 0)
-__global__ void boundary_flags(const int64_t* __restrict__ part, int64_t n_part, const int64_t* __restrict__ rowptr,
-                               const int32_t* __restrict__ colidx, const uint32_t* __restrict__ mark,
-                               uint32_t* __restrict__ is_b, uint32_t* __restrict__ deg_b) {
-  int64_t p = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (p >= n_part) return;
-  const int64_t v = part[p];
-  const int64_t b = rowptr[v], e = rowptr[v + 1];
-  bool out = false;
-  for (int64_t q = b; q < e && !out; ++q) out = mark[colidx[q]] == 0u;      // the self loop is inside
-  is_b[p] = out ? 1u : 0u;
-  deg_b[p] = out ? (uint32_t)(e - b - 1) : 0u;
+// is_b[p] = 1 iff part[p] has a neighbour outside the partition; deg_b[p] = its degree then (else 0).
+// A 16-lane group owns one row and looks at 64 of its entries per step (columns ascend, so the members of a
+// partition made of low ids all come first: one thread per row would walk half of every hub row alone).
+__global__ __launch_bounds__(256) void boundary_flags(const int64_t* __restrict__ part, int64_t n_part,
+                                                      const int64_t* __restrict__ rowptr,
+                                                      const int32_t* __restrict__ colidx,
+                                                      const uint32_t* __restrict__ mark, uint32_t* __restrict__ is_b,
+                                                      uint32_t* __restrict__ deg_b) {
+  const int l = threadIdx.x & 15;
+  const int64_t p = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) >> 4;
+  const bool live = p < n_part;                      // all lanes of a wave stay in the loop's shuffles
+  int64_t b = 0, e = 0;
+  if (live) {
+    const int64_t v = part[p];
+    b = rowptr[v];
+    e = rowptr[v + 1];
+  }
+  int out = 0;
+  for (int64_t q0 = b; ; q0 += 64) {
+    int more = (q0 < e && !out) ? 1 : 0;
+    // the wave leaves the loop together: when none of its four groups has entries left to look at
+    if (__ballot(more) == 0ull) break;
+    if (more) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int64_t q = q0 + u * 16 + l;
+        if (q < e && mark[colidx[q]] == 0u) out = 1;   // the self loop is inside
+      }
+    }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) out |= __shfl_xor(out, o, 16);
+  }
+  if (live && l == 0) {
+    is_b[p] = out ? 1u : 0u;
+    deg_b[p] = out ? (uint32_t)(e - b - 1) : 0u;
+  }
 }
 
 __global__ void compact_boundary(const int64_t* __restrict__ part, int64_t n_part, const uint32_t* __restrict__ is_b,
@@ -233,7 +257,7 @@ int augment_subgraph(const gad_graph* G, const int64_t* part, int64_t n_part, in
   const size_t max_items = (size_t)(N > n_part ? N : n_part);
   GAD_HIP(scratch.alloc(&tile_tmp, scan_tmp_len(max_items > sort_hist_len((uint32_t)max_walks) ? max_items
                                                                                                 : sort_hist_len((uint32_t)max_walks))));
-  boundary_flags<<<blocks(n_part), 256, 0, s>>>(part, n_part, G->rowptr, G->colidx, mark, is_b, deg_b);
+  boundary_flags<<<blocks(n_part * 16), 256, 0, s>>>(part, n_part, G->rowptr, G->colidx, mark, is_b, deg_b);
   GAD_LAUNCH_CHECK();
   GAD_HIP(hipMemcpyAsync(pos, is_b, (size_t)n_part * sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
   int st = scan_u32(pos, (uint32_t)n_part, tile_tmp, flags + 2, s);

@@ -21,40 +21,97 @@
 namespace gad {
 namespace {
 
-template <int EPI, int TNW, typename TC, typename TX>
-__device__ __forceinline__ void store_acc(const v16f (&acc)[2][TNW], TC* __restrict__ C, int64_t ldc, int64_t row0,
-                                          int col0, int64_t M, int N, int wm, int wn, float slope,
-                                          const TX* __restrict__ aux, int64_t ldaux) {
+// Row stride (floats) of a wave's staging block in the epilogue: rows 4 apart, which the two halves of a wave
+// write together, fall on different halves of the LDS banks.
+template <int TNW>
+constexpr int stage_ld() { return 32 * TNW + 8; }
+
+// LDS bytes of a block: the two operand tiles, reused by the epilogue as four staging blocks of 32 rows.
+template <int TNW>
+constexpr size_t block_lds_bytes() {
+  constexpr size_t tiles = 2 * sizeof(Tile<TNW>), stage = 4 * 32 * stage_ld<TNW>() * sizeof(float);
+  return tiles > stage ? tiles : stage;
+}
+
+// Epilogue: the accumulators of a wave (64 rows x 32 TNW columns, held column-per-lane) go through a
+// wave-private LDS block, 32 rows at a time, and leave as 16-byte row pieces, so that a wave instruction writes
+// (and, for the mask, reads) whole rows instead of 32-float column strips.  The mask values of a pass are requested
+// before the accumulators are staged.  Entered by all four waves after the last read of the operand tiles.
+// c_vec / aux_vec: 16-byte accesses allowed at any column that is a multiple of 4 (alignment checked on the host).
+template <int EPI, int TNW>
+__device__ __forceinline__ void store_acc(const v16f (&acc)[2][TNW], float* __restrict__ lds, float* __restrict__ C,
+                                          int64_t ldc, int64_t row0, int col0, int64_t M, int N, int wm, int wn,
+                                          float slope, const float* __restrict__ aux, int64_t ldaux, bool c_vec,
+                                          bool aux_vec) {
+  constexpr int W = 32 * TNW, LD = stage_ld<TNW>();
+  constexpr int LPR = W / 4;            // lanes per row, one 16-byte piece each
+  constexpr int RPI = 64 / LPR;         // rows per wave instruction
+  constexpr int NI = 32 / RPI;          // wave instructions per 32-row pass
   const int lane = threadIdx.x & 63;
+  float* mine = lds + (threadIdx.x >> 6) * (32 * LD);
+  const int rl = lane / LPR, cl = (lane % LPR) * 4;
+  const int col = col0 + wn * W + cl;
+  const bool full = col + 4 <= N;
 #pragma unroll
-  for (int tm = 0; tm < 2; ++tm)
+  for (int tm = 0; tm < 2; ++tm) {
+    const int64_t rbase = row0 + wm * 64 + tm * 32 + rl;
+    float m[NI][4];
+    if (EPI == EPI_MASK) {
 #pragma unroll
-    for (int tn = 0; tn < TNW; ++tn) {
-      const int col = col0 + wn * 32 * TNW + tn * 32 + (lane & 31);
+      for (int i = 0; i < NI; ++i) {
+        const int64_t row = rbase + i * RPI;
+        const float* ap = aux + row * ldaux + col;
+        if (row < M && full && aux_vec) {
+          load_row_piece<4, float>(ap, m[i]);
+        } else {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t row = row0 + wm * 64 + tm * 32 + acc_row(r, lane);
-        if (row < M && col < N) {
-          float v = acc[tm][tn][r];
-          if (EPI == EPI_RELU) v = leaky(v, v > 0.f, slope);
-          if (EPI == EPI_MASK) v = leaky(v, to_f32<TX>(aux[row * ldaux + col]) > 0.f, slope);
-          C[row * ldc + col] = from_f32<TC>(v);
+          for (int q = 0; q < 4; ++q) m[i][q] = (row < M && col + q < N) ? ap[q] : 0.f;
         }
       }
     }
+    __syncthreads();
+#pragma unroll
+    for (int tn = 0; tn < TNW; ++tn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mine[acc_row(r, lane) * LD + tn * 32 + (lane & 31)] = acc[tm][tn][r];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int64_t row = rbase + i * RPI;
+      const float4 t = *reinterpret_cast<const float4*>(&mine[(rl + i * RPI) * LD + cl]);
+      float v[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (EPI == EPI_RELU) v[q] = leaky(v[q], v[q] > 0.f, slope);
+        if (EPI == EPI_MASK) v[q] = leaky(v[q], m[i][q] > 0.f, slope);
+      }
+      if (row < M && col < N) {
+        float* cp = C + row * ldc + col;
+        if (full && c_vec) {
+          *reinterpret_cast<float4*>(cp) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            if (col + q < N) cp[q] = v[q];
+        }
+      }
+    }
+  }
 }
 
 static_assert(BM * BK / 8 == 256, "one 8-float piece of A per thread and tile");
 
 // ---- NN ----------------------------------------------------------------------------------------
 // grid: x = row tile of C (128 rows), y = column tile (64 TNW columns).
-template <int EPI, int TNW, typename TA, typename TC>
-__global__ __launch_bounds__(256) void gemm_nn_kernel(const TA* __restrict__ A, int64_t lda,
-                                                      const float* __restrict__ B, int64_t ldb, TC* __restrict__ C,
+template <int EPI, int TNW>
+__global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ A, int64_t lda,
+                                                      const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
                                                       int64_t ldc, int64_t M, int N, int K, bool a_vec, bool b_vec,
-                                                      float slope, const TA* __restrict__ aux, int64_t ldaux) {
+                                                      bool c_vec, float slope, const float* __restrict__ aux,
+                                                      int64_t ldaux, bool aux_vec) {
   constexpr int BNW = 64 * TNW, SEGB = BNW / 8;      // block columns; 8-float pieces per B row
-  __shared__ Tile<TNW> tiles[2];
+  __shared__ __align__(16) unsigned char lds_raw[block_lds_bytes<TNW>()];
+  Tile<TNW>* tiles = reinterpret_cast<Tile<TNW>*>(lds_raw);
   const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
   const int64_t row0 = (int64_t)blockIdx.x * BM;
   const int col0 = blockIdx.y * BNW;
@@ -71,7 +128,7 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const TA* __restrict__ A, 
   const bool has_b = t < BK * SEGB;
   float ra[8], rb[8];
   auto fetch = [&](int k1) {
-    load8<TA>(A, lda, row0 + t / (BK / 8), M, k1 + (t % (BK / 8)) * 8, K, a_vec, ra);
+    load8<float>(A, lda, row0 + t / (BK / 8), M, k1 + (t % (BK / 8)) * 8, K, a_vec, ra);
     if (has_b) load8<float>(B, ldb, k1 + t / SEGB, K, col0 + (t % SEGB) * 8, N, b_vec, rb);
   };
   auto stage = [&](Tile<TNW>& tile) {
@@ -89,17 +146,20 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const TA* __restrict__ A, 
     if (kt + 1 < n_kt) stage(tiles[cur ^ 1]);
     __syncthreads();
   }
-  store_acc<EPI, TNW, TC, TA>(acc, C, ldc, row0, col0, M, N, wm, wn, slope, aux, ldaux);
+  store_acc<EPI, TNW>(acc, reinterpret_cast<float*>(lds_raw), C, ldc, row0, col0, M, N, wm, wn, slope, aux, ldaux,
+                      c_vec, aux_vec);
 }
 
 // ---- TN ----------------------------------------------------------------------------------------
 // grid: x = output tile (tiles_k * tiles_n) of 128 x 64 TNW, y = slab of M.  Writes P[slab][K x N] (ld N).
-template <int TNW, typename TA>
-__global__ __launch_bounds__(256) void gemm_tn_kernel(const TA* __restrict__ A, int64_t lda, const TA* __restrict__ G,
-                                                      int64_t ldg, float* __restrict__ P, int64_t M, int K, int N,
-                                                      int64_t slab_rows, int tiles_n, bool a_vec, bool g_vec) {
+template <int TNW>
+__global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ A, int64_t lda,
+                                                      const float* __restrict__ G, int64_t ldg, float* __restrict__ P,
+                                                      int64_t M, int K, int N, int64_t slab_rows, int tiles_n,
+                                                      bool a_vec, bool g_vec, bool p_vec) {
   constexpr int BNW = 64 * TNW, SEGB = BNW / 8;
-  __shared__ Tile<TNW> tiles[2];
+  __shared__ __align__(16) unsigned char lds_raw[block_lds_bytes<TNW>()];
+  Tile<TNW>* tiles = reinterpret_cast<Tile<TNW>*>(lds_raw);
   const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
   const int k0 = (blockIdx.x / tiles_n) * BM;    // output row block (columns of A)
   const int n0 = (blockIdx.x % tiles_n) * BNW;   // output column block (columns of G)
@@ -117,8 +177,8 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const TA* __restrict__ A, 
   const bool has_b = t < BK * SEGB;
   float ra[8], rb[8];
   auto fetch = [&](int64_t m1) {
-    load8<TA>(A, lda, m1 + t / 16, m_end, k0 + (t % 16) * 8, K, a_vec, ra);
-    if (has_b) load8<TA>(G, ldg, m1 + t / SEGB, m_end, n0 + (t % SEGB) * 8, N, g_vec, rb);
+    load8<float>(A, lda, m1 + t / 16, m_end, k0 + (t % 16) * 8, K, a_vec, ra);
+    if (has_b) load8<float>(G, ldg, m1 + t / SEGB, m_end, n0 + (t % SEGB) * 8, N, g_vec, rb);
   };
   auto stage = [&](Tile<TNW>& tile) {
     store_direct(tile.a, t / 16, (t % 16) * 8, ra);
@@ -136,7 +196,8 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const TA* __restrict__ A, 
     __syncthreads();
   }
   float* Pslab = P + (int64_t)blockIdx.y * K * N;
-  store_acc<EPI_NONE, TNW, float, float>(acc, Pslab, N, k0, n0, K, N, wm, wn, 0.f, nullptr, 0);
+  store_acc<EPI_NONE, TNW>(acc, reinterpret_cast<float*>(lds_raw), Pslab, N, k0, n0, K, N, wm, wn, 0.f, nullptr, 0,
+                           p_vec, false);
 }
 
 __global__ void reduce_slabs(const float* __restrict__ P, int n_slabs, int64_t elems, int N, float* __restrict__ C,
@@ -179,22 +240,23 @@ void tn_split(int64_t M, int K, int N, int* n_slabs, int64_t* slab_rows) {
   *n_slabs = (int)ceil_div(M, *slab_rows);
 }
 
-template <int TNW, typename TA, typename TC>
-int gemm_nn_launch(const TA* A, int64_t lda, const float* B, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
-                   const Epi& e, hipStream_t s) {
-  const TA* aux = static_cast<const TA*>(e.aux);
+template <int TNW>
+int gemm_nn_launch(const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t M, int N,
+                   int K, const Epi& e, hipStream_t s) {
+  const float* aux = static_cast<const float*>(e.aux);
   const int64_t ldaux = e.ldaux;
   const dim3 grid((unsigned)ceil_div(M, BM), (unsigned)ceil_div(N, 64 * TNW));
-  const bool av = vec_ok(A, lda), bv = vec_ok(B, ldb);
+  const bool av = vec_ok(A, lda), bv = vec_ok(B, ldb), cv = vec_ok(C, ldc);
+  const bool xv = e.kind == EPI_MASK && vec_ok(aux, ldaux);
   switch (e.kind) {
     case EPI_NONE:
-      gemm_nn_kernel<EPI_NONE, TNW, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, e.slope, aux, ldaux);
+      gemm_nn_kernel<EPI_NONE, TNW><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, cv, e.slope, aux, ldaux, xv);
       break;
     case EPI_RELU:
-      gemm_nn_kernel<EPI_RELU, TNW, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, e.slope, aux, ldaux);
+      gemm_nn_kernel<EPI_RELU, TNW><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, cv, e.slope, aux, ldaux, xv);
       break;
     case EPI_MASK:
-      gemm_nn_kernel<EPI_MASK, TNW, TA, TC><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, e.slope, aux, ldaux);
+      gemm_nn_kernel<EPI_MASK, TNW><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, cv, e.slope, aux, ldaux, xv);
       break;
     default:
       return set_error(GAD_ERR_UNSUPPORTED, "unknown epilogue %d", e.kind);
@@ -203,27 +265,27 @@ int gemm_nn_launch(const TA* A, int64_t lda, const float* B, int64_t ldb, TC* C,
   return GAD_OK;
 }
 
-template <typename TA, typename TC>
-int gemm_nn_typed(const TA* A, int64_t lda, const float* B, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
-                  const Epi& e, hipStream_t s) {
-  if (block_cols(N) == 64) return gemm_nn_launch<1, TA, TC>(A, lda, B, ldb, C, ldc, M, N, K, e, s);
-  return gemm_nn_launch<2, TA, TC>(A, lda, B, ldb, C, ldc, M, N, K, e, s);
+int gemm_nn_f32(const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t M, int N, int K,
+                const Epi& e, hipStream_t s) {
+  if (block_cols(N) == 64) return gemm_nn_launch<1>(A, lda, B, ldb, C, ldc, M, N, K, e, s);
+  return gemm_nn_launch<2>(A, lda, B, ldb, C, ldc, M, N, K, e, s);
 }
 
-template <typename TA>
-int gemm_tn_typed(const TA* A, int64_t lda, const TA* G, int64_t ldg, float* C, int64_t ldc, int64_t M, int K, int N,
-                  float* partials, hipStream_t s) {
+int gemm_tn_f32(const float* A, int64_t lda, const float* G, int64_t ldg, float* C, int64_t ldc, int64_t M, int K, int N,
+                float* partials, hipStream_t s) {
   int n_slabs;
   int64_t slab_rows;
   tn_split(M, K, N, &n_slabs, &slab_rows);
   const int tiles_n = (int)ceil_div(N, block_cols(N));
   const dim3 grid((unsigned)(ceil_div(K, BM) * tiles_n), (unsigned)n_slabs);
+  // every slab of the partial products starts on a 16-byte boundary when K N is a multiple of 4
+  const bool pv = vec_ok(partials, N) && ((int64_t)K * N) % 4 == 0;
   if (block_cols(N) == 64)
-    gemm_tn_kernel<1, TA><<<grid, 256, 0, s>>>(A, lda, G, ldg, partials, M, K, N, slab_rows, tiles_n, vec_ok(A, lda),
-                                               vec_ok(G, ldg));
+    gemm_tn_kernel<1><<<grid, 256, 0, s>>>(A, lda, G, ldg, partials, M, K, N, slab_rows, tiles_n, vec_ok(A, lda),
+                                           vec_ok(G, ldg), pv);
   else
-    gemm_tn_kernel<2, TA><<<grid, 256, 0, s>>>(A, lda, G, ldg, partials, M, K, N, slab_rows, tiles_n, vec_ok(A, lda),
-                                               vec_ok(G, ldg));
+    gemm_tn_kernel<2><<<grid, 256, 0, s>>>(A, lda, G, ldg, partials, M, K, N, slab_rows, tiles_n, vec_ok(A, lda),
+                                           vec_ok(G, ldg), pv);
   GAD_LAUNCH_CHECK();
   const int64_t elems = (int64_t)K * N;
   reduce_slabs<<<(unsigned)ceil_div(elems, 256), 256, 0, s>>>(partials, n_slabs, elems, N, C, ldc);
@@ -252,7 +314,7 @@ int gemm_w(const void* A, int64_t lda, gad_dtype ta, const float* W, int w_rows,
     if (st != GAD_OK) return st;
     B = static_cast<const float*>(scratch);
   }
-  return gemm_nn_typed<float, float>((const float*)A, lda, B, N, (float*)C, ldc, M, N, K, e, s);
+  return gemm_nn_f32((const float*)A, lda, B, N, (float*)C, ldc, M, N, K, e, s);
 }
 
 size_t gemm_tn_partial_floats(int64_t M, int K, int N) {
@@ -265,7 +327,7 @@ size_t gemm_tn_partial_floats(int64_t M, int K, int N) {
 int gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, gad_dtype t, float* C, int64_t ldc, int64_t M,
             int K, int N, float* partials, hipStream_t s) {
   if (K == 0 || N == 0) return GAD_OK;
-  if (t == GAD_F32) return gemm_tn_typed<float>((const float*)A, lda, (const float*)G, ldg, C, ldc, M, K, N, partials, s);
+  if (t == GAD_F32) return gemm_tn_f32((const float*)A, lda, (const float*)G, ldg, C, ldc, M, K, N, partials, s);
   int n_slabs;
   int64_t slab_rows;
   tn_split(M, K, N, &n_slabs, &slab_rows);

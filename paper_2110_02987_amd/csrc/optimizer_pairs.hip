@@ -184,6 +184,23 @@ __global__ __launch_bounds__(256) void pair_tiles(const float* __restrict__ Vc, 
 
 static_assert(BM == 128 && 2 * BM == 256, "the info loader maps one thread to one row or column of the tile");
 
+// part[b] = sum of block b's contiguous share of the tile sums (fixed shares, fixed order inside a share).
+__global__ __launch_bounds__(256) void sum_tiles(const double* __restrict__ tile_sum, int64_t n_tiles, int64_t share,
+                                                 double* __restrict__ part) {
+  __shared__ double sm[256];
+  const int64_t b = (int64_t)blockIdx.x * share;
+  const int64_t e = b + share < n_tiles ? b + share : n_tiles;
+  double s = 0.0;
+  for (int64_t k = b + threadIdx.x; k < e; k += 256) s += tile_sum[k];
+  sm[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) part[blockIdx.x] = sm[0];
+}
+
 __global__ __launch_bounds__(256) void finalize_pairs(const double* __restrict__ tile_sum, int64_t n_tiles,
                                                       const unsigned long long* __restrict__ dpart, int n_dpart,
                                                       double* __restrict__ out2) {
@@ -214,10 +231,11 @@ __global__ __launch_bounds__(256) void finalize_pairs(const double* __restrict__
 }
 
 constexpr int kDegBlocks = 256;
+constexpr int kSumBlocks = 1024;
 constexpr size_t kAlign = 256;
 
 struct Layout {
-  size_t vc, nrm, degf, mean, colpart, tiles, dpart, total;
+  size_t vc, nrm, degf, mean, colpart, tiles, tilepart, dpart, total;
   int64_t ldv, T, n_tiles;
 };
 
@@ -238,6 +256,7 @@ Layout layout(int64_t n, int F) {
   L.mean = take((size_t)F * sizeof(double));
   L.colpart = take((size_t)kVarBlocks * F * sizeof(double));
   L.tiles = take((size_t)L.n_tiles * sizeof(double));
+  L.tilepart = take((size_t)kSumBlocks * sizeof(double));
   L.dpart = take((size_t)2 * kDegBlocks * sizeof(unsigned long long));
   L.total = off;
   return L;
@@ -259,6 +278,7 @@ int pair_importance(const gad_graph* g, const void* V, int F, gad_dtype dtype, d
   double* mean = reinterpret_cast<double*>(base + L.mean);
   double* colpart = reinterpret_cast<double*>(base + L.colpart);
   double* tile_sum = reinterpret_cast<double*>(base + L.tiles);
+  double* tile_part = reinterpret_cast<double*>(base + L.tilepart);
   unsigned long long* dpart = reinterpret_cast<unsigned long long*>(base + L.dpart);
   int st = column_means_f64(V, n, F, dtype, colpart, mean, s);
   if (st != GAD_OK) return st;
@@ -273,7 +293,12 @@ int pair_importance(const gad_graph* g, const void* V, int F, gad_dtype dtype, d
   GAD_LAUNCH_CHECK();
   pair_tiles<<<(unsigned)L.n_tiles, 256, 0, s>>>(Vc, L.ldv, nrm, degf, n, L.T, (float)beta, tile_sum);
   GAD_LAUNCH_CHECK();
-  finalize_pairs<<<1, 256, 0, s>>>(tile_sum, L.n_tiles, dpart, dblocks, out2);
+  // tile sums -> kSumBlocks partial sums -> one sum: the shares depend on the tile count alone
+  const int64_t share = ceil_div(L.n_tiles, kSumBlocks);
+  const int64_t n_part = ceil_div(L.n_tiles, share);
+  sum_tiles<<<(unsigned)n_part, 256, 0, s>>>(tile_sum, L.n_tiles, share, tile_part);
+  GAD_LAUNCH_CHECK();
+  finalize_pairs<<<1, 256, 0, s>>>(tile_part, n_part, dpart, dblocks, out2);
   GAD_LAUNCH_CHECK();
   return GAD_OK;
 }
