@@ -34,8 +34,19 @@ __global__ __launch_bounds__(256) void column_sums(const T* __restrict__ V, int6
   for (int c0 = 0; c0 < F; c0 += CW) {
     const int c = c0 + cl;
     double s = 0.0;
-    if (c < F)
-      for (int64_t r = r0 + rl; r < r1; r += RL) s += (double)to_float<T>(V[r * F + c]);
+    if (c < F) {
+      // four independent partial sums keep four loads in flight; they are combined in a fixed order
+      double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+      int64_t r = r0 + rl;
+      for (; r + 3 * RL < r1; r += 4 * RL) {
+        s0 += (double)to_float<T>(V[r * F + c]);
+        s1 += (double)to_float<T>(V[(r + RL) * F + c]);
+        s2 += (double)to_float<T>(V[(r + 2 * RL) * F + c]);
+        s3 += (double)to_float<T>(V[(r + 3 * RL) * F + c]);
+      }
+      for (; r < r1; r += RL) s0 += (double)to_float<T>(V[r * F + c]);
+      s = (s0 + s1) + (s2 + s3);
+    }
     sm[threadIdx.x] = s;
     __syncthreads();
     if (rl == 0 && c < F) {
@@ -47,66 +58,81 @@ __global__ __launch_bounds__(256) void column_sums(const T* __restrict__ V, int6
   }
 }
 
-__global__ void column_means(const double* __restrict__ part, int n_blocks, int F, int64_t n,
-                             double* __restrict__ mean) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= F) return;
+// One wave per column: lane l adds the partial sums of slabs l, l + 64, ..., then a fixed shuffle tree.
+__global__ __launch_bounds__(256) void column_means(const double* __restrict__ part, int n_blocks, int F, int64_t n,
+                                                    double* __restrict__ mean) {
+  const int c = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (c >= F) return;                     // whole waves leave together
   double s = 0.0;
-  for (int b = 0; b < n_blocks; ++b) s += part[(int64_t)b * F + c];
-  mean[c] = s / (double)n;
+  for (int b = lane; b < n_blocks; b += 64) s += part[(int64_t)b * F + c];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  if (lane == 0) mean[c] = s / (double)n;
 }
 
-// r_i = ||v_i - mean||^2 (16-lane group per row), block sums of r_i, and the integer degree sums.
+// r_i = ||v_i - mean||^2 (16-lane group per row, kDevRows rows per block in passes of 16), block sums of r_i in
+// row order, and the integer degree sums.
+constexpr int kDevRows = 256;
+
 template <typename T>
 __global__ __launch_bounds__(256) void deviations(const T* __restrict__ V, int64_t n, int F,
                                                   const double* __restrict__ mean, const int32_t* __restrict__ deg,
                                                   float* __restrict__ per_node, double* __restrict__ block_r,
                                                   unsigned long long* __restrict__ block_d1,
                                                   unsigned long long* __restrict__ block_d2) {
-  __shared__ double sm_r[16];
+  __shared__ double sm_r[kDevRows];
+  __shared__ unsigned long long sm_d1[4], sm_d2[4];
   const int grp = threadIdx.x >> 4, l = threadIdx.x & 15;
-  const int64_t i = (int64_t)blockIdx.x * 16 + grp;
-  double r = 0.0;
-  if (i < n) {
-    for (int c = l; c < F; c += 16) {
-      const double d = (double)to_float<T>(V[i * F + c]) - mean[c];
-      r += d * d;
+  const int64_t base = (int64_t)blockIdx.x * kDevRows;
+  for (int pass = 0; pass < kDevRows / 16; ++pass) {
+    const int64_t i = base + pass * 16 + grp;
+    double r = 0.0;
+    if (i < n) {
+      for (int c = l; c < F; c += 16) {
+        const double d = (double)to_float<T>(V[i * F + c]) - mean[c];
+        r += d * d;
+      }
+    }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) r += __shfl_xor(r, o, 64);
+    if (l == 0) {
+      sm_r[pass * 16 + grp] = i < n ? r : 0.0;
+      if (i < n && per_node) per_node[i] = (float)r;
     }
   }
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) r += __shfl_xor(r, o, 64);
-  if (l == 0) {
-    sm_r[grp] = i < n ? r : 0.0;
-    if (i < n && per_node) per_node[i] = (float)r;
-  }
-  // degree sums: thread t < 16 takes row blockIdx*16 + t
+  // degree sums: thread t takes row base + t (exact integers: the order does not matter)
   unsigned long long d1 = 0, d2 = 0;
-  if (threadIdx.x < 16) {
-    const int64_t j = (int64_t)blockIdx.x * 16 + threadIdx.x;
+  {
+    const int64_t j = base + threadIdx.x;
     if (j < n) {
       const unsigned long long d = (unsigned long long)deg[j];
       d1 = d;
       d2 = d * d;
     }
   }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double s = 0.0;
-    for (int k = 0; k < 16; ++k) s += sm_r[k];
-    block_r[blockIdx.x] = s;
-  }
-  if (threadIdx.x < 64) {   // first wave holds all 16 degree lanes
 #pragma unroll
-    for (int o = 8; o > 0; o >>= 1) {
-      d1 += __shfl_xor(d1, o, 64);
-      d2 += __shfl_xor(d2, o, 64);
-    }
+  for (int o = 32; o > 0; o >>= 1) {
+    d1 += __shfl_xor(d1, o, 64);
+    d2 += __shfl_xor(d2, o, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    sm_d1[threadIdx.x >> 6] = d1;
+    sm_d2[threadIdx.x >> 6] = d2;
+  }
+  __syncthreads();
+  if (threadIdx.x < 64) {                 // row sums: lane t adds rows t, t + 64, ..., then a fixed shuffle tree
+    double s = (sm_r[threadIdx.x] + sm_r[threadIdx.x + 64]) + (sm_r[threadIdx.x + 128] + sm_r[threadIdx.x + 192]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
     if (threadIdx.x == 0) {
-      block_d1[blockIdx.x] = d1;
-      block_d2[blockIdx.x] = d2;
+      block_r[blockIdx.x] = s;
+      block_d1[blockIdx.x] = sm_d1[0] + sm_d1[1] + sm_d1[2] + sm_d1[3];
+      block_d2[blockIdx.x] = sm_d2[0] + sm_d2[1] + sm_d2[2] + sm_d2[3];
     }
   }
 }
+
+static_assert(kDevRows == 256, "one degree per thread and four rows per lane in the block sum");
 
 __global__ __launch_bounds__(256) void finalize_zeta(const double* __restrict__ block_r, int64_t n_blocks, int64_t n,
                                                      const unsigned long long* __restrict__ block_d1,
@@ -176,11 +202,11 @@ __global__ __launch_bounds__(256) void consensus_update_kernel(ConsensusArgs a, 
 template <typename T>
 int variance_t(const gad_graph* g, const T* V, int F, double beta, double* out3, float* per_node, hipStream_t s) {
   const int64_t n = g->n;
-  // scratch layout (8-byte words): part[kVarBlocks x F] | mean[F] | block_r[nb] | block_d1[nb] | block_d2[nb], nb = ceil(n/16)
+  // scratch layout (8-byte words): part[kVarBlocks x F] | mean[F] | block_r[nb] | block_d1[nb] | block_d2[nb], nb = ceil(n / kDevRows)
   double* part = g->red_scratch;
   double* mean = part + (int64_t)kVarBlocks * F;
   double* block_r = mean + F;
-  const int64_t r_blocks = ceil_div(n, 16);
+  const int64_t r_blocks = ceil_div(n, kDevRows);
   unsigned long long* block_d1 = reinterpret_cast<unsigned long long*>(block_r + r_blocks);
   unsigned long long* block_d2 = block_d1 + r_blocks;
   int st = column_means_f64(V, n, F, sizeof(T) == 4 ? GAD_F32 : GAD_BF16, part, mean, s);
@@ -208,13 +234,13 @@ int column_means_f64(const void* V, int64_t n, int F, gad_dtype dtype, double* p
   }
 #undef GAD_COLSUM
   GAD_LAUNCH_CHECK();
-  column_means<<<(unsigned)ceil_div(F, 256), 256, 0, s>>>(part, n_blocks, F, n, mean);
+  column_means<<<(unsigned)ceil_div(F, 4), 256, 0, s>>>(part, n_blocks, F, n, mean);
   GAD_LAUNCH_CHECK();
   return GAD_OK;
 }
 
 size_t variance_scratch_doubles(int64_t n) {
-  return (size_t)kVarBlocks * kMaxWidth + kMaxWidth + 3 * (size_t)ceil_div(n, 16) + 4;
+  return (size_t)kVarBlocks * kMaxWidth + kMaxWidth + 3 * (size_t)ceil_div(n, kDevRows) + 4;
 }
 
 int subgraph_variance(const gad_graph* g, const void* V, int F, gad_dtype dtype, double beta, double* out3,
