@@ -225,11 +225,14 @@ def main() -> int:
         extras["augment_subgraph"] = dict(ms=ms, n_part=int(part.numel()), walk_len=L, budget=g.n // 20,
                                           n_walks=int(n_walks), n_halo=int(halo.numel()))
         # Eq. 14 with the distance inside the pair sum, all pairs, on the last layer's per-node gradients
-        out2 = torch.zeros(2, dtype=torch.float64, device="cuda")
-        ms, _ = timed(lambda: gad.pair_importance(g, G_last, 1.0, out2))
         pairs = g.n * (g.n - 1) / 2
-        extras["pair_importance"] = dict(ms=ms, pairs=pairs, F=int(G_last.shape[1]), pairs_per_s=pairs / (ms * 1e-3),
-                                         zeta_pair=float(out2[0].item()))
+        if pairs <= 5e11:                                  # about 1.5 s per call; the larger graphs would take minutes
+            out2 = torch.zeros(2, dtype=torch.float64, device="cuda")
+            ms, _ = timed(lambda: gad.pair_importance(g, G_last, 1.0, out2))
+            extras["pair_importance"] = dict(ms=ms, pairs=pairs, F=int(G_last.shape[1]),
+                                             pairs_per_s=pairs / (ms * 1e-3), zeta_pair=float(out2[0].item()))
+        else:
+            extras["pair_importance"] = dict(skipped=f"{pairs:.3g} pairs")
         del part, halo
 
     out = dict(metric="GCN fwd+bwd edges/s per layer and epoch ms per subgraph; SpMM % of HBM peak",

@@ -35,6 +35,7 @@ __global__ void fill_u32(uint32_t* p, int64_t n, uint32_t v) {
   if (i < n) p[i] = v;
 }
 
+// mark[v] = 1 + position of v in `part` (0: not in the partition).
 // flags[0]: a row outside [0, N); flags[1]: a row listed twice
 __global__ void mark_part(const int64_t* __restrict__ part, int64_t n_part, int64_t N, uint32_t* __restrict__ mark,
                           uint32_t* __restrict__ flags) {
@@ -45,17 +46,17 @@ __global__ void mark_part(const int64_t* __restrict__ part, int64_t n_part, int6
     flags[0] = 1u;
     return;
   }
-  if (atomicExch(&mark[v], 1u) != 0u) flags[1] = 1u;
+  if (atomicExch(&mark[v], (uint32_t)p + 1u) != 0u) flags[1] = 1u;
 }
 
-// is_b[p] = 1 iff part[p] has a neighbour outside the partition; deg_b[p] = its degree then (else 0).
-// A 16-lane group owns one row and looks at 64 of its entries per step (columns ascend, so the members of a
-// partition made of low ids all come first: one thread per row would walk half of every hub row alone).
+// is_b[p] = 1 iff part[p] has a neighbour outside the partition.  A 16-lane group owns one row and looks at 64
+// of its entries per step (columns ascend, so the members of a partition made of low ids all come first: one
+// thread per row would walk half of every hub row alone).  Rows longer than kLongRow entries get 0 here and are
+// decided chunk by chunk in boundary_flags_long.
 __global__ __launch_bounds__(256) void boundary_flags(const int64_t* __restrict__ part, int64_t n_part,
                                                       const int64_t* __restrict__ rowptr,
                                                       const int32_t* __restrict__ colidx,
-                                                      const uint32_t* __restrict__ mark, uint32_t* __restrict__ is_b,
-                                                      uint32_t* __restrict__ deg_b) {
+                                                      const uint32_t* __restrict__ mark, uint32_t* __restrict__ is_b) {
   const int l = threadIdx.x & 15;
   const int64_t p = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) >> 4;
   const bool live = p < n_part;                      // all lanes of a wave stay in the loop's shuffles
@@ -64,10 +65,11 @@ __global__ __launch_bounds__(256) void boundary_flags(const int64_t* __restrict_
     const int64_t v = part[p];
     b = rowptr[v];
     e = rowptr[v + 1];
+    if (e - b > kLongRow) e = b;                     // a long row: left to the chunk pass
   }
   int out = 0;
   for (int64_t q0 = b; ; q0 += 64) {
-    int more = (q0 < e && !out) ? 1 : 0;
+    const int more = (q0 < e && !out) ? 1 : 0;
     // the wave leaves the loop together: when none of its four groups has entries left to look at
     if (__ballot(more) == 0ull) break;
     if (more) {
@@ -80,10 +82,45 @@ __global__ __launch_bounds__(256) void boundary_flags(const int64_t* __restrict_
 #pragma unroll
     for (int o = 8; o > 0; o >>= 1) out |= __shfl_xor(out, o, 16);
   }
-  if (live && l == 0) {
-    is_b[p] = out ? 1u : 0u;
-    deg_b[p] = out ? (uint32_t)(e - b - 1) : 0u;
+  if (live && l == 0) is_b[p] = out ? 1u : 0u;
+}
+
+// The rows of more than kLongRow entries, by the graph's own chunk list (kLongRow entries per chunk): a 16-lane group
+// owns one chunk of a row of the partition and raises the row's flag when the chunk holds an outside neighbour.
+__global__ __launch_bounds__(256) void boundary_flags_long(const int32_t* __restrict__ chunk_row,
+                                                           const int32_t* __restrict__ chunk_begin, int64_t n_chunks,
+                                                           const int64_t* __restrict__ rowptr,
+                                                           const int32_t* __restrict__ colidx,
+                                                           const uint32_t* __restrict__ mark,
+                                                           uint32_t* __restrict__ is_b) {
+  const int l = threadIdx.x & 15;
+  const int64_t c = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) >> 4;
+  uint32_t m = 0;
+  int64_t b = 0, e = 0;
+  if (c < n_chunks) {
+    const int64_t row = chunk_row[c];
+    m = mark[row];
+    if (m != 0u) {
+      b = rowptr[row] + chunk_begin[c];
+      e = rowptr[row + 1];
+      if (e > b + kLongRow) e = b + kLongRow;
+    }
   }
+  int out = 0;
+  for (int64_t q = b + l; q < e; q += 16)
+    if (mark[colidx[q]] == 0u) out = 1;
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) out |= __shfl_xor(out, o, 16);
+  if (m != 0u && out && l == 0) atomicOr(&is_b[m - 1u], 1u);
+}
+
+// deg_b[p] = degree of part[p] if it is a boundary node, else 0
+__global__ void boundary_degrees(const int64_t* __restrict__ part, int64_t n_part, const int64_t* __restrict__ rowptr,
+                                 const uint32_t* __restrict__ is_b, uint32_t* __restrict__ deg_b) {
+  const int64_t p = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (p >= n_part) return;
+  const int64_t v = part[p];
+  deg_b[p] = is_b[p] ? (uint32_t)(rowptr[v + 1] - rowptr[v] - 1) : 0u;
 }
 
 __global__ void compact_boundary(const int64_t* __restrict__ part, int64_t n_part, const uint32_t* __restrict__ is_b,
@@ -257,7 +294,16 @@ int augment_subgraph(const gad_graph* G, const int64_t* part, int64_t n_part, in
   const size_t max_items = (size_t)(N > n_part ? N : n_part);
   GAD_HIP(scratch.alloc(&tile_tmp, scan_tmp_len(max_items > sort_hist_len((uint32_t)max_walks) ? max_items
                                                                                                 : sort_hist_len((uint32_t)max_walks))));
-  boundary_flags<<<blocks(n_part * 16), 256, 0, s>>>(part, n_part, G->rowptr, G->colidx, mark, is_b, deg_b);
+  GAD_GRID_CHECK(ceil_div(n_part * 16, 256), 256);
+  GAD_GRID_CHECK(ceil_div((int64_t)G->n_chunks * 16, 256), 256);
+  boundary_flags<<<blocks(n_part * 16), 256, 0, s>>>(part, n_part, G->rowptr, G->colidx, mark, is_b);
+  GAD_LAUNCH_CHECK();
+  if (G->n_chunks > 0) {
+    boundary_flags_long<<<blocks((int64_t)G->n_chunks * 16), 256, 0, s>>>(G->chunk_row, G->chunk_begin, G->n_chunks,
+                                                                          G->rowptr, G->colidx, mark, is_b);
+    GAD_LAUNCH_CHECK();
+  }
+  boundary_degrees<<<blocks(n_part), 256, 0, s>>>(part, n_part, G->rowptr, is_b, deg_b);
   GAD_LAUNCH_CHECK();
   GAD_HIP(hipMemcpyAsync(pos, is_b, (size_t)n_part * sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
   int st = scan_u32(pos, (uint32_t)n_part, tile_tmp, flags + 2, s);

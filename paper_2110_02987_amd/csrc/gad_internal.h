@@ -23,6 +23,16 @@ int set_error(int status, const char* fmt, ...);   // formats into the thread-lo
 
 #define GAD_LAUNCH_CHECK() GAD_HIP(hipGetLastError())
 
+// A launch is valid when, in every grid dimension, the workgroup count fits 31 bits and the thread count 32 bits;
+// a larger one is rejected here on the host (it would not run).
+#define GAD_GRID_CHECK(blocks, threads)                                                                      \
+  do {                                                                                                       \
+    const long long _b = (long long)(blocks);                                                                \
+    if (_b < 0 || _b > 0x7FFFFFFFll || _b * (long long)(threads) > 0xFFFFFFFFll)                             \
+      return gad::set_error(GAD_ERR_SHAPE, "%lld workgroups of %d threads exceed the launch limits (%s:%d)", _b, \
+                            (int)(threads), __FILE__, __LINE__);                                             \
+  } while (0)
+
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 

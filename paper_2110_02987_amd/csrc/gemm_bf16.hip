@@ -358,6 +358,7 @@ int launch_nt(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C
   constexpr size_t smem = tiles_bytes > stage_bytes ? tiles_bytes : stage_bytes;
   const int tiles_n = (int)ceil_div(N, BN);
   const int64_t total = ceil_div(M, 128) * tiles_n;
+  GAD_GRID_CHECK(total, 256);
   const bf16_t* aux = static_cast<const bf16_t*>(e.aux);
   const bool av = vec_ok(A, lda);
   const bool cv = (ldc % (16 / (int)sizeof(TC)) == 0) && ((reinterpret_cast<uintptr_t>(C) & 15u) == 0);
@@ -426,6 +427,7 @@ int gemm_tn_bf16(const void* A, int64_t lda, const void* G, int64_t ldg, float* 
   const int tiles_n = (int)ceil_div(N, 128);
   const int tiles = (int)ceil_div(K, 128) * tiles_n;
   const int64_t total = (int64_t)tiles * n_slabs;
+  GAD_GRID_CHECK(total, 256);
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* g = static_cast<const bf16_t*>(G);
   gemm_tn_kernel<<<(unsigned)total, 256, smem, s>>>(a, lda, g, ldg, partials, M, K, N, slab_rows, tiles_n, tiles, total,

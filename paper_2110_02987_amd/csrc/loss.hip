@@ -113,11 +113,12 @@ __global__ __launch_bounds__(256) void sum_doubles(const double* __restrict__ v,
 template <typename TI>
 __global__ void copy_rows_kernel(const TI* __restrict__ in, int64_t ldi, float* __restrict__ out, int64_t ldo,
                                  int64_t n, int width) {
-  const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (e >= n * width) return;
-  const int64_t i = e / width;
-  const int c = (int)(e % width);
-  out[i * ldo + c] = to_f32<TI>(in[i * ldi + c]);
+  const int64_t total = n * width, stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < total; e += stride) {
+    const int64_t i = e / width;
+    const int c = (int)(e % width);
+    out[i * ldo + c] = to_f32<TI>(in[i * ldi + c]);
+  }
 }
 
 }  // namespace
@@ -128,6 +129,7 @@ int softmax_xent(const float* Z, int64_t ldz, const int32_t* labels, const uint8
                  const float* row_scale, int64_t n, int C, void* G, int64_t ldg, gad_dtype tg, double* block_partials, double* loss_out, hipStream_t s) {
   if (n == 0) return GAD_OK;
   const int64_t blocks = ceil_div(n, kRowsPerBlock);
+  GAD_GRID_CHECK(blocks, 256);
 #define GAD_SOFTMAX(TG, ITEMS)                                                                                    \
   softmax_xent_kernel<TG, ITEMS><<<(unsigned)blocks, 256, 0, s>>>(Z, ldz, labels, mask, scale, row_scale, n, C, \
                                                                   static_cast<TG*>(G), ldg, block_partials)
@@ -149,7 +151,8 @@ int softmax_xent(const float* Z, int64_t ldz, const int32_t* labels, const uint8
 
 int copy_rows(const void* in, int64_t ldi, gad_dtype ti, float* out, int64_t ldo, int64_t n, int width, hipStream_t s) {
   if (n == 0 || width == 0) return GAD_OK;
-  const unsigned blocks = (unsigned)ceil_div(n * width, 256);
+  const int64_t want = ceil_div(n * width, 256);
+  const unsigned blocks = (unsigned)(want < (1 << 22) ? want : (1 << 22));      // the kernel strides over the rest
   if (ti == GAD_F32)
     copy_rows_kernel<float><<<blocks, 256, 0, s>>>((const float*)in, ldi, out, ldo, n, width);
   else

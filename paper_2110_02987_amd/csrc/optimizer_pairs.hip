@@ -93,13 +93,16 @@ __device__ __forceinline__ void tile_of(int64_t b, int64_t T, int* ti, int* tj) 
 
 __global__ __launch_bounds__(256) void pair_tiles(const float* __restrict__ Vc, int64_t ldv,
                                                   const float* __restrict__ nrm, const float* __restrict__ degf,
-                                                  int64_t n, int64_t T, float beta, double* __restrict__ tile_sum) {
+                                                  int64_t n, int64_t T, int64_t n_tiles, float beta,
+                                                  double* __restrict__ tile_sum) {
   __shared__ Tile<2> tiles[2];
   __shared__ float info[4][BM];          // ||v_i||^2, deg_i of the tile's rows; ||v_j||^2, deg_j of its columns
   __shared__ double red[256];
   const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1, lane = t & 63;
+  const int64_t tile = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;     // the grid is folded into two dimensions
+  if (tile >= n_tiles) return;                                          // (whole blocks leave)
   int ti, tj;
-  tile_of(blockIdx.x, T, &ti, &tj);
+  tile_of(tile, T, &ti, &tj);
   const int64_t i0 = (int64_t)ti * BM, j0 = (int64_t)tj * BM;
   {
     const int64_t r = (t < BM ? i0 : j0 - BM) + t;
@@ -179,7 +182,7 @@ __global__ __launch_bounds__(256) void pair_tiles(const float* __restrict__ Vc, 
     if (t < o) red[t] += red[t + o];
     __syncthreads();
   }
-  if (t == 0) tile_sum[blockIdx.x] = red[0];
+  if (t == 0) tile_sum[tile] = red[0];
 }
 
 static_assert(BM == 128 && 2 * BM == 256, "the info loader maps one thread to one row or column of the tile");
@@ -270,7 +273,9 @@ int pair_importance(const gad_graph* g, const void* V, int F, gad_dtype dtype, d
                     hipStream_t s) {
   const int64_t n = g->n;
   const Layout L = layout(n, F);
-  if (L.n_tiles > 2147483647ll) return set_error(GAD_ERR_SHAPE, "n = %lld has too many pair tiles for one launch", (long long)n);
+  constexpr int64_t kGridX = 1 << 20;                                   // tiles per row of the folded grid
+  const int64_t grid_y = ceil_div(L.n_tiles, kGridX);
+  if (grid_y > 65535) return set_error(GAD_ERR_SHAPE, "n = %lld has too many pair tiles for one launch", (long long)n);
   char* base = static_cast<char*>(ws);
   float* Vc = reinterpret_cast<float*>(base + L.vc);
   float* nrm = reinterpret_cast<float*>(base + L.nrm);
@@ -282,6 +287,7 @@ int pair_importance(const gad_graph* g, const void* V, int F, gad_dtype dtype, d
   unsigned long long* dpart = reinterpret_cast<unsigned long long*>(base + L.dpart);
   int st = column_means_f64(V, n, F, dtype, colpart, mean, s);
   if (st != GAD_OK) return st;
+  GAD_GRID_CHECK(ceil_div(n, 16), 256);
   const unsigned row_blocks = (unsigned)ceil_div(n, 16);
   if (dtype == GAD_F32)
     centre_rows<float><<<row_blocks, 256, 0, s>>>(static_cast<const float*>(V), n, F, mean, g->deg, Vc, L.ldv, nrm, degf);
@@ -291,7 +297,8 @@ int pair_importance(const gad_graph* g, const void* V, int F, gad_dtype dtype, d
   const int dblocks = (int)(ceil_div(n, 256) < kDegBlocks ? ceil_div(n, 256) : kDegBlocks);
   degree_partials<<<dblocks, 256, 0, s>>>(g->deg, n, dpart);
   GAD_LAUNCH_CHECK();
-  pair_tiles<<<(unsigned)L.n_tiles, 256, 0, s>>>(Vc, L.ldv, nrm, degf, n, L.T, (float)beta, tile_sum);
+  const dim3 grid((unsigned)(L.n_tiles < kGridX ? L.n_tiles : kGridX), (unsigned)grid_y);
+  pair_tiles<<<grid, 256, 0, s>>>(Vc, L.ldv, nrm, degf, n, L.T, L.n_tiles, (float)beta, tile_sum);
   GAD_LAUNCH_CHECK();
   // tile sums -> kSumBlocks partial sums -> one sum: the shares depend on the tile count alone
   const int64_t share = ceil_div(L.n_tiles, kSumBlocks);

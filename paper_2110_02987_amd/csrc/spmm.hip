@@ -208,6 +208,7 @@ int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, i
            hipStream_t s) {
   const TI* aux = static_cast<const TI*>(e.aux);
   const int64_t ldp = round_up(width, 4);
+  GAD_GRID_CHECK(ceil_div(g->n_short, 4) + ceil_div(g->n_chunks, 4), 256);
   const unsigned row_blocks = (unsigned)ceil_div(g->n_short, 4);
   const unsigned chunk_blocks = (unsigned)ceil_div(g->n_chunks, 4);
   const dim3 grid(chunk_blocks + row_blocks, (unsigned)ceil_div(width, LPR * V));

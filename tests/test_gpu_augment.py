@@ -45,6 +45,27 @@ def test_augment_matches_oracle(gad, n, avg, l, part, budget, seed):
     assert n2 == exp2["n_walks"] == cap and np.array_equal(halo2.cpu().numpy(), exp2["halo"])
 
 
+@pytest.mark.parametrize("n_part", [601, 600, 130])
+def test_augment_with_a_hub_row_inside_the_partition(gad, n_part):
+    """A hub of 600 neighbours (its row spans several 128-entry chunks) on top of a ring: with rows 0..600 in the
+    partition the hub is interior, with rows 0..599 its last chunk holds the one outside neighbour, with rows 0..129
+    every chunk but the first does."""
+    n = 1000
+    hub = np.arange(1, 601, dtype=np.int64)
+    ring = np.arange(1, n, dtype=np.int64)                       # the ring leaves the hub (node 0) out
+    gr = dict(src=np.concatenate([np.zeros(600, dtype=np.int64), ring]), dst=np.concatenate([hub, ring % (n - 1) + 1]),
+              n_global=n, local_ids=np.arange(n, dtype=np.int64), halo_ids=np.zeros(0, dtype=np.int64))
+    G = gad.build_subgraph(dev(gr["src"]), dev(gr["dst"]), n, dev(gr["local_ids"]), dev(gr["halo_ids"]))
+    ref = T1.build(**gr)
+    assert_csr_equal(G, ref)
+    rows = np.arange(n_part, dtype=np.int64)
+    assert (0 in AUG.boundary(ref.rowptr, ref.colidx, rows)) == (n_part != 601)
+    for seed in (0, 1):
+        exp = AUG.augment(ref.rowptr, ref.colidx, rows, 3, 40, seed)
+        halo, n_walks = gad.augment_subgraph(G, dev(rows), 3, 40, seed)
+        assert n_walks == exp["n_walks"] and np.array_equal(halo.cpu().numpy(), exp["halo"])
+
+
 def test_augment_degenerate_and_errors(gad):
     _, G, ref = _whole_graph(gad, 400, 4.0, seed=2)
     everything = torch.arange(400, dtype=torch.int64, device="cuda")

@@ -53,6 +53,37 @@ def test_reddit_shaped_partition(gad):
     progress(f"[reddit_part] pair importance ok: {out2[0].item():.6e}")
 
 
+def test_pair_importance_beyond_2_32_threads(gad):
+    """800,000 nodes = 1.95e7 pair tiles, more threads than one grid dimension holds: the tile grid is folded.
+    No double loop finishes at this size; two node-vector patterns with a closed form stand in (a property that
+    holds at any size: every pair is counted exactly once).  Identical vectors: zeta_pair = S_pp / beta (the paper's
+    worked example).  Two values a, b by the parity of the row: the like pairs contribute
+    (S_even^2 - Q_even + S_odd^2 - Q_odd) / (2 beta), the unlike pairs S_even S_odd / (||a - b|| + beta), with
+    S = sum of p_i and Q = sum of p_i^2 over the rows of a parity."""
+    import dataclasses
+    n = 800_000
+    cfg = dataclasses.replace(wl.CONFIGS["tiny"], n_local=n, n_halo=0, avg_degree=4.0)
+    progress("[pairs_800k] generating graph")
+    g, ref = build_both(gad, wl.make_graph(cfg))
+    beta = 0.25
+    out2 = torch.zeros(2, dtype=torch.float64, device="cuda")
+    V = np.tile(np.linspace(-1.0, 2.0, 24, dtype=np.float32), (n, 1))
+    gad.pair_importance(g, dev(V), beta, out2)
+    spp = T1.zeta(ref, V, beta)[1]
+    assert abs(out2[1].item() - spp) <= 1e-12
+    assert abs(out2[0].item() - spp / beta) <= 1e-6 * spp / beta
+    progress(f"[pairs_800k] identical vectors ok: {out2[0].item():.9e}")
+    a, b = V[0].copy(), V[0][::-1].copy()
+    V[1::2] = b
+    gad.pair_importance(g, dev(V), beta, out2)
+    p = ref.deg.astype(np.float64) / float(ref.deg.sum())
+    se, so, qe, qo = p[0::2].sum(), p[1::2].sum(), (p[0::2] ** 2).sum(), (p[1::2] ** 2).sum()
+    d = float(np.linalg.norm(a.astype(np.float64) - b.astype(np.float64)))
+    exp = (se * se - qe + so * so - qo) / (2 * beta) + se * so / (d + beta)
+    assert abs(out2[0].item() - exp) <= TOL * exp
+    progress(f"[pairs_800k] two-value vectors ok: {out2[0].item():.9e} vs {exp:.9e}")
+
+
 @pytest.mark.parametrize("name", ["reddit_part", "products_part"])
 def test_partitions_in_bf16_storage(gad, name):
     """The second and third workloads with bfloat16 storage of features and activations (bf16 matrix instruction for
