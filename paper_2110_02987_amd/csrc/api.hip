@@ -482,6 +482,7 @@ int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X,
   if (!graphs || !X || !dims || !params || !labels || !loss_scales || !workspaces || !workspace_bytes || !grads || !zeta)
     return set_error(GAD_ERR_NULL, "a required argument is NULL");
   if (L < 1 || L > kMaxLayers) return set_error(GAD_ERR_SHAPE, "L = %d outside [1, %d]", L, kMaxLayers);
+  if (!isfinite(eta)) return set_error(GAD_ERR_SHAPE, "eta is not finite");
   int64_t off[kMaxLayers + 1];
   off[0] = 0;
   for (int l = 0; l < L; ++l) {

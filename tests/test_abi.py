@@ -60,3 +60,15 @@ def test_host_side_validation(lib):
     assert lib.gad_weighted_consensus(None, C.c_int(2), z, C.c_int64(4), C.c_void_p(16), None) == -1
     assert lib.gad_spmm(None, None, C.c_int64(4), None, C.c_int64(4), C.c_int32(4), C.c_int(0), None) == -1
     assert lib.gad_subgraph_variance(None, None, C.c_int32(4), C.c_int(0), C.c_double(1.0), None, None, None) == -1
+    # entry points added around the per-iteration step: the host checks come before any launch
+    assert lib.gad_gemm_workspace_bytes(C.c_int64(8), C.c_int32(0), C.c_int32(8), C.byref(b)) == -2
+    assert lib.gad_gemm_workspace_bytes(C.c_int64(8), C.c_int32(8), C.c_int32(8), None) == -1
+    assert lib.gad_spmm_workspace_bytes(None, C.c_int32(8), C.byref(b)) == -1
+    assert lib.gad_pair_importance_workspace_bytes(None, C.c_int32(8), C.byref(b)) == -1
+    assert lib.gad_pair_importance(None, None, C.c_int32(4), C.c_int(0), C.c_double(1.0), None, None, C.c_size_t(0), None) == -1
+    assert lib.gad_graph_concat(None, C.c_int(2), None, C.byref(out)) == -1
+    assert lib.gad_graph_concat(bufs, C.c_int(0), None, C.byref(out)) == -2
+    nh = C.c_int64()
+    assert lib.gad_augment_subgraph(None, None, C.c_int64(1), C.c_int32(2), C.c_int64(1), C.c_uint64(0), C.c_int64(10),
+                                    None, C.byref(nh), None, None) == -1
+    assert lib.gad_consensus_update(bufs, C.c_int(2), z, C.c_int64(4), C.c_float(0.1), None, None, None) == -1
