@@ -307,6 +307,19 @@ __global__ void fill_long_rows(int64_t n, const uint32_t* __restrict__ chunk_fir
   long_first[long_slot[i]] = (int32_t)chunk_first[i];
 }
 
+// is_many[i] = 1 iff row i has more than kWaveReduce chunks
+__global__ void flag_many(int64_t n, const uint32_t* __restrict__ chunks_of, uint32_t* __restrict__ is_many) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i < n) is_many[i] = chunks_of[i] > (uint32_t)kWaveReduce ? 1u : 0u;
+}
+
+// many_pos: exclusive scan of is_many; long_slot: position of row i among the long rows.
+__global__ void fill_many(int64_t n, const uint32_t* __restrict__ is_many, const uint32_t* __restrict__ many_pos,
+                          const uint32_t* __restrict__ long_slot, int32_t* __restrict__ many_slot) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i < n && is_many[i]) many_slot[many_pos[i]] = (int32_t)long_slot[i];
+}
+
 // One block per long row: its chunks, and for each the key (first gathered column << 32 | chunk id).
 __global__ __launch_bounds__(256) void fill_chunks(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
                                                    const int32_t* __restrict__ long_row,
@@ -427,6 +440,17 @@ int build_schedule(gad_graph* g, hipStream_t s) {
     }
     take_low32<<<(unsigned)ceil_div(g->n_chunks, 256), 256, 0, s>>>(ck, g->n_chunks, g->chunk_perm);
     GAD_LAUNCH_CHECK();
+    // the rows whose chunk sums a whole block adds (is_long and chunk_first are free again: reused as flag and scan)
+    GAD_HIP(hipMalloc((void**)&g->many_slot, sizeof(int32_t) * (size_t)g->n_long));
+    flag_many<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(n, chunks_of, is_long);
+    GAD_LAUNCH_CHECK();
+    GAD_HIP(hipMemcpyAsync(chunk_first, is_long, sizeof(uint32_t) * (size_t)n, hipMemcpyDeviceToDevice, s));
+    if ((st = exclusive_scan_u32(chunk_first, (uint32_t)n, tile_tmp, flags + 3, s)) != GAD_OK) return st;
+    fill_many<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(n, is_long, chunk_first, long_slot, g->many_slot);
+    GAD_LAUNCH_CHECK();
+    GAD_HIP(hipMemcpyAsync(h, flags, 4 * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    GAD_HIP(hipStreamSynchronize(s));
+    g->n_many = (int32_t)h[3];
   }
   GAD_HIP(hipStreamSynchronize(s));
   return GAD_OK;

@@ -54,6 +54,7 @@ struct Epi {
 // Rows longer than this many non-zeros are split into chunks of this size; each chunk is summed by
 // one wave into a partial row and the partials of a row are added in chunk order.
 constexpr int kLongRow = 128;
+constexpr int kWaveReduce = 64;   // chunk sums of a row that one wave adds; rows with more are added by a block
 constexpr int kMaxWidth = 4096;      // widest feature / hidden dimension accepted
 constexpr int kMaxLayers = 16;
 constexpr int kMaxConsensus = 128;   // most buffers one consensus call averages
@@ -77,6 +78,8 @@ struct gad_graph {
   int32_t n_chunks = 0;              // total number of chunks over all long rows
   int32_t* long_row = nullptr;       // [n_long] row id, ascending
   int32_t* long_first = nullptr;     // [n_long] first chunk id of the row (its chunks are consecutive)
+  int32_t n_many = 0;                // long rows of more than kWaveReduce chunks
+  int32_t* many_slot = nullptr;      // [n_many] their positions in long_row, ascending
   int32_t* chunk_row = nullptr;      // [n_chunks] row id of the chunk
   int32_t* chunk_begin = nullptr;    // [n_chunks] offset of the chunk inside its row
   int32_t* chunk_perm = nullptr;     // [n_chunks] chunk ids in scheduling order

@@ -128,8 +128,6 @@ __global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ r
 // Rows with k <= kWaveReduce: one wave per (row, slab of 256 columns) adds the chunks in chunk order.
 // Rows with more chunks: one block per (row, slab of 64 columns); the chunks are cut into four contiguous runs,
 // one per wave, each added in chunk order, then the four run sums are added in run order.
-constexpr int kWaveReduce = 64;
-
 template <typename TI, typename TO>
 __global__ __launch_bounds__(256) void spmm_reduce_few(const int64_t* __restrict__ rowptr,
                                                        const float* __restrict__ dinv,
@@ -171,14 +169,15 @@ __global__ __launch_bounds__(256) void spmm_reduce_many(const int64_t* __restric
                                                         const float* __restrict__ dinv,
                                                         const int32_t* __restrict__ long_row,
                                                         const int32_t* __restrict__ long_first,
+                                                        const int32_t* __restrict__ many_slot,
                                                         const float* __restrict__ partial, int64_t ldp, int width,
                                                         TO* __restrict__ out, int64_t ldo, int epi, float slope,
                                                         const TI* __restrict__ aux, int64_t ldaux) {
   __shared__ float run_sum[4][64];
-  const int64_t i = long_row[blockIdx.x];
+  const int slot = many_slot[blockIdx.x];             // only the rows of more than kWaveReduce chunks are launched
+  const int64_t i = long_row[slot];
   const int64_t k = (rowptr[i + 1] - rowptr[i] + kLongRow - 1) / kLongRow;
-  if (k <= kWaveReduce) return;                       // block-uniform
-  const int64_t first = long_first[blockIdx.x];
+  const int64_t first = long_first[slot];
   const int lane = threadIdx.x & 63, run = threadIdx.x >> 6;
   const int64_t q0 = first + run * k / 4, q1 = first + (run + 1) * k / 4;
   const int c = blockIdx.y * 64 + lane;
@@ -222,9 +221,12 @@ int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, i
         g->rowptr, g->dinv, g->long_row, g->long_first, g->n_long, partial, ldp, width, out, ldo, e.kind, e.slope, aux,
         e.ldaux);
     GAD_LAUNCH_CHECK();
-    spmm_reduce_many<TI, TO><<<dim3((unsigned)g->n_long, (unsigned)ceil_div(width, 64)), 256, 0, s>>>(
-        g->rowptr, g->dinv, g->long_row, g->long_first, partial, ldp, width, out, ldo, e.kind, e.slope, aux, e.ldaux);
-    GAD_LAUNCH_CHECK();
+    if (g->n_many > 0) {
+      spmm_reduce_many<TI, TO><<<dim3((unsigned)g->n_many, (unsigned)ceil_div(width, 64)), 256, 0, s>>>(
+          g->rowptr, g->dinv, g->long_row, g->long_first, g->many_slot, partial, ldp, width, out, ldo, e.kind, e.slope,
+          aux, e.ldaux);
+      GAD_LAUNCH_CHECK();
+    }
   }
   return GAD_OK;
 }
