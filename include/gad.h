@@ -15,7 +15,12 @@
  *    A graph is read-only to every call except gad_subgraph_variance, which uses a reduction buffer inside
  *    the graph: variance calls on ONE graph from different streams must not overlap.
  *  - All calls enqueue work on `hip_stream` (a hipStream_t, NULL = default stream) and return
- *    without synchronising, except gad_build_subgraph, which synchronises the stream.
+ *    without synchronising, except gad_build_subgraph, gad_graph_concat and gad_augment_subgraph, which
+ *    synchronise the stream.  gad_gcn_backward (and the training rounds built on it) runs its weight-gradient
+ *    products on a stream of the library's own that forks from `hip_stream` and joins it again before the
+ *    call returns: everything the call enqueues is ordered before later work on `hip_stream`, also while that
+ *    stream is being captured into a HIP graph.  GAD_SERIAL_BACKWARD=1 in the environment keeps all of it on
+ *    `hip_stream`.
  *  - Every function returns a gad_status.  Arguments are validated on the host before any kernel
  *    is launched; nothing is launched when the status is an argument error.  gad_last_error()
  *    returns a thread-local, statically stored message for the last failure on this thread.

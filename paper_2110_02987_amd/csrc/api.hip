@@ -3,6 +3,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 
 #include <mutex>
 #include <unordered_map>
@@ -126,6 +127,39 @@ bool forward_saved(const gad_graph* g, const void* ws, int L, const int32_t* dim
 }
 
 inline void* at(void* ws, size_t off) { return static_cast<char*>(ws) + off; }
+
+// The weight-gradient products of the backward pass are bound by the matrix cores, the sparse products next to them
+// by memory, and neither needs the other's result: dW_l runs on a side stream while the main stream goes on with
+// the gradient of the layer below.  One side stream (default priority) and two events per host thread and device,
+// created at first use and kept until the process ends.  The fork / join pattern (event recorded on one stream,
+// awaited on the other) is also valid while the caller's stream is being captured into a HIP graph.
+struct Side {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, done = nullptr;
+};
+
+int side_of_this_thread(Side** out) {
+  thread_local std::unordered_map<int, Side> sides;
+  int dev = 0;
+  GAD_HIP(hipGetDevice(&dev));
+  Side& sd = sides[dev];
+  if (!sd.stream) {
+    GAD_HIP(hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking));
+    GAD_HIP(hipEventCreateWithFlags(&sd.fork, hipEventDisableTiming));
+    GAD_HIP(hipEventCreateWithFlags(&sd.done, hipEventDisableTiming));
+  }
+  *out = &sd;
+  return GAD_OK;
+}
+
+// GAD_SERIAL_BACKWARD=1 in the environment keeps the whole backward pass on the caller's stream.
+bool overlap_enabled() {
+  static const bool on = [] {
+    const char* v = getenv("GAD_SERIAL_BACKWARD");
+    return !(v && v[0] == '1');
+  }();
+  return on;
+}
 
 }  // namespace
 }  // namespace gad
@@ -297,6 +331,31 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
   void* wsc = at(workspace, p.wt);
   float* psum = static_cast<float*>(at(workspace, p.sp));
   float* tn = static_cast<float*>(at(workspace, p.tn));
+  Side* side = nullptr;
+  if (overlap_enabled() && (st = side_of_this_thread(&side)) != GAD_OK) return st;
+  bool side_busy = false;                                // a weight gradient is in flight on the side stream
+  // dW_l = A^T B on the side stream, after everything enqueued on the main stream so far
+  auto weight_grad = [&](const void* A, int64_t lda, const void* B, int64_t ldb, int l) -> int {
+    hipStream_t ws = s;
+    if (side) {
+      GAD_HIP(hipEventRecord(side->fork, s));
+      GAD_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
+      ws = side->stream;
+    }
+    int r = gemm_tn(A, lda, B, ldb, dtype, dW[l], dims[l + 1], n, dims[l], dims[l + 1], tn, ws);
+    if (side) {
+      GAD_HIP(hipEventRecord(side->done, side->stream));
+      side_busy = true;
+    }
+    return r;
+  };
+  // the main stream waits for the weight gradient in flight: before a buffer it reads is written again, and
+  // before this call returns
+  auto join = [&]() -> int {
+    if (side_busy) GAD_HIP(hipStreamWaitEvent(s, side->done, 0));
+    side_busy = false;
+    return GAD_OK;
+  };
   for (int l = L - 1; l >= 0; --l) {
     const int fin = dims[l], fout = dims[l + 1];
     const int64_t ldg = pad_ld(fout);        // G_l, S_l
@@ -309,26 +368,28 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
     dact.slope = negative_slope;
     dact.aux = hin;
     dact.ldaux = ldhin;
-    if (G_out && G_out[l] && (st = copy_rows(gcur, ldg, dtype, G_out[l], fout, n, fout, s)) != GAD_OK) return st;
+    if (G_out && G_out[l] && (st = copy_rows(gcur, ldg, dtype, G_out[l], fout, n, fout, s)) != GAD_OK) break;
+    // the layer above may still be reading tmp and what is now gnext (its G); both are written below
+    if ((st = join()) != GAD_OK) break;
     if (p.agg_first[l]) {
-      if ((st = gemm_tn(at(workspace, p.agg[l]), ldi, gcur, ldg, dtype, dW[l], fout, n, fin, fout, tn, s)) != GAD_OK)
-        return st;
-      if (l > 0) {
-        if ((st = gemm_w(gcur, ldg, dtype, W[l], fin, fout, true, tmp, ldi, dtype, n, none, wsc, s)) != GAD_OK) return st;
-        if ((st = spmm(g, tmp, ldi, dtype, gnext, ldi, dtype, fin, dact, psum, s)) != GAD_OK) return st;
-      }
+      // forked behind the dense product, so that the weight gradient (matrix cores) runs beside the sparse
+      // product (memory) rather than beside another dense product
+      if (l > 0 && (st = gemm_w(gcur, ldg, dtype, W[l], fin, fout, true, tmp, ldi, dtype, n, none, wsc, s)) != GAD_OK) break;
+      if ((st = weight_grad(at(workspace, p.agg[l]), ldi, gcur, ldg, l)) != GAD_OK) break;
+      if (l > 0 && (st = spmm(g, tmp, ldi, dtype, gnext, ldi, dtype, fin, dact, psum, s)) != GAD_OK) break;
     } else {
-      if ((st = spmm(g, gcur, ldg, dtype, tmp, ldg, dtype, fout, none, psum, s)) != GAD_OK) return st;
-      if ((st = gemm_tn(hin, ldhin, tmp, ldg, dtype, dW[l], fout, n, fin, fout, tn, s)) != GAD_OK) return st;
+      if ((st = spmm(g, gcur, ldg, dtype, tmp, ldg, dtype, fout, none, psum, s)) != GAD_OK) break;
+      if ((st = weight_grad(hin, ldhin, tmp, ldg, l)) != GAD_OK) break;
       if (l > 0) {
-        if ((st = gemm_w(tmp, ldg, dtype, W[l], fin, fout, true, gnext, ldi, dtype, n, dact, wsc, s)) != GAD_OK) return st;
+        if ((st = gemm_w(tmp, ldg, dtype, W[l], fin, fout, true, gnext, ldi, dtype, n, dact, wsc, s)) != GAD_OK) break;
       }
     }
     void* t = gcur;
     gcur = gnext;
     gnext = t;
   }
-  return GAD_OK;
+  const int stj = join();                                // also on an error path: the side stream never outlives the call
+  return st != GAD_OK ? st : stj;
 }
 
 int gad_gcn_activation(const gad_graph* g, const void* workspace, size_t workspace_bytes, int L,
