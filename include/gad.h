@@ -216,7 +216,9 @@ int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtyp
  *   V          [n x F] node vectors, ld = F; float32 or bfloat16.
  *   out2       device double[2]: zeta_pair, S_pp.
  *   workspace  device, 256-byte aligned, gad_pair_importance_workspace_bytes(g, F) bytes.
- * Errors: as gad_subgraph_variance; n above about 47 million (more pair tiles than one launch holds). */
+ * The pair terms are formed in float32 (distances below 1e-19 count as 0) and summed in float64.
+ * Errors: as gad_subgraph_variance; beta outside the normal float32 range; n above about 47 million (more pair
+ * tiles than one launch holds). */
 int gad_pair_importance_workspace_bytes(const gad_graph* g, int32_t F, size_t* bytes);
 int gad_pair_importance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta, double* out2,
                         void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -490,6 +490,8 @@ int gad_pair_importance(const gad_graph* g, const void* V, int32_t F, gad_dtype 
   if (!g || !V || !out2 || !workspace) return set_error(GAD_ERR_NULL, "graph, V, out2 or workspace is NULL");
   if (F < 1 || F > kMaxWidth) return set_error(GAD_ERR_SHAPE, "F = %d outside [1, %d]", F, kMaxWidth);
   if (!(beta > 0.0) || !isfinite(beta)) return set_error(GAD_ERR_SHAPE, "beta must be positive and finite");
+  if (!((float)beta >= 1.17549435e-38f) || !isfinite((float)beta))      // the pair terms are formed in float32
+    return set_error(GAD_ERR_SHAPE, "beta = %g is not a normal float32 number", beta);
   if (dtype != GAD_F32 && dtype != GAD_BF16) return set_error(GAD_ERR_UNSUPPORTED, "unknown dtype");
   if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 ||
       workspace_bytes < pair_importance_workspace_bytes(g->n, F))

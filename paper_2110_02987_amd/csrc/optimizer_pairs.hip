@@ -141,7 +141,14 @@ __global__ __launch_bounds__(256) void pair_tiles(const float* __restrict__ Vc, 
     __syncthreads();
   }
 
+  // 64 pairs per lane.  Square root and reciprocal are the hardware's one-instruction forms (1 ulp; the library
+  // forms cost ten times the instructions and this loop bounds the kernel for short vectors); a squared distance
+  // below the smallest normal float counts as 0.  Rows and columns past n carry degree 0.
+  // First pass: every pair from the Gram tile; a pair whose lost digits would show adds nothing here and sets its
+  // bit.  Second pass: those pairs, from coordinate differences.  Keeping the rare path
+  // out of the unrolled loop keeps the kernel's code small.
   float sum = 0.f;
+  uint32_t redo[2] = {0u, 0u};                         // redo[tm], bit 16 tn + r
 #pragma unroll
   for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
@@ -152,30 +159,37 @@ __global__ __launch_bounds__(256) void pair_tiles(const float* __restrict__ Vc, 
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int rl = wm * 64 + tm * 32 + acc_row(r, lane);
-        const int64_t gi = i0 + rl;
-        if (gi < gj && gj < n) {
-          const float ni = info[0][rl];
-          float d2 = fmaxf(ni + nj - 2.f * acc[tm][tn][r], 0.f);
-          float d = sqrtf(d2);
-          const float delta = kGramErr * (ni + nj);
-          if (delta > kTermTol * (d + sqrtf(delta)) * (d + beta)) {   // close pair whose lost digits would show
-            const float4* a = reinterpret_cast<const float4*>(Vc + gi * ldv);
-            const float4* b = reinterpret_cast<const float4*>(Vc + gj * ldv);
-            float e = 0.f;
-            for (int c = 0; c < K / 4; ++c) {
-              const float4 x = a[c], y = b[c];
-              const float d0 = x.x - y.x, d1 = x.y - y.y, d2_ = x.z - y.z, d3 = x.w - y.w;
-              e = fmaf(d0, d0, e);
-              e = fmaf(d1, d1, e);
-              e = fmaf(d2_, d2_, e);
-              e = fmaf(d3, d3, e);
-            }
-            d = sqrtf(e);
-          }
-          sum += info[1][rl] * dj / (d + beta);
-        }
+        const bool valid = (i0 + rl < gj) & (gj < n);                 // (bitwise: no branches in this loop)
+        const float s2 = info[0][rl] + nj;
+        const float d2 = fmaxf(s2 - 2.f * acc[tm][tn][r], 0.f);
+        const float d = __builtin_amdgcn_sqrtf(d2);
+        const float delta = kGramErr * s2;
+        const bool close = valid & (delta > kTermTol * (d + __builtin_amdgcn_sqrtf(delta)) * (d + beta));
+        redo[tm] |= (close ? 1u : 0u) << (16 * tn + r);
+        const float w = (valid & !close) ? info[1][rl] * dj : 0.f;
+        sum = fmaf(w, __builtin_amdgcn_rcpf(d + beta), sum);
       }
     }
+  uint64_t todo = ((uint64_t)redo[1] << 32) | redo[0];
+  while (todo != 0) {
+    const int bit = __ffsll((unsigned long long)todo) - 1;
+    todo &= todo - 1;
+    const int tm = bit >> 5, tn = (bit >> 4) & 1, r = bit & 15;
+    const int rl = wm * 64 + tm * 32 + acc_row(r, lane);
+    const int cl = wn * 64 + tn * 32 + (lane & 31);
+    const float4* a = reinterpret_cast<const float4*>(Vc + (i0 + rl) * ldv);
+    const float4* b = reinterpret_cast<const float4*>(Vc + (j0 + cl) * ldv);
+    float e = 0.f;
+    for (int c = 0; c < K / 4; ++c) {
+      const float4 x = a[c], y = b[c];
+      const float d0 = x.x - y.x, d1 = x.y - y.y, d2 = x.z - y.z, d3 = x.w - y.w;
+      e = fmaf(d0, d0, e);
+      e = fmaf(d1, d1, e);
+      e = fmaf(d2, d2, e);
+      e = fmaf(d3, d3, e);
+    }
+    sum = fmaf(info[1][rl] * info[3][cl], __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(e) + beta), sum);
+  }
   red[t] = (double)sum;
   __syncthreads();
   for (int o = 128; o > 0; o >>= 1) {
