@@ -28,6 +28,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="products_part")
+    ap.add_argument("--storage", choices=["f32", "bf16"], default=None,
+                    help="storage type of features / activations (default: the workload's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=20, help="standalone launches of the dominant kernel")
     ap.add_argument("--kernels-only", action="store_true",
@@ -44,6 +46,11 @@ def main() -> int:
     from paper_2110_02987_amd import gad, workloads as wl
 
     cfg = wl.CONFIGS[args.workload]
+    variant = ""
+    if args.storage and args.storage != cfg.dtype:          # a variant of the named workload, reported as such
+        import dataclasses
+        cfg = dataclasses.replace(cfg, dtype=args.storage)
+        variant = f" [{args.storage} storage variant]"
     dims, L = list(cfg.dims), cfg.n_layers
     torch.cuda.set_device(0)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -168,7 +175,7 @@ def main() -> int:
     # HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE in KiB, each scaled by
     # what the same counter reads for a plain 1 GiB copy); None when no summary covers this workload.
     tr = os.path.join(ROOT, "profiles", f"spmm_{cfg.name}_hbm_traffic.txt")
-    if os.path.exists(tr):
+    if os.path.exists(tr) and not variant:                  # the committed counters are those of the workload's own type
         for line in open(tr):
             if line.startswith("traffic "):
                 kv = dict(t.split("=") for t in line.split()[1:])
@@ -238,7 +245,7 @@ def main() -> int:
     out = dict(metric="GCN fwd+bwd edges/s per layer and epoch ms per subgraph; SpMM % of HBM peak",
                value=value, unit="edges/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step,
                higher_is_better=True, scaling="weak", vs_baseline=None, dtype=cfg.dtype, data="synthetic",
-               config=dict(workload=f"{cfg.name}: n={g.n} ({cfg.n_local} local + {cfg.n_halo} halo), nnz={g.nnz}, "
+               config=dict(workload=f"{cfg.name}{variant}: n={g.n} ({cfg.n_local} local + {cfg.n_halo} halo), nnz={g.nnz}, "
                                     f"GCN {'-'.join(map(str, dims))}, consensus K={K}",
                            n=g.n, nnz=g.nnz, dims=dims),
                epoch_ms=epoch_ms, forward_ms=fwd_ms, backward_ms=bwd_ms, variance_consensus_ms=tail_ms,

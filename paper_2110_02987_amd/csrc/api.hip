@@ -277,7 +277,9 @@ int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, c
     Epi act;                                             // sigma of Eq. 7 on every layer but the last
     act.kind = last ? EPI_NONE : EPI_RELU;
     act.slope = negative_slope;
-    const Epi none;
+    act.full_rows = true;                                // its input is the aggregate in the workspace
+    Epi none;
+    none.full_rows = h != X;                             // workspace matrices are whole [n x ld] blocks; X is the caller's
     const gad_dtype t_dst = last ? GAD_F32 : dtype;      // the logits are kept in float32
     void* dst = at(workspace, p.act[l + 1]);
     const int64_t ldd = pad_ld(dims[l + 1]);
@@ -342,7 +344,7 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
       GAD_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
       ws = side->stream;
     }
-    int r = gemm_tn(A, lda, B, ldb, dtype, dW[l], dims[l + 1], n, dims[l], dims[l + 1], tn, ws);
+    int r = gemm_tn(A, lda, B, ldb, dtype, dW[l], dims[l + 1], n, dims[l], dims[l + 1], tn, A != X, ws);
     if (side) {
       GAD_HIP(hipEventRecord(side->done, side->stream));
       side_busy = true;
@@ -362,12 +364,14 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
     const int64_t ldi = pad_ld(fin);         // dM, G_{l-1}, H_l
     const void* hin = l == 0 ? X : at(workspace, p.act[l]);
     const int64_t ldhin = l == 0 ? dims[0] : ldi;
-    const Epi none;
+    Epi none;
+    none.full_rows = true;                               // the dense products below read workspace matrices
     Epi dact;                                            // derivative of sigma, decided by the saved activation H_l
     dact.kind = EPI_MASK;
     dact.slope = negative_slope;
     dact.aux = hin;
     dact.ldaux = ldhin;
+    dact.full_rows = true;
     if (G_out && G_out[l] && (st = copy_rows(gcur, ldg, dtype, G_out[l], fout, n, fout, s)) != GAD_OK) break;
     // the layer above may still be reading tmp and what is now gnext (its G); both are written below
     if ((st = join()) != GAD_OK) break;
@@ -466,7 +470,8 @@ int gad_gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, float* C
   if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 ||
       workspace_bytes < gemm_tn_partial_floats(M, K, N) * sizeof(float))
     return set_error(GAD_ERR_WORKSPACE, "workspace too small or not %zu-byte aligned", kAlign);
-  return gemm_tn(A, lda, G, ldg, dtype, C, N, M, K, N, static_cast<float*>(workspace), static_cast<hipStream_t>(hip_stream));
+  return gemm_tn(A, lda, G, ldg, dtype, C, N, M, K, N, static_cast<float*>(workspace), false,
+                 static_cast<hipStream_t>(hip_stream));
 }
 
 int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta, double* out3,

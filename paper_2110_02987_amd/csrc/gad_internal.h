@@ -49,6 +49,7 @@ struct Epi {
   float slope = 0.f;
   const void* aux = nullptr;   // storage type of the kernel's node-matrix input
   int64_t ldaux = 0;
+  bool full_rows = false;      // every row of the node-matrix input can be read up to its leading dimension
 };
 
 // Rows longer than this many non-zeros are split into chunks of this size; each chunk is summed by
@@ -124,11 +125,11 @@ size_t bf16_weight_elems(int n_out, int k);      // elements of the bfloat16 cop
 int gemm_w_bf16(const void* A, int64_t lda, const float* W, int w_rows, int w_cols, bool trans_w, void* C, int64_t ldc,
                 gad_dtype tc, int64_t M, const Epi& epi, void* scratch, hipStream_t s);
 int gemm_tn_bf16(const void* A, int64_t lda, const void* G, int64_t ldg, float* partials, int64_t M, int K, int N,
-                 int n_slabs, int64_t slab_rows, hipStream_t s);
+                 int n_slabs, int64_t slab_rows, bool full_rows, hipStream_t s);
 // C[K x N] (ldc) = A[M x K]^T * G[M x N]; `partials` must hold gemm_tn_partial_floats(M, K, N) floats.
 size_t gemm_tn_partial_floats(int64_t M, int K, int N);
 int gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, gad_dtype t, float* C, int64_t ldc, int64_t M,
-            int K, int N, float* partials, hipStream_t s);
+            int K, int N, float* partials, bool full_rows, hipStream_t s);
 int transpose_f32(const float* in, int rows, int cols, float* out, hipStream_t s);   // out[cols x rows]
 
 // Z [n x C] (ldz, float32) -> G [n x C] (ldg, storage type tg), loss (double, device).

@@ -325,13 +325,13 @@ size_t gemm_tn_partial_floats(int64_t M, int K, int N) {
 }
 
 int gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, gad_dtype t, float* C, int64_t ldc, int64_t M,
-            int K, int N, float* partials, hipStream_t s) {
+            int K, int N, float* partials, bool full_rows, hipStream_t s) {
   if (K == 0 || N == 0) return GAD_OK;
   if (t == GAD_F32) return gemm_tn_f32((const float*)A, lda, (const float*)G, ldg, C, ldc, M, K, N, partials, s);
   int n_slabs;
   int64_t slab_rows;
   tn_split(M, K, N, &n_slabs, &slab_rows);
-  int st = gemm_tn_bf16(A, lda, G, ldg, partials, M, K, N, n_slabs, slab_rows, s);
+  int st = gemm_tn_bf16(A, lda, G, ldg, partials, M, K, N, n_slabs, slab_rows, full_rows, s);
   if (st != GAD_OK) return st;
   const int64_t elems = (int64_t)K * N;
   reduce_slabs<<<(unsigned)ceil_div(elems, 256), 256, 0, s>>>(partials, n_slabs, elems, N, C, ldc);

@@ -65,6 +65,15 @@ __device__ __forceinline__ uint4 keep_if(bool ok, uint4 v) {
   return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
 }
 
+// The first n_valid (any integer; 8 or more keeps all) of the 8 bfloat16 in v, zeros in the others.
+__device__ __forceinline__ uint32_t keep_pair(uint32_t w, int n_valid) {
+  return n_valid >= 2 ? w : (n_valid == 1 ? (w & 0xFFFFu) : 0u);
+}
+__device__ __forceinline__ uint4 keep_first(uint4 v, int n_valid) {
+  return make_uint4(keep_pair(v.x, n_valid), keep_pair(v.y, n_valid - 2), keep_pair(v.z, n_valid - 4),
+                    keep_pair(v.w, n_valid - 6));
+}
+
 // Offset (in elements) of 16-byte chunk `chunk` of tile row `row`; LDK = row stride.
 template <int LDK, bool SWZ>
 __device__ __forceinline__ int tile_off(int row, int chunk) {
@@ -203,10 +212,10 @@ __device__ __forceinline__ void store_rows(const v16f (&acc)[2][TN], float* __re
 // ---- NT ----------------------------------------------------------------------------------------
 // Block tile 128 x (64 TN); work item = (row tile, column tile) with the column tile fastest, so the blocks
 // that share a row tile of A follow each other on one XCD.  Bt has ldb = K rounded up to BK, zero filled.
-// FAST: A may be fetched in aligned 16-byte pieces that lie wholly inside or wholly outside the matrix (16-byte
-// aligned rows, K a multiple of 8).  Its loads are unconditional (a piece outside the matrix is fetched from the
-// matrix's first bytes and zeroed when it is staged), so the compiler can count the loads in flight and wait only
-// for the oldest tile; the general path waits for all of them.
+// FAST: A may be fetched in aligned 16-byte pieces (16-byte aligned rows; a piece that straddles column K reads
+// padding inside the row, which the caller must have declared readable).  Its loads are unconditional (a piece outside the matrix is fetched from the matrix's
+// first bytes; what lies outside is zeroed when the piece is staged), so the compiler can count the loads in
+// flight and wait only for the oldest tile; the general path waits for all of them.
 template <int BK, int TN, int EPI, typename TC, bool FAST>
 __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                       const bf16_t* __restrict__ Bt, int64_t ldb,
@@ -253,8 +262,8 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const bf16_t* __restric
 #pragma unroll
     for (int j = 0; j < PA; ++j) {
       const int p = t + 256 * j;
-      const bool ok = !FAST || (row0 + p / CH < M && k1 + (p % CH) * 8 < K);
-      *reinterpret_cast<uint4*>(tile + (p / CH) * LDK + (p % CH) * 8) = keep_if(ok, a[j]);
+      const int n_valid = !FAST ? 8 : (row0 + p / CH < M ? K - (k1 + (p % CH) * 8) : 0);
+      *reinterpret_cast<uint4*>(tile + (p / CH) * LDK + (p % CH) * 8) = keep_first(a[j], n_valid);
     }
 #pragma unroll
     for (int j = 0; j < PB; ++j) {
@@ -317,7 +326,7 @@ __device__ __forceinline__ void transpose8x8(const uint4 (&in)[8], uint4 (&out)[
   }
 }
 
-// FAST: as for the NT kernel, for both operands (16-byte aligned rows, K and N multiples of 8).
+// FAST: as for the NT kernel, for both operands (16-byte aligned rows).
 template <bool FAST>
 __global__ __launch_bounds__(256, 2) void gemm_tn_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                       const bf16_t* __restrict__ G, int64_t ldg,
@@ -363,7 +372,7 @@ __global__ __launch_bounds__(256, 2) void gemm_tn_kernel(const bf16_t* __restric
     uint4 rin_ok[8], rout[8];
 #pragma unroll
     for (int r = 0; r < 8; ++r)
-      rin_ok[r] = keep_if(!FAST || (m1 + mb * 8 + r < m_end && col_ok), in[r]);
+      rin_ok[r] = keep_first(in[r], !FAST ? 8 : (m1 + mb * 8 + r < m_end ? n_cols - c0 : 0));
     transpose8x8(rin_ok, rout);
 #pragma unroll
     for (int c = 0; c < 8; ++c)
@@ -427,7 +436,7 @@ int launch_nt(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C
   GAD_GRID_CHECK(total, 256);
   const bf16_t* aux = static_cast<const bf16_t*>(e.aux);
   const bool av = vec_ok(A, lda);
-  const bool fast = av && K % 8 == 0;
+  const bool fast = av && (e.full_rows || K % 8 == 0);      // no 16-byte piece may reach past the end of a row
   const bool cv = (ldc % (16 / (int)sizeof(TC)) == 0) && ((reinterpret_cast<uintptr_t>(C) & 15u) == 0);
   const bool xv = aux != nullptr && vec_ok(aux, e.ldaux);
 #define GAD_NT_LAUNCH(EPI)                                                                                          \
@@ -483,12 +492,12 @@ int gemm_w_bf16(const void* A, int64_t lda, const float* W, int w_rows, int w_co
 }
 
 int gemm_tn_bf16(const void* A, int64_t lda, const void* G, int64_t ldg, float* partials, int64_t M, int K, int N,
-                 int n_slabs, int64_t slab_rows, hipStream_t s) {
+                 int n_slabs, int64_t slab_rows, bool full_rows, hipStream_t s) {
   constexpr size_t smem = 2u * 2u * 128u * TLDK * sizeof(bf16_t);
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* g = static_cast<const bf16_t*>(G);
   const bool av = vec_ok(a, lda), gv = vec_ok(g, ldg);
-  const bool fast = av && gv && K % 8 == 0 && N % 8 == 0;
+  const bool fast = av && gv && (full_rows || (K % 8 == 0 && N % 8 == 0));   // no piece may reach past a row's end
   auto kern = fast ? gemm_tn_kernel<true> : gemm_tn_kernel<false>;
   static bool attr_set[2] = {false, false};
   if (!attr_set[fast]) {
