@@ -6,7 +6,7 @@ gcn_forward + gcn_backward (full batch: one pass = one epoch of that subgraph), 
 per-node gradients, and the K-way weighted_consensus of parameter copies.  The CSR build (a load-time
 step) is timed separately and reported as `build_ms`.
 
-Prints ONE JSON line (see README for the fields).  `value` = layer-edges per second:
+Prints ONE JSON line (the README lists the fields).  `value` = layer-edges per second:
 n_layers * nnz(A+I) / (forward + backward time), i.e. the per-layer edge rate of a full fwd+bwd.
 """
 import argparse

@@ -13,7 +13,7 @@ def pytest_configure(config):
 
 
 def progress(msg: str) -> None:
-    """Append a line to gpurun_out/test_progress.log so that long GPU tests show signs of life."""
+    """Append a line to test_progress.log in the run's output folder so that long GPU tests show signs of life."""
     d = os.path.join(ROOT, "gpurun_out")
     try:
         os.makedirs(d, exist_ok=True)

@@ -2,7 +2,7 @@
 CSR bit-exact against the oracle, one whole forward + backward against the float64 CSR oracle,
 plus variance importance and weighted consensus where the workload asks for them.
 
-Each test writes progress lines to gpurun_out/test_progress.log (generation and the float64 oracle take
+Each test appends progress lines to a log in the run's output folder (generation and the float64 oracle take
 tens of seconds on the large graphs).
 """
 import time
