@@ -36,7 +36,7 @@ def _node_matrix(rng, m, width, ld, bf16):
 SHAPES_W = [  # M, K, N, lda, ldc
     (1, 1, 1, 1, 1), (127, 5, 3, 5, 3), (129, 47, 65, 48, 80), (1000, 100, 256, 112, 256), (5000, 256, 47, 256, 48),
     (777, 602, 200, 608, 208), (4096, 128, 512, 128, 512), (2500, 512, 64, 512, 64), (3001, 33, 130, 33, 130),
-    (640, 64, 600, 72, 600),
+    (640, 64, 600, 72, 600), (300, 4096, 64, 4096, 64), (200, 48, 4096, 48, 4096),      # the widest K and N accepted
 ]
 
 
@@ -88,6 +88,7 @@ def test_gemm_w_bf16_is_float32_accumulation(gad):
 SHAPES_TN = [  # M, K, N, lda, ldg
     (1, 1, 1, 1, 1), (63, 5, 3, 5, 3), (1000, 47, 65, 48, 80), (70_000, 100, 256, 112, 256), (33_333, 256, 47, 256, 48),
     (5000, 602, 41, 608, 48), (20_000, 128, 512, 128, 512), (9001, 130, 129, 130, 129), (150_000, 64, 16, 64, 16),
+    (3000, 4096, 24, 4096, 24), (3000, 24, 4096, 24, 4096),                                # the widest K and N accepted
 ]
 
 

@@ -142,6 +142,19 @@ def test_spmm_widths(gad, width, ld):
         assert np.all(np.isnan(got[:, width:]))       # padding columns are never written
 
 
+def test_spmm_at_the_widest_row_accepted(gad):
+    """width = 4096 (the maximum): 16 column slabs of the 256-column kernel; one more column is an argument error."""
+    cfg = wl.CONFIGS["tiny"]
+    g, ref = build_both(gad, wl.make_graph(cfg))
+    T = np.random.default_rng(4096).standard_normal((cfg.n, 4096)).astype(np.float32)
+    out = torch.empty((cfg.n, 4096), device="cuda")
+    gad.spmm(g, dev(T), out, 4096)
+    assert rel_err(out.cpu().numpy(), T1.spmm(ref, T.astype(np.float64))) < TOL
+    with pytest.raises(gad.GadError) as e:
+        gad.spmm(g, torch.zeros((cfg.n, 4097), device="cuda"), torch.zeros((cfg.n, 4097), device="cuda"), 4097)
+    assert e.value.status == -2
+
+
 def test_spmm_star_and_isolated(gad):
     n = 5000
     none = np.zeros(0, dtype=np.int64)
@@ -225,7 +238,8 @@ def check_step(gad, g, ref, X, Ws, y, mask, c, dims, bf16=False, slope=0.0):
 
 
 @pytest.mark.parametrize("name,dims", [("tiny", None), ("products_small", None), ("products_small", (100, 32, 64, 7)),
-                                       ("tiny", (128, 200, 3)), ("tiny", (5, 4)), ("products_small", (33, 41, 47, 41, 602, 13))])
+                                       ("tiny", (128, 200, 3)), ("tiny", (5, 4)), ("products_small", (33, 41, 47, 41, 602, 13)),
+                                       ("tiny", (12, 9) * 8 + (5,))])          # 16 layers: the deepest model accepted
 def test_gcn_step_matches_oracle(gad, name, dims):
     cfg = wl.CONFIGS[name]
     dims = tuple(dims or cfg.dims)
@@ -328,6 +342,12 @@ def test_gcn_errors(gad):
     assert e.value.status == -5
     with pytest.raises(gad.GadError) as e:
         gad.gcn_workspace_bytes(g, (128, 0, 16))
+    assert e.value.status == -2
+    with pytest.raises(gad.GadError) as e:                    # one layer more than the deepest model accepted
+        gad.gcn_workspace_bytes(g, (8,) * 18)
+    assert e.value.status == -2
+    with pytest.raises(gad.GadError) as e:                    # one column more than the widest layer accepted
+        gad.gcn_workspace_bytes(g, (128, 4097, 16))
     assert e.value.status == -2
     gad.gcn_forward(g, X, dims, Ws, y, None, 1.0, ws)
     with pytest.raises(gad.GadError) as e:                    # backward with other dims than the forward
