@@ -133,6 +133,8 @@ inline void* at(void* ws, size_t off) { return static_cast<char*>(ws) + off; }
 // the gradient of the layer below.  One side stream (default priority) and two events per host thread and device,
 // created at first use and kept until the process ends.  The fork / join pattern (event recorded on one stream,
 // awaited on the other) is also valid while the caller's stream is being captured into a HIP graph.
+constexpr double kForkFlops = 2e9;     // smallest weight-gradient product that is forked (about 20 us of matrix work)
+
 struct Side {
   hipStream_t stream = nullptr;
   hipEvent_t fork = nullptr, done = nullptr;
@@ -339,13 +341,15 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
   // dW_l = A^T B on the side stream, after everything enqueued on the main stream so far
   auto weight_grad = [&](const void* A, int64_t lda, const void* B, int64_t ldb, int l) -> int {
     hipStream_t ws = s;
-    if (side) {
+    // a product of a few microseconds gains nothing beside another kernel and would pay for the two events
+    const bool fork = side && 2.0 * (double)n * dims[l] * dims[l + 1] >= kForkFlops;
+    if (fork) {
       GAD_HIP(hipEventRecord(side->fork, s));
       GAD_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
       ws = side->stream;
     }
     int r = gemm_tn(A, lda, B, ldb, dtype, dW[l], dims[l + 1], n, dims[l], dims[l + 1], tn, A != X, ws);
-    if (side) {
+    if (fork) {
       GAD_HIP(hipEventRecord(side->done, side->stream));
       side_busy = true;
     }
