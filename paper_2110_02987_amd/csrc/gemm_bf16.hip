@@ -74,17 +74,28 @@ __device__ __forceinline__ uint4 keep_first(uint4 v, int n_valid) {
                     keep_pair(v.w, n_valid - 6));
 }
 
+// Tile layouts in LDS (rows of BK contraction indices, 16-byte chunks of 8):
+//   kPadded   row stride BK + 8 elements, chunks in place (64-deep tiles: 144-byte stride, conflict free);
+//   kSwzTn    the same stride, chunk c of row r at position c ^ ((r >> 4) & 7) (the transposing writes of the TN tile);
+//   kSwz32    32-deep tiles without padding (64-byte rows), chunk c of row r at position c ^ ((r >> 2) & 3): the
+//             16-byte reads of 16 consecutive rows and the staging writes of 4 consecutive rows each cover 16
+//             different 16-byte slots of a 256-byte window (the padded 80-byte stride made the writes collide).
+enum Layout : int { kPadded = 0, kSwzTn = 1, kSwz32 = 2 };
+template <int BK, int MODE>
+constexpr int tile_ld() { return MODE == kSwz32 ? BK : BK + 8; }
+
 // Offset (in elements) of 16-byte chunk `chunk` of tile row `row`; LDK = row stride.
-template <int LDK, bool SWZ>
+template <int LDK, int MODE>
 __device__ __forceinline__ int tile_off(int row, int chunk) {
-  return row * LDK + ((SWZ ? (chunk ^ ((row >> 4) & 7)) : chunk) << 3);
+  const int c = MODE == kSwzTn ? (chunk ^ ((row >> 4) & 7)) : MODE == kSwz32 ? (chunk ^ ((row >> 2) & 3)) : chunk;
+  return row * LDK + (c << 3);
 }
 
 // acc[tm][tn] += L[wrow + 32 tm .., :] R[wcol + 32 tn .., :]^T over the BK contraction indices of one tile.
-template <int BK, int TM, int TN, bool SWZ>
+template <int BK, int TM, int TN, int MODE>
 __device__ __forceinline__ void mma_tile(const bf16_t* __restrict__ Ls, const bf16_t* __restrict__ Rs, int wrow,
                                          int wcol, v16f (&acc)[TM][TN]) {
-  constexpr int LDK = BK + 8;
+  constexpr int LDK = tile_ld<BK, MODE>();
   const int lane = threadIdx.x & 63;
   const int i = lane & 31, kg = lane >> 5;
 #pragma unroll
@@ -93,10 +104,10 @@ __device__ __forceinline__ void mma_tile(const bf16_t* __restrict__ Ls, const bf
     bf16x8 a[TM], b[TN];
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
-      a[tm] = *reinterpret_cast<const bf16x8*>(Ls + tile_off<LDK, SWZ>(wrow + tm * 32 + i, chunk));
+      a[tm] = *reinterpret_cast<const bf16x8*>(Ls + tile_off<LDK, MODE>(wrow + tm * 32 + i, chunk));
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
-      b[tn] = *reinterpret_cast<const bf16x8*>(Rs + tile_off<LDK, SWZ>(wcol + tn * 32 + i, chunk));
+      b[tn] = *reinterpret_cast<const bf16x8*>(Rs + tile_off<LDK, MODE>(wcol + tn * 32 + i, chunk));
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -223,7 +234,8 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const bf16_t* __restric
                                                       bool a_vec, bool c_vec, float slope,
                                                       const bf16_t* __restrict__ aux, int64_t ldaux, bool aux_vec,
                                                       int tiles_n, int64_t total) {
-  constexpr int BM = 128, BN = 64 * TN, LDK = BK + 8, CH = BK / 8;
+  constexpr int MODE = BK == 32 ? kSwz32 : kPadded;
+  constexpr int BM = 128, BN = 64 * TN, LDK = tile_ld<BK, MODE>(), CH = BK / 8;
   constexpr int PA = BM * CH / 256, PB = BN * CH / 256;      // 16-byte pieces per thread and tile
   constexpr int TILE = (BM + BN) * LDK;
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -263,12 +275,12 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const bf16_t* __restric
     for (int j = 0; j < PA; ++j) {
       const int p = t + 256 * j;
       const int n_valid = !FAST ? 8 : (row0 + p / CH < M ? K - (k1 + (p % CH) * 8) : 0);
-      *reinterpret_cast<uint4*>(tile + (p / CH) * LDK + (p % CH) * 8) = keep_first(a[j], n_valid);
+      *reinterpret_cast<uint4*>(tile + tile_off<LDK, MODE>(p / CH, p % CH)) = keep_first(a[j], n_valid);
     }
 #pragma unroll
     for (int j = 0; j < PB; ++j) {
       const int p = t + 256 * j;
-      *reinterpret_cast<uint4*>(tile + (BM + p / CH) * LDK + (p % CH) * 8) = keep_if(col0 + p / CH < N, b[j]);
+      *reinterpret_cast<uint4*>(tile + BM * LDK + tile_off<LDK, MODE>(p / CH, p % CH)) = keep_if(col0 + p / CH < N, b[j]);
     }
   };
   // The pipeline is free of conditions (fetches past the last tile read the matrix's first bytes, stages past it
@@ -286,7 +298,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const bf16_t* __restric
       const int kt = kt0 + d;
       bf16_t* cur = smem + (kt & 1) * TILE;
       bf16_t* nxt = smem + ((kt & 1) ^ 1) * TILE;
-      mma_tile<BK, 2, TN, false>(cur, cur + BM * LDK, wm * 64, wn * 32 * TN, acc);
+      mma_tile<BK, 2, TN, MODE>(cur, cur + BM * LDK, wm * 64, wn * 32 * TN, acc);
       const int slot = (d + 1) % kDepth;                     // tile kt + 1
       stage(ra[slot], rb[slot], nxt, (kt + 1) * BK);
       fetch(ra[slot], rb[slot], (kt + 1 + kDepth) * BK);
@@ -376,7 +388,7 @@ __global__ __launch_bounds__(256, 2) void gemm_tn_kernel(const bf16_t* __restric
     transpose8x8(rin_ok, rout);
 #pragma unroll
     for (int c = 0; c < 8; ++c)
-      *reinterpret_cast<uint4*>(tl + tile_off<TLDK, true>(tile_row0 + c, mb)) = rout[c];
+      *reinterpret_cast<uint4*>(tl + tile_off<TLDK, kSwzTn>(tile_row0 + c, mb)) = rout[c];
   };
   // As in the NT kernel, the pipeline is free of conditions: rows past the slab are fetched as zeros.
   const int64_t n_mt = (m_end - m_begin + TBK - 1) / TBK;
@@ -392,7 +404,7 @@ __global__ __launch_bounds__(256, 2) void gemm_tn_kernel(const bf16_t* __restric
       const int64_t mt = mt0 + d;
       bf16_t* cur = smem + (mt & 1) * TILE;
       bf16_t* nxt = smem + ((mt & 1) ^ 1) * TILE;
-      mma_tile<TBK, 2, 2, true>(cur, cur, wm * 64, 128 + wn * 64, acc);
+      mma_tile<TBK, 2, 2, kSwzTn>(cur, cur, wm * 64, 128 + wn * 64, acc);
       const int slot = (d + 1) % kTnDepth;                   // tile mt + 1
       stage(rin[slot], nxt, m_begin + (mt + 1) * TBK);
       fetch(rin[slot], m_begin + (mt + 1 + kTnDepth) * TBK);
@@ -428,7 +440,7 @@ template <int kNtBK, int TN, typename TC>
 int launch_nt(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
               const Epi& e, hipStream_t s) {
   constexpr int BN = 64 * TN;
-  constexpr size_t tiles_bytes = 2u * (128 + BN) * (kNtBK + 8) * sizeof(bf16_t);     // double-buffered operand tiles
+  constexpr size_t tiles_bytes = 2u * (128 + BN) * (kNtBK == 32 ? 32 : kNtBK + 8) * sizeof(bf16_t);   // two operand tiles
   constexpr size_t stage_bytes = 4u * 32 * (32 * TN + 8) * sizeof(float);            // epilogue staging, reuses them
   constexpr size_t smem = tiles_bytes > stage_bytes ? tiles_bytes : stage_bytes;
   const int tiles_n = (int)ceil_div(N, BN);
