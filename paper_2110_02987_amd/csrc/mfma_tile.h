@@ -22,8 +22,10 @@ struct Tile {
 // acc[tm][tn] += As[:, 64*wm + 32*tm .. ]^T Bs[:, 64*wn + 32*tn ..]
 // (Measured without gain against this per-k-step form at three blocks per CU: reading all fragments of a tile ahead
 // of the matrix instructions, reading the next step's fragments one step ahead, a 32-deep tile at two blocks per
-// CU, persistent blocks that fetch the next tile before writing the finished one, and starting the three blocks
-// of a CU a third of a tile time apart.)
+// CU, persistent blocks that fetch the next tile before writing the finished one, starting the three blocks
+// of a CU a third of a tile time apart, a 256 x 128 block tile with 4 x 2 accumulators per wave at two blocks per
+// CU (slower: 101 against 113 TFLOP/s at long K), and two tiles in flight in registers (the register ring costs
+// the fourth wave per SIMD).)
 template <int TNW>
 __device__ __forceinline__ void mma_tile(const Tile<TNW>& t, int wm, int wn, v16f (&acc)[2][TNW]) {
   const int lane = threadIdx.x & 63;

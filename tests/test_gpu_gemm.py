@@ -37,6 +37,7 @@ SHAPES_W = [  # M, K, N, lda, ldc
     (1, 1, 1, 1, 1), (127, 5, 3, 5, 3), (129, 47, 65, 48, 80), (1000, 100, 256, 112, 256), (5000, 256, 47, 256, 48),
     (777, 602, 200, 608, 208), (4096, 128, 512, 128, 512), (2500, 512, 64, 512, 64), (3001, 33, 130, 33, 130),
     (640, 64, 600, 72, 600), (300, 4096, 64, 4096, 64), (200, 48, 4096, 48, 4096),      # the widest K and N accepted
+    (300_001, 100, 256, 112, 256), (270_003, 47, 200, 48, 208),                        # tall enough for the 256-row tile
 ]
 
 
