@@ -17,6 +17,7 @@
 #include "dtype.h"
 #include "gad_internal.h"
 #include "mfma_tile.h"
+#include "xcd.h"
 
 namespace gad {
 namespace {
@@ -102,19 +103,22 @@ __device__ __forceinline__ void store_acc(const v16f (&acc)[2][TNW], float* __re
 static_assert(BM * BK / 8 == 256, "one 8-float piece of A per thread and tile");
 
 // ---- NN ----------------------------------------------------------------------------------------
-// grid: x = row tile of C (128 rows), y = column tile (64 TNW columns).
+// grid: one block per (row tile of 128 rows, column tile of 64 TNW columns), column tile fastest and renumbered so
+// that the column tiles of a row tile run on the same XCD: the rows of A come from HBM once and from that XCD's L2
+// for the other column tiles.
 template <int EPI, int TNW>
 __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ A, int64_t lda,
                                                       const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
                                                       int64_t ldc, int64_t M, int N, int K, bool a_vec, bool b_vec,
                                                       bool c_vec, float slope, const float* __restrict__ aux,
-                                                      int64_t ldaux, bool aux_vec) {
+                                                      int64_t ldaux, bool aux_vec, int tiles_n, int64_t total) {
   constexpr int BNW = 64 * TNW, SEGB = BNW / 8;      // block columns; 8-float pieces per B row
   __shared__ __align__(16) unsigned char lds_raw[block_lds_bytes<TNW>()];
   Tile<TNW>* tiles = reinterpret_cast<Tile<TNW>*>(lds_raw);
   const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
-  const int64_t row0 = (int64_t)blockIdx.x * BM;
-  const int col0 = blockIdx.y * BNW;
+  const int64_t item = xcd_order(blockIdx.x, total);
+  const int64_t row0 = (item / tiles_n) * BM;
+  const int col0 = (int)(item % tiles_n) * BNW;
   v16f acc[2][TNW];
 #pragma unroll
   for (int x = 0; x < 2; ++x)
@@ -245,18 +249,24 @@ int gemm_nn_launch(const float* A, int64_t lda, const float* B, int64_t ldb, flo
                    int K, const Epi& e, hipStream_t s) {
   const float* aux = static_cast<const float*>(e.aux);
   const int64_t ldaux = e.ldaux;
-  const dim3 grid((unsigned)ceil_div(M, BM), (unsigned)ceil_div(N, 64 * TNW));
+  const int tiles_n = (int)ceil_div(N, 64 * TNW);
+  const int64_t total = ceil_div(M, BM) * tiles_n;
+  GAD_GRID_CHECK(total, 256);
+  const unsigned grid = (unsigned)total;
   const bool av = vec_ok(A, lda), bv = vec_ok(B, ldb), cv = vec_ok(C, ldc);
   const bool xv = e.kind == EPI_MASK && vec_ok(aux, ldaux);
   switch (e.kind) {
     case EPI_NONE:
-      gemm_nn_kernel<EPI_NONE, TNW><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, cv, e.slope, aux, ldaux, xv);
+      gemm_nn_kernel<EPI_NONE, TNW><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, cv, e.slope, aux, ldaux, xv,
+                                                         tiles_n, total);
       break;
     case EPI_RELU:
-      gemm_nn_kernel<EPI_RELU, TNW><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, cv, e.slope, aux, ldaux, xv);
+      gemm_nn_kernel<EPI_RELU, TNW><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, cv, e.slope, aux, ldaux, xv,
+                                                         tiles_n, total);
       break;
     case EPI_MASK:
-      gemm_nn_kernel<EPI_MASK, TNW><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, cv, e.slope, aux, ldaux, xv);
+      gemm_nn_kernel<EPI_MASK, TNW><<<grid, 256, 0, s>>>(A, lda, B, ldb, C, ldc, M, N, K, av, bv, cv, e.slope, aux, ldaux, xv,
+                                                         tiles_n, total);
       break;
     default:
       return set_error(GAD_ERR_UNSUPPORTED, "unknown epilogue %d", e.kind);

@@ -678,7 +678,10 @@ def test_training_step_under_hip_graph_capture(gad):
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
+    # every call of the round comes from this thread: what other threads of the process do meanwhile is not the
+    # capture's business (in the default "global" mode one call that is unsafe under capture, from any thread,
+    # invalidates it)
+    with torch.cuda.graph(graph, capture_error_mode="thread_local"):
         round_(p_c, g_c, l_c)
     p_c.copy_(dev(flat))                                         # the capture itself does not run the kernels
     for r in range(3):
