@@ -12,6 +12,8 @@
  *  - Matrices are row-major.  "ld" is the leading dimension in elements.
  *  - The caller owns every buffer it passes in, including the workspaces.  The library owns only
  *    gad_graph objects (create / destroy pair) and scratch memory that lives inside one call.
+ *    The calls that allocate or free device memory (gad_build_subgraph, gad_graph_concat, gad_augment_subgraph,
+ *    gad_graph_destroy) must not run while a stream of the process is being captured into a HIP graph.
  *    A graph is read-only to every call except gad_subgraph_variance, which uses a reduction buffer inside
  *    the graph: variance calls on ONE graph from different streams must not overlap.
  *  - All calls enqueue work on `hip_stream` (a hipStream_t, NULL = default stream) and return

@@ -678,11 +678,18 @@ def test_training_step_under_hip_graph_capture(gad):
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
-    # every call of the round comes from this thread: what other threads of the process do meanwhile is not the
-    # capture's business (in the default "global" mode one call that is unsafe under capture, from any thread,
-    # invalidates it)
-    with torch.cuda.graph(graph, capture_error_mode="thread_local"):
-        round_(p_c, g_c, l_c)
+    # Nothing may free device memory while the stream is capturing.  A graph object of an earlier test that is
+    # still waiting for the cycle collector would do just that (gad_graph_destroy frees), so the collector runs
+    # now and stays off until the capture has ended; other threads of the process are not the capture's business
+    # either ("thread_local": only this thread's calls are held to the capture's rules).
+    import gc
+    gc.collect()
+    gc.disable()
+    try:
+        with torch.cuda.graph(graph, capture_error_mode="thread_local"):
+            round_(p_c, g_c, l_c)
+    finally:
+        gc.enable()
     p_c.copy_(dev(flat))                                         # the capture itself does not run the kernels
     for r in range(3):
         graph.replay()
