@@ -19,6 +19,8 @@
 // tile (NT) or two tiles (TN) are on their way from global memory into registers while the current one is
 // multiplied (double-buffered LDS, one barrier per tile).  Blocks are renumbered so that the blocks sharing an operand tile run on the same XCD
 // (consecutive workgroup ids go to different XCDs, each with an L2 of its own).
+#include <atomic>
+
 #include "dtype.h"
 #include "gad_internal.h"
 #include "xcd.h"
@@ -454,11 +456,11 @@ int launch_nt(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C
 #define GAD_NT_LAUNCH(EPI)                                                                                          \
   {                                                                                                                 \
     auto kern = fast ? gemm_nt_kernel<kNtBK, TN, EPI, TC, true> : gemm_nt_kernel<kNtBK, TN, EPI, TC, false>;        \
-    static bool attr_set[2] = {false, false};                                                                       \
-    if (!attr_set[fast]) {                                                                                          \
+    static std::atomic<bool> attr_set[2];          /* set once per kernel; setting it twice is harmless */          \
+    if (!attr_set[fast].load(std::memory_order_acquire)) {                                                          \
       GAD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,  \
                                   (int)smem));                                                                      \
-      attr_set[fast] = true;                                                                                        \
+      attr_set[fast].store(true, std::memory_order_release);                                                        \
     }                                                                                                               \
     kern<<<(unsigned)total, 256, smem, s>>>(A, lda, Bt, ldb, C, ldc, M, N, K, av, cv, e.slope, aux, e.ldaux, xv,    \
                                             tiles_n, total);                                                        \
@@ -511,11 +513,11 @@ int gemm_tn_bf16(const void* A, int64_t lda, const void* G, int64_t ldg, float* 
   const bool av = vec_ok(a, lda), gv = vec_ok(g, ldg);
   const bool fast = av && gv && (full_rows || (K % 8 == 0 && N % 8 == 0));   // no piece may reach past a row's end
   auto kern = fast ? gemm_tn_kernel<true> : gemm_tn_kernel<false>;
-  static bool attr_set[2] = {false, false};
-  if (!attr_set[fast]) {
+  static std::atomic<bool> attr_set[2];            // set once per kernel; setting it twice is harmless
+  if (!attr_set[fast].load(std::memory_order_acquire)) {
     GAD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)smem));
-    attr_set[fast] = true;
+    attr_set[fast].store(true, std::memory_order_release);
   }
   const int tiles_n = (int)ceil_div(N, 128);
   const int tiles = (int)ceil_div(K, 128) * tiles_n;
