@@ -586,7 +586,6 @@ int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int6
   g->n = n;
   g->n_local = n_local;
   g->nnz = nnz;
-  GAD_HIP(hipGetDevice(&g->device));
   auto fail = [&](int st) {
     gad_graph_destroy(g);
     return st;
@@ -596,6 +595,7 @@ int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int6
     hipError_t _e = (expr);                                                                                \
     if (_e != hipSuccess) return fail(set_error(GAD_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(_e))); \
   } while (0)
+  GAD_HIP_G(hipGetDevice(&g->device));
   GAD_HIP_G(hipMalloc((void**)&g->rowptr, sizeof(int64_t) * (size_t)(n + 1)));
   GAD_HIP_G(hipMalloc((void**)&g->colidx, sizeof(int32_t) * (size_t)nnz));
   GAD_HIP_G(hipMalloc((void**)&g->deg, sizeof(int32_t) * (size_t)n));
