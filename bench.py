@@ -95,10 +95,10 @@ def main() -> int:
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    def step(record=None):
+    def step(record=None, x_unchanged=False):
         e = [ev() for _ in range(4)] if record is not None else None
         if e: e[0].record()
-        gad.gcn_forward(g, Xd, dims, Wd, yd, md, c, ws, None, loss, dt)
+        gad.gcn_forward(g, Xd, dims, Wd, yd, md, c, ws, None, loss, dt, x_unchanged=x_unchanged)
         if e: e[1].record()
         gad.gcn_backward(g, Xd, dims, Wd, ws, dW, G_out, dt)
         if e: e[2].record()
@@ -131,6 +131,15 @@ def main() -> int:
     tail_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in rec]))
     epoch_ms = fwd_ms + bwd_ms
     value = L * g.nnz / (epoch_ms * 1e-3)
+    # The same step when the caller vouches that X has not changed (static features): the first layer's aggregate
+    # A~ X is then reused.  Reported beside the figures above, never in `value`.
+    cached_epoch_ms = None
+    if not args.kernels_only:
+        rec_c = []
+        for _ in range(args.steps):
+            step(rec_c, x_unchanged=True)
+        torch.cuda.synchronize()
+        cached_epoch_ms = float(np.mean([e[0].elapsed_time(e[2]) for e in rec_c]))
 
     # ---- dominant kernel: the SpMM at each width the step uses, timed alone with events on the launch stream
     widths = []
@@ -249,6 +258,7 @@ def main() -> int:
                                     f"GCN {'-'.join(map(str, dims))}, consensus K={K}",
                            n=g.n, nnz=g.nnz, dims=dims),
                epoch_ms=epoch_ms, forward_ms=fwd_ms, backward_ms=bwd_ms, variance_consensus_ms=tail_ms,
+               epoch_ms_first_aggregate_reused=cached_epoch_ms,
                build_ms=build_ms, spmm={str(k): v for k, v in spmm.items()}, gemm=gemm, extras=extras,
                mfma_peak_TFLOPs=mfma_peak, roofline=roofline)
 

@@ -159,6 +159,16 @@ int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, c
                     const float* row_scale, float negative_slope, void* workspace, size_t workspace_bytes,
                     float* logits_out, double* loss_out, void* hip_stream);
 
+/* gad_gcn_forward for a caller that guarantees that X holds what it held at the last forward on this workspace:
+ * the first layer's aggregate A~ X (Eq. 7 applied to H_0 = X) does not depend on the weights, so it is the same
+ * in every iteration of Algorithm 2 and is then taken from the workspace instead of being computed again.  Runs
+ * the full forward when the workspace holds no forward of this (g, X, L, dims, dtype), or when the first layer
+ * transforms before it aggregates (dims[0] > dims[1]).  Same arguments, results and errors as gad_gcn_forward. */
+int gad_gcn_forward_cached(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
+                           const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
+                           const float* row_scale, float negative_slope, void* workspace, size_t workspace_bytes,
+                           float* logits_out, double* loss_out, void* hip_stream);
+
 int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
                      const float* const* W, float negative_slope, void* workspace, size_t workspace_bytes,
                      float* const* dW, float* const* G_out, void* hip_stream);

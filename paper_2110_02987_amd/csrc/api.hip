@@ -254,10 +254,11 @@ int gad_gcn_workspace_bytes(const gad_graph* g, int L, const int32_t* dims, gad_
   return GAD_OK;
 }
 
-int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
-                    const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
-                    const float* row_scale, float negative_slope, void* workspace, size_t workspace_bytes,
-                    float* logits_out, double* loss_out, void* hip_stream) {
+// reuse_first: the caller vouches that X is unchanged since the forward this workspace holds
+static int forward_impl(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
+                        const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
+                        const float* row_scale, float negative_slope, void* workspace, size_t workspace_bytes,
+                        float* logits_out, double* loss_out, void* hip_stream, bool reuse_first) {
   Plan p;
   int st = make_plan(g, L, dims, dtype, &p);
   if (st != GAD_OK) return st;
@@ -288,7 +289,9 @@ int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, c
     if (p.agg_first[l]) {
       void* m = at(workspace, p.agg[l]);
       const int64_t ldm = pad_ld(dims[l]);
-      if ((st = spmm(g, h, ldh, dtype, m, ldm, dtype, dims[l], none, psum, s)) != GAD_OK) return st;
+      // A~ X of the first layer is still in the workspace when the last forward on it had this graph, X and model
+      const bool have = l == 0 && reuse_first && forward_saved(g, workspace, L, dims, dtype, X);
+      if (!have && (st = spmm(g, h, ldh, dtype, m, ldm, dtype, dims[l], none, psum, s)) != GAD_OK) return st;
       if ((st = gemm_w(m, ldm, dtype, W[l], dims[l], dims[l + 1], false, dst, ldd, t_dst, n, act, wsc, s)) != GAD_OK)
         return st;
     } else {
@@ -312,6 +315,22 @@ int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, c
     g_saved[workspace] = Saved{g, L, std::vector<int32_t>(dims, dims + L + 1), dtype, X, negative_slope};
   }
   return GAD_OK;
+}
+
+int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
+                    const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
+                    const float* row_scale, float negative_slope, void* workspace, size_t workspace_bytes,
+                    float* logits_out, double* loss_out, void* hip_stream) {
+  return forward_impl(g, X, dtype, L, dims, W, labels, mask, loss_scale, row_scale, negative_slope, workspace,
+                      workspace_bytes, logits_out, loss_out, hip_stream, false);
+}
+
+int gad_gcn_forward_cached(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
+                           const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
+                           const float* row_scale, float negative_slope, void* workspace, size_t workspace_bytes,
+                           float* logits_out, double* loss_out, void* hip_stream) {
+  return forward_impl(g, X, dtype, L, dims, W, labels, mask, loss_scale, row_scale, negative_slope, workspace,
+                      workspace_bytes, logits_out, loss_out, hip_stream, true);
 }
 
 int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libgad.so")
 
 F32, BF16 = 0, 1
 SYMBOLS = ["gad_last_error", "gad_build_subgraph", "gad_graph_info", "gad_graph_destroy", "gad_graph_concat", "gad_augment_subgraph",
-           "gad_gcn_workspace_bytes", "gad_gcn_forward", "gad_gcn_backward", "gad_gcn_activation", "gad_spmm_workspace_bytes", "gad_spmm",
+           "gad_gcn_workspace_bytes", "gad_gcn_forward", "gad_gcn_forward_cached", "gad_gcn_backward", "gad_gcn_activation", "gad_spmm_workspace_bytes", "gad_spmm",
            "gad_gemm_workspace_bytes", "gad_gemm_w", "gad_gemm_tn",
            "gad_subgraph_variance", "gad_pair_importance_workspace_bytes", "gad_pair_importance",
            "gad_weighted_consensus", "gad_consensus_update", "gad_train_round", "gad_train_round_batched"]
@@ -164,7 +164,10 @@ def alloc_workspace(g: Graph, dims: Sequence[int], dtype: int = F32) -> torch.Te
 def gcn_forward(g: Graph, X: torch.Tensor, dims: Sequence[int], W: List[torch.Tensor], labels: torch.Tensor,
                 mask: Optional[torch.Tensor], loss_scale: float, workspace: torch.Tensor,
                 logits_out: Optional[torch.Tensor] = None, loss_out: Optional[torch.Tensor] = None,
-                dtype: int = F32, negative_slope: float = 0.0, row_scale: Optional[torch.Tensor] = None) -> None:
+                dtype: int = F32, negative_slope: float = 0.0, row_scale: Optional[torch.Tensor] = None,
+                x_unchanged: bool = False) -> None:
+    """x_unchanged: the caller vouches that X holds what it held at the last forward on this workspace
+    (gad_gcn_forward_cached: the first layer's aggregate is then reused)."""
     _dev(X, torch.float32 if dtype == F32 else torch.bfloat16, "X")
     _dev(labels, torch.int32, "labels")
     if mask is not None:
@@ -177,7 +180,8 @@ def gcn_forward(g: Graph, X: torch.Tensor, dims: Sequence[int], W: List[torch.Te
         _dev(loss_out, torch.float64, "loss_out")
     if row_scale is not None:
         _dev(row_scale, torch.float32, "row_scale")
-    _check(lib().gad_gcn_forward(g.handle, _ptr(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims), _ptr_array(W),
+    fn = lib().gad_gcn_forward_cached if x_unchanged else lib().gad_gcn_forward
+    _check(fn(g.handle, _ptr(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims), _ptr_array(W),
                                  _ptr(labels), _ptr(mask), C.c_float(loss_scale), _ptr(row_scale), C.c_float(negative_slope), _ptr(workspace),
                                  C.c_size_t(workspace.numel()), _ptr(logits_out), _ptr(loss_out), _stream()))
 

@@ -323,6 +323,59 @@ def test_gcn_step_sum_loss_no_mask_and_dense_oracle(gad):
         assert rel_err(a, b) < TOL
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_forward_with_cached_first_aggregate(gad, bf16):
+    """gad_gcn_forward_cached: with X unchanged the first layer's aggregate is reused.  New weights after a round:
+    logits, loss and (after the backward) dW must be what the full forward gives, bit for bit, and match the
+    oracle.  Another X, another model or a fresh workspace fall back to the full forward; a first layer that
+    transforms before it aggregates has nothing to reuse."""
+    cfg = wl.CONFIGS["products_small"]
+    g, ref = build_both(gad, wl.make_graph(cfg))
+    dims, dtype, tol = (33, 41, 13), (1 if bf16 else 0), (TOL_BF16 if bf16 else TOL)
+    X, X2 = wl.make_features(cfg.n, dims[0]), wl.make_features(cfg.n, dims[0], sub=5)
+    if bf16:
+        (Xd, X), (X2d, X2) = bf16_dev(X), bf16_dev(X2)
+    else:
+        Xd, X2d = dev(X), dev(X2)
+    y, mask = wl.make_labels(cfg.n, dims[-1]), wl.make_mask(cfg)
+    yd, md, c = dev(y), dev(mask), 1.0 / mask.sum()
+    Wa = wl.make_weights(dims)
+    Wb = [w * np.float32(0.7) + np.float32(0.01) for w in Wa]
+
+    def run(ws, Xdev, Ws, cached):
+        Wd = [dev(w) for w in Ws]
+        logits = torch.empty((g.n, dims[-1]), device="cuda")
+        loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+        dW = [torch.empty_like(w) for w in Wd]
+        gad.gcn_forward(g, Xdev, dims, Wd, yd, md, c, ws, logits, loss, dtype, x_unchanged=cached)
+        gad.gcn_backward(g, Xdev, dims, Wd, ws, dW, None, dtype)
+        torch.cuda.synchronize()
+        return logits, loss.item(), dW
+
+    ws, ws_ref = gad.alloc_workspace(g, dims, dtype), gad.alloc_workspace(g, dims, dtype)
+    run(ws, Xd, Wa, cached=True)                         # fresh workspace: runs the full forward
+    got = run(ws, Xd, Wb, cached=True)                   # second round, new weights: aggregate reused
+    full = run(ws_ref, Xd, Wb, cached=False)
+    assert torch.equal(got[0], full[0]) and got[1] == full[1]
+    assert all(torch.equal(a, b) for a, b in zip(got[2], full[2]))
+    f = T1.forward(ref, X, Wb, y, mask, c)
+    assert rel_err(got[0].cpu().numpy(), f["Z"]) < tol and abs(got[1] - f["loss"]) <= tol * abs(f["loss"])
+    got2 = run(ws, X2d, Wb, cached=True)                 # other features: must not reuse
+    f2 = T1.forward(ref, X2, Wb, y, mask, c)
+    assert rel_err(got2[0].cpu().numpy(), f2["Z"]) < tol
+    assert torch.equal(got2[0], run(ws_ref, X2d, Wb, cached=False)[0])
+    # transform-first first layer (64 -> 16): nothing to reuse, same result as the full forward
+    dims_t = (64, 16, 5)
+    Xt = dev(wl.make_features(cfg.n, 64))
+    Wt = [dev(w) for w in wl.make_weights(dims_t)]
+    yt = dev(wl.make_labels(cfg.n, 5))
+    wst = gad.alloc_workspace(g, dims_t)
+    la, lb = torch.empty((g.n, 5), device="cuda"), torch.empty((g.n, 5), device="cuda")
+    gad.gcn_forward(g, Xt, dims_t, Wt, yt, md, c, wst, la)
+    gad.gcn_forward(g, Xt, dims_t, Wt, yt, md, c, wst, lb, x_unchanged=True)
+    assert torch.equal(la, lb)
+
+
 def test_gcn_errors(gad):
     cfg = wl.CONFIGS["tiny"]
     g, _ = build_both(gad, wl.make_graph(cfg))
