@@ -260,6 +260,9 @@ int gad_weighted_consensus(const float* const* bufs, int K, const double* zeta, 
  *   (grads + k * n_params, same layout), then gad_consensus_update is applied with zeta (host, K doubles) and eta.
  *   X, labels, masks, workspaces: host arrays of K device pointers (masks or masks[k] may be NULL);
  *   loss_scales, workspace_bytes: host arrays of K values; losses: device double[K] or NULL.
+ *   x_unchanged != 0: the caller vouches that every X[k] holds what it held at the last round on workspaces[k];
+ *   the forward passes then run as gad_gcn_forward_cached (the features of Algorithm 2 do not change between
+ *   rounds, so every round after the first can say so).
  *   Nothing is launched if the weights are invalid. */
 int gad_consensus_update(const float* const* grads, int K, const double* zeta, int64_t n_elems, float eta,
                          float* params, float* avg_out, void* hip_stream);
@@ -268,16 +271,17 @@ int gad_consensus_update(const float* const* grads, int K, const double* zeta, i
  * row_scale[i] = c_k * zeta_k / sum_j zeta_j on the rows of block k (c_k = the block's own loss scale), backward
  * into `grad` (float32[n_params], the layout of `params`) -- which is the weighted consensus gradient of Eq. 15 --
  * then params <- params - eta * grad (Eq. 16).  loss (device double[1] or NULL) receives the weighted loss
- * sum_k (zeta_k / sum zeta) loss_k.  Other arguments as gad_gcn_forward / gad_train_round. */
+ * sum_k (zeta_k / sum zeta) loss_k.  Other arguments (x_unchanged included) as gad_gcn_forward / gad_train_round. */
 int gad_train_round_batched(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims, float* params,
                             const int32_t* labels, const uint8_t* mask, const float* row_scale, float negative_slope,
-                            void* workspace, size_t workspace_bytes, float* grad, float eta, double* loss, void* hip_stream);
+                            void* workspace, size_t workspace_bytes, float* grad, float eta, double* loss,
+                            int x_unchanged, void* hip_stream);
 
 int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X, gad_dtype dtype, int L,
                     const int32_t* dims, float* params, const int32_t* const* labels, const uint8_t* const* masks,
                     const float* loss_scales, float negative_slope, void* const* workspaces,
                     const size_t* workspace_bytes, float* grads, const double* zeta, float eta, double* losses,
-                    void* hip_stream);
+                    int x_unchanged, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -568,7 +568,7 @@ int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X,
                     const int32_t* dims, float* params, const int32_t* const* labels, const uint8_t* const* masks,
                     const float* loss_scales, float negative_slope, void* const* workspaces,
                     const size_t* workspace_bytes, float* grads, const double* zeta, float eta, double* losses,
-                    void* hip_stream) {
+                    int x_unchanged, void* hip_stream) {
   if (K < 1 || K > kMaxConsensus) return set_error(GAD_ERR_SHAPE, "K = %d outside [1, %d]", K, kMaxConsensus);
   if (!graphs || !X || !dims || !params || !labels || !loss_scales || !workspaces || !workspace_bytes || !grads || !zeta)
     return set_error(GAD_ERR_NULL, "a required argument is NULL");
@@ -591,8 +591,9 @@ int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X,
   for (int k = 0; k < K; ++k) {
     float* dW[kMaxLayers];
     for (int l = 0; l < L; ++l) dW[l] = grads + (int64_t)k * P + off[l];
-    st = gad_gcn_forward(graphs[k], X[k], dtype, L, dims, W, labels[k], masks ? masks[k] : nullptr, loss_scales[k],
-                         nullptr, negative_slope, workspaces[k], workspace_bytes[k], nullptr, losses ? losses + k : nullptr, hip_stream);
+    st = forward_impl(graphs[k], X[k], dtype, L, dims, W, labels[k], masks ? masks[k] : nullptr, loss_scales[k], nullptr,
+                      negative_slope, workspaces[k], workspace_bytes[k], nullptr, losses ? losses + k : nullptr,
+                      hip_stream, x_unchanged != 0);
     if (st != GAD_OK) return st;
     st = gad_gcn_backward(graphs[k], X[k], dtype, L, dims, W, negative_slope, workspaces[k], workspace_bytes[k], dW,
                           nullptr, hip_stream);
@@ -603,7 +604,8 @@ int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X,
 
 int gad_train_round_batched(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims, float* params,
                             const int32_t* labels, const uint8_t* mask, const float* row_scale, float negative_slope,
-                            void* workspace, size_t workspace_bytes, float* grad, float eta, double* loss, void* hip_stream) {
+                            void* workspace, size_t workspace_bytes, float* grad, float eta, double* loss,
+                            int x_unchanged, void* hip_stream) {
   if (!dims || !params || !grad) return set_error(GAD_ERR_NULL, "dims, params or grad is NULL");
   if (L < 1 || L > kMaxLayers) return set_error(GAD_ERR_SHAPE, "L = %d outside [1, %d]", L, kMaxLayers);
   if (!isfinite(eta)) return set_error(GAD_ERR_SHAPE, "eta is not finite");
@@ -619,8 +621,8 @@ int gad_train_round_batched(const gad_graph* g, const void* X, gad_dtype dtype, 
     W[l] = params + off[l];
     dW[l] = grad + off[l];
   }
-  int st = gad_gcn_forward(g, X, dtype, L, dims, W, labels, mask, 1.f, row_scale, negative_slope, workspace, workspace_bytes,
-                           nullptr, loss, hip_stream);
+  int st = forward_impl(g, X, dtype, L, dims, W, labels, mask, 1.f, row_scale, negative_slope, workspace, workspace_bytes,
+                        nullptr, loss, hip_stream, x_unchanged != 0);
   if (st != GAD_OK) return st;
   st = gad_gcn_backward(g, X, dtype, L, dims, W, negative_slope, workspace, workspace_bytes, dW, nullptr, hip_stream);
   if (st != GAD_OK) return st;

@@ -302,7 +302,8 @@ def consensus_update(grads: List[torch.Tensor], zeta: Sequence[float], eta: floa
 def train_round(graphs: List[Graph], X: List[torch.Tensor], dims: Sequence[int], params: torch.Tensor,
                 labels: List[torch.Tensor], masks: Optional[List[Optional[torch.Tensor]]], loss_scales: Sequence[float],
                 workspaces: List[torch.Tensor], grads: torch.Tensor, zeta: Sequence[float], eta: float,
-                losses: Optional[torch.Tensor] = None, dtype: int = F32, negative_slope: float = 0.0) -> None:
+                losses: Optional[torch.Tensor] = None, dtype: int = F32, negative_slope: float = 0.0,
+                x_unchanged: bool = False) -> None:
     K = len(graphs)
     _dev(params, torch.float32, "params")
     _dev(grads, torch.float32, "grads")
@@ -316,13 +317,13 @@ def train_round(graphs: List[Graph], X: List[torch.Tensor], dims: Sequence[int],
     _check(lib().gad_train_round(C.c_int(K), gh, _ptr_array(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims),
                                  _ptr(params), _ptr_array(labels), mk, ls, C.c_float(negative_slope), _ptr_array(workspaces), wb,
                                  _ptr(grads), z,
-                                 C.c_float(eta), _ptr(losses), _stream()))
+                                 C.c_float(eta), _ptr(losses), C.c_int(1 if x_unchanged else 0), _stream()))
 
 
 def train_round_batched(g: Graph, X: torch.Tensor, dims: Sequence[int], params: torch.Tensor, labels: torch.Tensor,
                         mask: Optional[torch.Tensor], row_scale: torch.Tensor, workspace: torch.Tensor, grad: torch.Tensor,
                         eta: float, loss: Optional[torch.Tensor] = None, dtype: int = F32,
-                        negative_slope: float = 0.0) -> None:
+                        negative_slope: float = 0.0, x_unchanged: bool = False) -> None:
     _dev(params, torch.float32, "params")
     _dev(grad, torch.float32, "grad")
     _dev(row_scale, torch.float32, "row_scale")
@@ -330,4 +331,5 @@ def train_round_batched(g: Graph, X: torch.Tensor, dims: Sequence[int], params: 
     _check(lib().gad_train_round_batched(g.handle, _ptr(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims),
                                          _ptr(params), _ptr(labels), _ptr(mask), _ptr(row_scale),
                                          C.c_float(negative_slope), _ptr(workspace), C.c_size_t(workspace.numel()),
-                                         _ptr(grad), C.c_float(eta), _ptr(loss), _stream()))
+                                         _ptr(grad), C.c_float(eta), _ptr(loss), C.c_int(1 if x_unchanged else 0),
+                                         _stream()))

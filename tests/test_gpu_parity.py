@@ -618,7 +618,8 @@ def test_train_rounds_match_oracle(gad):
     W_ref = [w.astype(np.float64) for w in Ws]
     tots = []
     for r in range(rounds):
-        gad.train_round(graphs, Xd, dims, params, yd, md, cs, wss, grads, zeta, eta, losses)
+        # the features do not change between rounds: from the second round on the first aggregates are reused
+        gad.train_round(graphs, Xd, dims, params, yd, md, cs, wss, grads, zeta, eta, losses, x_unchanged=r > 0)
         W_ref, l_ref, _ = T1.train_round(refs, Xs, W_ref, ys, ms, cs, zeta, eta)
         got = losses.cpu().numpy()
         assert np.all(np.abs(got - l_ref) <= 2e-4 * np.abs(l_ref)), f"round {r}"
@@ -678,7 +679,7 @@ def test_batched_round_on_union_matches_looped_round_and_oracle(gad):
     Xud, yud, mud, rsd = dev(Xu), dev(yu), dev(mu), dev(row_scale)
     W_ref = [w_.astype(np.float64) for w_ in Ws]
     for r in range(rounds):
-        gad.train_round_batched(U, Xud, dims, params_b, yud, mud, rsd, ws_u, grad_b, eta, loss_b)
+        gad.train_round_batched(U, Xud, dims, params_b, yud, mud, rsd, ws_u, grad_b, eta, loss_b, x_unchanged=r > 0)
         gad.train_round(graphs, Xd, dims, params_l, yd, md, cs, wss, grads_l, zeta, eta, losses_l)
         W_ref, l_ref, g_ref = T1.train_round(refs, Xs, W_ref, ys, ms, cs, zeta, eta)
         assert abs(loss_b.item() - float(np.dot(w, l_ref))) <= 2e-4 * abs(float(np.dot(w, l_ref))), f"round {r}"
