@@ -21,7 +21,7 @@ from typing import Dict, Tuple
 import numpy as np
 
 _TAGS = {"edges": 1, "perm": 2, "extra": 3, "features": 4, "weights": 5,
-         "labels": 6, "copies": 7, "orient": 8, "zeta": 9}
+         "labels": 6, "copies": 7, "orient": 8, "zeta": 9, "rows": 10}
 
 
 def _rng(seed: int, tag: str, sub: int = 0) -> np.random.Generator:
@@ -47,6 +47,7 @@ class Workload:
     global_factor: int = 1          # id space = global_factor * n  (2 => half the ids are outside g')
     extra_edge_frac: float = 0.0    # fraction of extra edges with an endpoint outside g'
     consensus_k: int = 0            # >0: weighted consensus over K parameter copies
+    shuffle_rows: bool = True       # rows of the subgraph in a seeded random order of the generator's node numbers
 
     @property
     def n(self) -> int:
@@ -144,8 +145,11 @@ def make_graph(cfg: Workload, seed: int = 0) -> dict:
     """Raw input of the CSR build: directed endpoint pairs in *global* ids plus the id lists.
 
     Returns dict(src, dst [int64, E_in], n_global, local_ids [int64], halo_ids [int64]).
-    Node k of the subgraph (0 <= k < n) is global id ``perm[k]``; the first n_local of them are
-    the local nodes, the next n_halo the replicated (halo) nodes, in that order.
+    Generator node u (0 <= u < n) is global id ``perm[u]``.  Row k of the subgraph is generator node ``order[k]``,
+    a seeded shuffle: the generators number their nodes in a structured way (Chung-Lu: by falling expected degree;
+    R-MAT: by bit pattern), and a real partition has no such row order.  The first n_local rows are the local nodes,
+    the next n_halo the replicated (halo) nodes -- a random subset, listed after the locals.
+    ``shuffle_rows=False`` keeps row k = generator node k (rows sorted by expected degree for Chung-Lu).
     """
     n = cfg.n
     if cfg.graph == "er":
@@ -179,9 +183,10 @@ def make_graph(cfg: Workload, seed: int = 0) -> dict:
         order = rng.permutation(len(src))
         src = src[order]
         dst = dst[order]
+    order = _rng(seed, "rows").permutation(n) if cfg.shuffle_rows else np.arange(n)
     return dict(src=np.ascontiguousarray(src), dst=np.ascontiguousarray(dst), n_global=int(n_global),
-                local_ids=np.ascontiguousarray(perm[: cfg.n_local]),
-                halo_ids=np.ascontiguousarray(perm[cfg.n_local: n]))
+                local_ids=np.ascontiguousarray(perm[order[: cfg.n_local]]),
+                halo_ids=np.ascontiguousarray(perm[order[cfg.n_local: n]]))
 
 
 # --------------------------------------------------------------------------------------
