@@ -17,7 +17,8 @@ Readings taken where the paper is silent or garbled:
   sigma_x and xbar are read as the population standard deviation and the mean of I(v) over the candidates the
   first batch has visited; with counts c_v, m visited candidates, S1 = sum c, S2 = sum c^2 this is
   n = ceil((z_c / E)^2 (m S2 - S1^2) / S1^2), z_c = 1.96, E = 0.05.  The total is max(first batch, n), capped by
-  the caller.
+  the caller.  n is an integer decided by a real number: it is evaluated exactly, (z_c / E)^2 = 38416 / 25 as a
+  rational and the ceiling of an integer quotient, so that no rounding of an intermediate can move it.
 * The score of a walk is the sum of I(v) over its l steps (positions outside the partition; a node met twice
   adds twice).  Walks are taken in descending score, ties by walk number; their nodes are added in step order
   until the budget is reached (Algorithm 1, the repeat loop), so every added node hangs on the partition through
@@ -26,7 +27,7 @@ Readings taken where the paper is silent or garbled:
 """
 from __future__ import annotations
 
-import math
+from fractions import Fraction
 
 import numpy as np
 
@@ -81,8 +82,9 @@ def mc_walk_count(counts) -> int:
     if len(c) == 0:
         return 0
     m, s1, s2 = len(c), int(sum(c)), int(sum(x * x for x in c))
-    q = Z_C / E_MC
-    return int(math.ceil(q * q * float(m * s2 - s1 * s1) / float(s1 * s1)))
+    q2 = (Fraction(str(Z_C)) / Fraction(str(E_MC))) ** 2               # 38416 / 25, exactly
+    n = q2 * (m * s2 - s1 * s1) / (s1 * s1)                            # exact rational
+    return -((-n.numerator) // n.denominator)                          # its ceiling
 
 
 def augment(rowptr, colidx, part, l, budget, seed, max_walks=1 << 22):

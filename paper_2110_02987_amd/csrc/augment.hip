@@ -247,13 +247,15 @@ struct Scratch {
 
 inline unsigned blocks(int64_t n) { return (unsigned)ceil_div(n > 0 ? n : 1, 256); }
 
-// Eq. 4 solved for n at E = 0.05, z_c = 1.96:  n = ceil((z_c / E)^2 (m S2 - S1^2) / S1^2).
+// Eq. 4 solved for n at E = 0.05, z_c = 1.96:  n = ceil((z_c / E)^2 (m S2 - S1^2) / S1^2), evaluated exactly:
+// (z_c / E)^2 = 38416 / 25, and the ceiling is that of an integer quotient.  S1 <= walks * steps <= 2^30,
+// S2 <= S1 * walks <= 2^56 and m <= S1, so 38416 * m * S2 stays below 2^102.
 int64_t walk_count(unsigned long long m, unsigned long long s1, unsigned long long s2) {
   if (m == 0 || s1 == 0) return 0;
   const unsigned __int128 num = (unsigned __int128)m * s2 - (unsigned __int128)s1 * s1;     // >= 0 (Cauchy-Schwarz)
   const unsigned __int128 den = (unsigned __int128)s1 * s1;
-  const double q = 1.96 / 0.05;
-  return (int64_t)ceil(q * q * (double)num / (double)den);
+  const unsigned __int128 a = 38416u * num, b = 25u * den;
+  return (int64_t)((a + b - 1) / b);
 }
 
 }  // namespace
