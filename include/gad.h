@@ -219,6 +219,18 @@ int gad_gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, float* C
 int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta,
                           double* out3, float* per_node_out, void* hip_stream);
 
+/* gad_subgraph_variance for callers that cannot allocate device memory or tolerate a library that does (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same results,
+ * but the reduction buffer is a fixed array inside the library (4.8 MB of device memory on every GPU the library
+ * runs on, held until the process ends) instead of memory owned by the graph.  The call allocates and frees
+ * nothing.  Limits: F <= 1024 and n <= 8,388,608 (GAD_ERR_SHAPE beyond them, nothing launched).  The current device
+ * must be the graph's (GAD_ERR_STATE).  All calls on one GPU share the one array: calls that overlap on a GPU
+ * (different streams or threads) race; calls on one stream are ordered.  Nothing in the array has to start at
+ * zero: every word a kernel reads is written earlier in the same call.  The first call on a device looks up the
+ * array's device address; make that call outside a stream capture. */
+int gad_subgraph_variance_static(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta,
+                                 double* out3, float* per_node_out, void* hip_stream);
+
 /* Eq. 14 read with the distance inside the sum (the formula as printed sums only its numerator and leaves i, j
  * free in the denominator; with identical node vectors, as in the paper's worked example, both readings agree):
  *

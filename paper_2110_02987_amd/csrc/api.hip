@@ -506,6 +506,15 @@ int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtyp
   return subgraph_variance(g, V, F, dtype, beta, out3, per_node_out, static_cast<hipStream_t>(hip_stream));
 }
 
+int gad_subgraph_variance_static(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta, double* out3,
+                                 float* per_node_out, void* hip_stream) {
+  if (!g || !V || !out3) return set_error(GAD_ERR_NULL, "graph, V or out3 is NULL");
+  if (F < 1) return set_error(GAD_ERR_SHAPE, "F = %d must be positive", F);
+  if (!(beta > 0.0) || !isfinite(beta)) return set_error(GAD_ERR_SHAPE, "beta must be positive and finite");
+  if (dtype != GAD_F32 && dtype != GAD_BF16) return set_error(GAD_ERR_UNSUPPORTED, "unknown dtype");
+  return subgraph_variance_static(g, V, F, dtype, beta, out3, per_node_out, static_cast<hipStream_t>(hip_stream));
+}
+
 int gad_pair_importance_workspace_bytes(const gad_graph* g, int32_t F, size_t* bytes) {
   if (!g || !bytes) return set_error(GAD_ERR_NULL, "graph or bytes is NULL");
   if (F < 1 || F > kMaxWidth) return set_error(GAD_ERR_SHAPE, "F = %d outside [1, %d]", F, kMaxWidth);

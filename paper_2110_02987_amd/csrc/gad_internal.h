@@ -60,6 +60,8 @@ constexpr int kMaxWidth = 4096;      // widest feature / hidden dimension accept
 constexpr int kMaxLayers = 16;
 constexpr int kMaxConsensus = 128;   // most buffers one consensus call averages
 constexpr int kVarBlocks = 512;      // row slabs of the column-sum pass of the variance reduction
+constexpr int kStaticVarMaxF = 1024;            // limits of the variance call that keeps its reduction buffer in a
+constexpr int64_t kStaticVarMaxN = 1ll << 23;   // file-scope device array (gad_subgraph_variance_static)
 
 }  // namespace gad
 
@@ -146,6 +148,9 @@ int pair_importance(const gad_graph* g, const void* V, int F, gad_dtype dtype, d
                     hipStream_t s);
 int subgraph_variance(const gad_graph* g, const void* V, int F, gad_dtype dtype, double beta, double* out3,
                       float* per_node, hipStream_t s);
+// The same reduction with its buffer in a file-scope device array: allocates nothing; F <= kStaticVarMaxF, n <= kStaticVarMaxN.
+int subgraph_variance_static(const gad_graph* g, const void* V, int F, gad_dtype dtype, double beta, double* out3,
+                             float* per_node, hipStream_t s);
 int weighted_consensus(const float* const* bufs, int K, const double* w, int64_t n, float* out, hipStream_t s);
 int consensus_update(const float* const* bufs, int K, const double* w, int64_t n, float eta, float* params,
                      float* avg_out, hipStream_t s);

@@ -9,6 +9,8 @@
 // results are reproducible from run to run; the degree sums are exact 64-bit integer sums.
 #include <math.h>
 
+#include <mutex>
+
 #include "gad_internal.h"
 
 namespace gad {
@@ -199,11 +201,14 @@ __global__ __launch_bounds__(256) void consensus_update_kernel(ConsensusArgs a, 
   params[e] = (float)((double)params[e] - (double)eta * s);
 }
 
+// `red`: reduction buffer of at least kVarBlocks * F + F + 3 * ceil(n / kDevRows) 8-byte words.  Every word that a
+// kernel reads is written by an earlier kernel of the same call, so the buffer needs no clearing between calls.
 template <typename T>
-int variance_t(const gad_graph* g, const T* V, int F, double beta, double* out3, float* per_node, hipStream_t s) {
+int variance_t(const gad_graph* g, const T* V, int F, double beta, double* out3, float* per_node, double* red,
+               hipStream_t s) {
   const int64_t n = g->n;
   // scratch layout (8-byte words): part[kVarBlocks x F] | mean[F] | block_r[nb] | block_d1[nb] | block_d2[nb], nb = ceil(n / kDevRows)
-  double* part = g->red_scratch;
+  double* part = red;
   double* mean = part + (int64_t)kVarBlocks * F;
   double* block_r = mean + F;
   const int64_t r_blocks = ceil_div(n, kDevRows);
@@ -245,8 +250,46 @@ size_t variance_scratch_doubles(int64_t n) {
 
 int subgraph_variance(const gad_graph* g, const void* V, int F, gad_dtype dtype, double beta, double* out3,
                       float* per_node, hipStream_t s) {
-  if (dtype == GAD_F32) return variance_t<float>(g, static_cast<const float*>(V), F, beta, out3, per_node, s);
-  return variance_t<uint16_t>(g, static_cast<const uint16_t*>(V), F, beta, out3, per_node, s);
+  double* red = g->red_scratch;
+  if (dtype == GAD_F32) return variance_t<float>(g, static_cast<const float*>(V), F, beta, out3, per_node, red, s);
+  return variance_t<uint16_t>(g, static_cast<const uint16_t*>(V), F, beta, out3, per_node, red, s);
+}
+
+// ---- the same reduction for callers that cannot allocate -----------------------------------------------------
+// The reduction buffer is a file-scope device array instead of memory of the graph.  Each device that loads the
+// library holds its own copy of the array until the process ends; the array's name is only a host-side stand-in, so
+// its device address is looked up once per device (with that device current) and every launch takes that address.
+namespace {
+constexpr size_t kStaticDoubles = (size_t)kVarBlocks * kStaticVarMaxF + kStaticVarMaxF +
+                                  3 * (size_t)(kStaticVarMaxN / kDevRows) + 4;     // 4.8 MB
+static __device__ __align__(256) double scratch[kStaticDoubles];
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+double* g_static_ptr[kMaxDevices] = {};     // device address of `scratch` on each device, null until first use there
+}  // namespace
+
+int subgraph_variance_static(const gad_graph* g, const void* V, int F, gad_dtype dtype, double beta, double* out3,
+                             float* per_node, hipStream_t s) {
+  if (F > kStaticVarMaxF || g->n > kStaticVarMaxN)
+    return set_error(GAD_ERR_SHAPE, "F = %d or n = %lld beyond what the static reduction buffer holds (F <= %d, n <= %lld)",
+                     F, (long long)g->n, kStaticVarMaxF, (long long)kStaticVarMaxN);
+  int dev = 0;
+  GAD_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return set_error(GAD_ERR_UNSUPPORTED, "device ordinal %d out of range", dev);
+  if (dev != g->device) return set_error(GAD_ERR_STATE, "the graph lives on device %d, the current device is %d", g->device, dev);
+  double* red = nullptr;
+  {
+    std::lock_guard<std::mutex> lk(g_static_mu);
+    if (!g_static_ptr[dev]) {
+      void* p = nullptr;
+      GAD_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+      if (!p) return set_error(GAD_ERR_HIP, "the static reduction buffer has no address on device %d", dev);
+      g_static_ptr[dev] = static_cast<double*>(p);
+    }
+    red = g_static_ptr[dev];
+  }
+  if (dtype == GAD_F32) return variance_t<float>(g, static_cast<const float*>(V), F, beta, out3, per_node, red, s);
+  return variance_t<uint16_t>(g, static_cast<const uint16_t*>(V), F, beta, out3, per_node, red, s);
 }
 
 int weighted_consensus(const float* const* bufs, int K, const double* w, int64_t n, float* out, hipStream_t s) {

@@ -19,7 +19,7 @@ F32, BF16 = 0, 1
 SYMBOLS = ["gad_last_error", "gad_build_subgraph", "gad_graph_info", "gad_graph_destroy", "gad_graph_concat", "gad_augment_subgraph",
            "gad_gcn_workspace_bytes", "gad_gcn_forward", "gad_gcn_forward_cached", "gad_gcn_backward", "gad_gcn_activation", "gad_spmm_workspace_bytes", "gad_spmm",
            "gad_gemm_workspace_bytes", "gad_gemm_w", "gad_gemm_tn",
-           "gad_subgraph_variance", "gad_pair_importance_workspace_bytes", "gad_pair_importance",
+           "gad_subgraph_variance", "gad_subgraph_variance_static", "gad_pair_importance_workspace_bytes", "gad_pair_importance",
            "gad_weighted_consensus", "gad_consensus_update", "gad_train_round", "gad_train_round_batched"]
 
 _lib = None
@@ -265,6 +265,16 @@ def subgraph_variance(g: Graph, V: torch.Tensor, beta: float, out3: torch.Tensor
     _dev(out3, torch.float64, "out3")
     _check(lib().gad_subgraph_variance(g.handle, _ptr(V), C.c_int32(V.shape[1]), C.c_int(dtype), C.c_double(beta),
                                        _ptr(out3), _ptr(per_node_out), _stream()))
+
+
+def subgraph_variance_static(g: Graph, V: torch.Tensor, beta: float, out3: torch.Tensor,
+                             per_node_out: Optional[torch.Tensor] = None) -> None:
+    """subgraph_variance with the reduction buffer in the library's fixed device array (allocates nothing)."""
+    dtype = F32 if V.dtype == torch.float32 else BF16
+    _dev(V, torch.float32 if dtype == F32 else torch.bfloat16, "V")
+    _dev(out3, torch.float64, "out3")
+    _check(lib().gad_subgraph_variance_static(g.handle, _ptr(V), C.c_int32(V.shape[1]), C.c_int(dtype),
+                                              C.c_double(beta), _ptr(out3), _ptr(per_node_out), _stream()))
 
 
 def pair_importance(g: Graph, V: torch.Tensor, beta: float, out2: torch.Tensor,
