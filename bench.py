@@ -22,6 +22,28 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
 
 
+class HipEvents:
+    """HIP events made through the runtime itself (hipEventCreate): their handles can be handed to the library,
+    which records them on the stream it launches on."""
+
+    def __init__(self, count):
+        import ctypes as C
+        self.C, self.hip = C, C.CDLL("libamdhip64.so")
+        self.ev = []
+        for _ in range(count):
+            e = C.c_void_p()
+            assert self.hip.hipEventCreate(C.byref(e)) == 0
+            self.ev.append(e)
+
+    def handles(self):
+        return [e.value for e in self.ev]
+
+    def ms(self, i, j):
+        t = self.C.c_float()
+        assert self.hip.hipEventElapsedTime(self.C.byref(t), self.ev[i], self.ev[j]) == 0
+        return float(t.value)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -30,6 +52,9 @@ def main() -> int:
     ap.add_argument("--workload", default="products_part")
     ap.add_argument("--storage", choices=["f32", "bf16"], default=None,
                     help="storage type of features / activations (default: the workload's own)")
+    ap.add_argument("--generator-row-order", action="store_true",
+                    help="variant: rows in the generator's node order (Chung-Lu: sorted by expected degree) instead of "
+                         "the seeded shuffle")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=20, help="standalone launches of the dominant kernel")
     ap.add_argument("--kernels-only", action="store_true",
@@ -51,6 +76,10 @@ def main() -> int:
         import dataclasses
         cfg = dataclasses.replace(cfg, dtype=args.storage)
         variant = f" [{args.storage} storage variant]"
+    if args.generator_row_order:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, shuffle_rows=False)
+        variant += " [rows in generator order]"
     dims, L = list(cfg.dims), cfg.n_layers
     torch.cuda.set_device(0)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -126,10 +155,11 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in rec]))
-    bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in rec]))
-    tail_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in rec]))
-    epoch_ms = fwd_ms + bwd_ms
+    med = lambda xs: float(np.median(xs))
+    fwd_ms = med([e[0].elapsed_time(e[1]) for e in rec])
+    bwd_ms = med([e[1].elapsed_time(e[2]) for e in rec])
+    tail_ms = med([e[2].elapsed_time(e[3]) for e in rec])
+    epoch_ms = med([e[0].elapsed_time(e[2]) for e in rec])
     value = L * g.nnz / (epoch_ms * 1e-3)
     # The same step when the caller vouches that X has not changed (static features): the first layer's aggregate
     # A~ X is then reused.  Reported beside the figures above, never in `value`.
@@ -139,7 +169,32 @@ def main() -> int:
         for _ in range(args.steps):
             step(rec_c, x_unchanged=True)
         torch.cuda.synchronize()
-        cached_epoch_ms = float(np.mean([e[0].elapsed_time(e[2]) for e in rec_c]))
+        cached_epoch_ms = med([e[0].elapsed_time(e[2]) for e in rec_c])
+
+    # ---- per layer: the library records events at the layer boundaries of both passes (its own stream).  The
+    # instrumented backward waits for each layer's weight gradient before the next layer starts, so the layers add
+    # up to a little more than the plain backward above.  edges/s of a layer = nnz / (its forward + its backward).
+    per_layer = None
+    if not args.kernels_only:
+        hev = HipEvents(2 * L + 3)
+        gad.gcn_layer_events(hev.handles())
+        f_l, b_l, loss_l = [[] for _ in range(L)], [[] for _ in range(L)], []
+        for _ in range(args.steps):
+            step()
+            torch.cuda.synchronize()
+            for l in range(L):
+                f_l[l].append(hev.ms(l, l + 1))
+                b_l[l].append(hev.ms(L + 2 + (L - 1 - l), L + 3 + (L - 1 - l)))
+            loss_l.append(hev.ms(L, L + 1))
+        gad.gcn_layer_events([])
+        per_layer = []
+        for l in range(L):
+            fm, bm = med(f_l[l]), med(b_l[l])
+            per_layer.append(dict(layer=l + 1, dims=f"{dims[l]}x{dims[l + 1]}",
+                                  order="aggregate-first" if dims[l] <= dims[l + 1] else "transform-first",
+                                  spmm_width=min(dims[l], dims[l + 1]), forward_ms=fm, backward_ms=bm,
+                                  edges_per_s=g.nnz / ((fm + bm) * 1e-3)))
+        per_layer.append(dict(layer="loss", forward_ms=med(loss_l)))
 
     # ---- dominant kernel: the SpMM at each width the step uses, timed alone with events on the launch stream
     widths = []
@@ -148,6 +203,22 @@ def main() -> int:
         widths.append(w)                                   # forward
         if not (l == 0 and dims[l] <= dims[l + 1]):
             widths.append(w)                               # backward (layer 1 needs none when it aggregates first)
+    # the attainable ceiling of a plain device copy on this machine, in the same run: 1 GiB read + 1 GiB written
+    a_ = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    b_ = torch.empty_like(a_)
+    for _ in range(3):
+        b_.copy_(a_)
+    cp = []
+    for _ in range(10):
+        e0, e1 = ev(), ev()
+        e0.record()
+        b_.copy_(a_)
+        e1.record()
+        torch.cuda.synchronize()
+        cp.append(e0.elapsed_time(e1))
+    copy_ceiling = 2.0 * a_.numel() * 4 / med(cp) * 1e-6          # GB/s
+    del a_, b_
+
     spmm = {}
     for w in sorted(set(widths)):
         ld = (w + 15) // 16 * 16
@@ -156,13 +227,15 @@ def main() -> int:
         sws = gad.spmm_workspace(g, w)
         for _ in range(3):
             gad.spmm(g, T, O, w, dt, sws)
-        a, b = ev(), ev()
-        a.record()
+        times = []
         for _ in range(args.kernel_reps):
+            a, b = ev(), ev()
+            a.record()
             gad.spmm(g, T, O, w, dt, sws)
-        b.record()
+            b.record()
+            times.append((a, b))
         torch.cuda.synchronize()
-        ms = a.elapsed_time(b) / args.kernel_reps
+        ms = med([a.elapsed_time(b) for a, b in times])
         compulsory = 4 * g.nnz + 12 * g.n + 2 * g.n * w * esz
         gather = g.nnz * (4 + w * esz) + g.n * (12 + w * esz)
         spmm[w] = dict(ms=ms, launches_per_step=widths.count(w), edges_per_s=g.nnz / (ms * 1e-3),
@@ -170,30 +243,47 @@ def main() -> int:
                        compulsory_bytes=compulsory, gather_model_bytes=gather)
         del T, O, sws
     dom = max(spmm, key=lambda w: spmm[w]["ms"] * spmm[w]["launches_per_step"])
-    # Algorithmic bytes = per-edge and per-row figures of the gather model (4 B index + one w-wide row per edge;
-    # rowptr + dinv + one written row per node) x the edges and rows of one launch.  The compulsory model (every
-    # array touched once) is reported beside it: the gap between the two is what caches can save.
+    d = spmm[dom]
+    # Roofline of the dominant kernel against the 8 TB/s HBM peak.  `achieved` = bytes that cross from L2 to the
+    # memory side per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a plain
+    # 1 GiB copy) / the launch time measured here.  The counters cannot be read from inside this process: they come
+    # from the committed summary under profiles/, which names the commit and the command it was taken with.  The
+    # counter sits in front of the Infinity Cache, so this is an upper bound of the DRAM rate.  Beside it, the two
+    # byte models of the method: gather (4 B index + one w-wide row per edge; rowptr + dinv + one written row per
+    # node: what moves if no gathered row is reused from a cache; it can exceed the peak because L2 serves part of
+    # it) and compulsory (every array once: the least HBM could move).
     roofline = dict(bound="hbm", kernel=f"spmm_kernel (A~ T at width {dom}, {cfg.dtype} storage)",
-                    achieved=spmm[dom]["gather_model_GBps"], peak=HBM_PEAK_GBPS, unit="GB/s",
-                    frac=spmm[dom]["gather_model_GBps"] / HBM_PEAK_GBPS, traffic=None,
-                    avg_launch_ms=spmm[dom]["ms"],
-                    model=f"gather: nnz*(4 + {esz}w) + n*(12 + {esz}w) bytes per launch",
-                    algorithmic_bytes=spmm[dom]["gather_model_bytes"],
-                    compulsory_bytes=spmm[dom]["compulsory_bytes"], compulsory_GBps=spmm[dom]["compulsory_GBps"],
-                    compulsory_frac=spmm[dom]["compulsory_GBps"] / HBM_PEAK_GBPS)
-    # HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE in KiB, each scaled by
-    # what the same counter reads for a plain 1 GiB copy); None when no summary covers this workload.
+                    achieved=None, peak=HBM_PEAK_GBPS, unit="GB/s", frac=None, traffic=None, traffic_source=None,
+                    avg_launch_ms=d["ms"],
+                    gather_model=dict(bytes=d["gather_model_bytes"], GBps=d["gather_model_GBps"],
+                                      formula=f"nnz*(4 + {esz}w) + n*(12 + {esz}w)"),
+                    compulsory_model=dict(bytes=d["compulsory_bytes"], GBps=d["compulsory_GBps"],
+                                          frac_of_peak=d["compulsory_GBps"] / HBM_PEAK_GBPS,
+                                          formula=f"4 nnz + 12 n + 2 n w {esz}"),
+                    time_over_compulsory=d["ms"] / (d["compulsory_bytes"] / HBM_PEAK_GBPS * 1e-6),
+                    copy_ceiling_GBps=copy_ceiling)
     tr = os.path.join(ROOT, "profiles", f"spmm_{cfg.name}_hbm_traffic.txt")
-    if os.path.exists(tr) and not variant:                  # the committed counters are those of the workload's own type
+    if os.path.exists(tr) and not variant:                  # the committed counters are those of the workload as named
+        stamp = ""
         for line in open(tr):
+            if line.startswith("# taken at commit"):
+                stamp = line[1:].strip()
             if line.startswith("traffic "):
                 kv = dict(t.split("=") for t in line.split()[1:])
                 if int(kv["width"]) == dom:
                     nbytes = 1024.0 * (float(kv["fetch_kib"]) * float(kv["fetch_scale"]) +
                                        float(kv["write_kib"]) * float(kv["write_scale"]))
                     roofline["traffic"] = nbytes
-                    roofline["traffic_GBps"] = nbytes / spmm[dom]["ms"] * 1e-6
-                    roofline["traffic_frac_of_peak"] = roofline["traffic_GBps"] / HBM_PEAK_GBPS
+                    roofline["traffic_source"] = f"profiles/{os.path.basename(tr)} ({stamp})"
+                    roofline["traffic_launch_ms_in_profile"] = float(kv.get("avg_dur_us", "nan")) * 1e-3
+                    roofline["achieved"] = nbytes / d["ms"] * 1e-6
+                    roofline["traffic_over_gather_model"] = nbytes / d["gather_model_bytes"]
+                    roofline["traffic_over_compulsory"] = nbytes / d["compulsory_bytes"]
+    if roofline["achieved"] is None:                         # no counter summary for this workload / variant:
+        roofline["achieved"] = d["compulsory_GBps"]          # the strict lower bound of the HBM rate stands in
+        roofline["achieved_is"] = "compulsory-model bytes / time (lower bound; no counter summary for this workload)"
+    roofline["frac"] = roofline["achieved"] / HBM_PEAK_GBPS
+    roofline["frac_of_copy_ceiling"] = roofline["achieved"] / copy_ceiling
 
     # ---- the dense contractions of each layer, timed alone (MFMA kernels): H W forward and the weight gradient
     mfma_peak = 2500.0 if bf16 else 157.3                  # published dense TFLOP/s of the instruction's type
@@ -259,7 +349,7 @@ def main() -> int:
                            n=g.n, nnz=g.nnz, dims=dims),
                epoch_ms=epoch_ms, forward_ms=fwd_ms, backward_ms=bwd_ms, variance_consensus_ms=tail_ms,
                epoch_ms_first_aggregate_reused=cached_epoch_ms,
-               build_ms=build_ms, spmm={str(k): v for k, v in spmm.items()}, gemm=gemm, extras=extras,
+               per_layer=per_layer, build_ms=build_ms, spmm={str(k): v for k, v in spmm.items()}, gemm=gemm, extras=extras,
                mfma_peak_TFLOPs=mfma_peak, roofline=roofline)
 
     # ---- the oracle, as it stands, on the host cores (reported baseline, not a target)

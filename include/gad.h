@@ -150,9 +150,23 @@ int gad_augment_subgraph(const gad_graph* G, const int64_t* part_rows, int64_t n
  *              gad_subgraph_variance).
  *
  * gad_gcn_backward must follow a gad_gcn_forward on the same graph, workspace, L, dims, dtype and negative_slope
- * (else GAD_ERR_STATE); X and W must still hold the values the forward saw.  Rows whose label is
- * outside [0, F_L) contribute nothing (treated as masked). */
+ * (else GAD_ERR_STATE); X and W must still hold the values the forward saw.  One backward per forward: the backward
+ * overwrites the forward's seed gradient, so a second backward on the same forward returns GAD_ERR_STATE (the saved
+ * activations stay readable through gad_gcn_activation, and the first layer's aggregate stays reusable by
+ * gad_gcn_forward_cached).  Rows whose label is outside [0, F_L) contribute nothing (treated as masked).
+ *
+ * Which forward a workspace holds is kept on the host, keyed by the workspace address; the record is dropped when a
+ * forward starts on that address (a forward that fails leaves none), when its graph is destroyed, and by
+ * gad_workspace_forget.  The library cannot see a workspace being freed: before the memory of a workspace is freed
+ * or used for anything else, call gad_workspace_forget on it -- otherwise a later buffer at the same address would be
+ * taken to hold that forward (gad_gcn_backward and gad_gcn_activation would accept it, gad_gcn_forward_cached would
+ * reuse an aggregate that is not there).  At most 1024 workspaces are remembered; the oldest record is dropped
+ * beyond that. */
 int gad_gcn_workspace_bytes(const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, size_t* bytes);
+
+/* Drops what the library remembers about the forward held by `workspace` (host call, nothing is launched).
+ * GAD_OK whether or not anything was remembered. */
+int gad_workspace_forget(const void* workspace);
 
 int gad_gcn_forward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
                     const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
@@ -172,6 +186,18 @@ int gad_gcn_forward_cached(const gad_graph* g, const void* X, gad_dtype dtype, i
 int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
                      const float* const* W, float negative_slope, void* workspace, size_t workspace_bytes,
                      float* const* dW, float* const* G_out, void* hip_stream);
+
+/* Measurement aid: per-layer timing of the two passes (the per-layer edge rate of a layer is nnz over its forward
+ * plus its backward time).  events: host array of `count` hipEvent_t created by the caller with timing enabled;
+ * the setting belongs to the calling host thread; count = 0 switches it off.  While count >= 2 L + 3, a forward or
+ * backward pass of an L-layer model on this thread records, on its stream,
+ *   events[0] before its first kernel, events[l] after the last kernel of layer l (1 <= l <= L), events[L + 1] after
+ *   the loss and seed gradient (forward);
+ *   events[L + 2] before the first kernel of the backward, events[L + 3 + k] after layer L - k is done (0 <= k < L;
+ *   the weight-gradient product that otherwise runs beside the next layer's kernels is waited for first, so the
+ *   instrumented backward can take a little longer than the plain one).
+ * Do not use while the stream is being captured into a HIP graph. */
+int gad_gcn_layer_events(void* const* events, int count);
 
 /* Copies a saved activation of the last forward on `workspace` into out (float32 [n x dims[layer]], ld
  * dims[layer]):  layer in [1, L-1] gives H_layer = sigma(P_layer), layer = L gives the logits Z.

@@ -89,6 +89,11 @@ int make_plan(const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, P
 }
 
 // Which forward a workspace currently holds (host-side bookkeeping; the workspace itself is device memory).
+// An entry is erased when a forward starts on the workspace and written when its last launch has been enqueued, so
+// a forward that fails half way leaves no entry behind.  A backward overwrites the seed gradient of the forward
+// (and, for deeper models, the gradient buffers it swaps): it marks the entry, and a second backward is refused.
+// The library cannot see a workspace being freed: gad_workspace_forget erases the entry, and the table holds at most
+// kMaxSaved entries (the least recently written one is dropped beyond that).
 struct Saved {
   const gad_graph* g;
   int L;
@@ -96,9 +101,30 @@ struct Saved {
   gad_dtype dtype;
   const void* X;
   float slope;
+  bool grads_consumed;     // a backward has run on this forward
+  uint64_t tick;           // order of insertion
 };
+constexpr size_t kMaxSaved = 1024;
 std::mutex g_saved_mu;
 std::unordered_map<const void*, Saved> g_saved;
+uint64_t g_saved_tick = 0;
+
+void forget_workspace(const void* ws) {
+  std::lock_guard<std::mutex> lk(g_saved_mu);
+  g_saved.erase(ws);
+}
+
+void remember_forward(const void* ws, const gad_graph* g, int L, const int32_t* dims, gad_dtype dtype, const void* X,
+                      float slope) {
+  std::lock_guard<std::mutex> lk(g_saved_mu);
+  if (g_saved.size() >= kMaxSaved && g_saved.find(ws) == g_saved.end()) {
+    auto oldest = g_saved.begin();
+    for (auto it = g_saved.begin(); it != g_saved.end(); ++it)
+      if (it->second.tick < oldest->second.tick) oldest = it;
+    g_saved.erase(oldest);
+  }
+  g_saved[ws] = Saved{g, L, std::vector<int32_t>(dims, dims + L + 1), dtype, X, slope, false, ++g_saved_tick};
+}
 
 int check_common(const gad_graph* g, const void* X, int L, const int32_t* dims, const float* const* W, void* ws,
                  size_t ws_bytes, const Plan& p) {
@@ -114,19 +140,33 @@ int check_common(const gad_graph* g, const void* X, int L, const int32_t* dims, 
   return GAD_OK;
 }
 
-// True iff `ws` holds a forward of exactly this problem (X = nullptr: any features).
+// True iff `ws` holds a forward of exactly this problem (X = nullptr: any features).  for_backward: the forward's
+// gradients must still be there; on success they are marked as consumed.
 bool forward_saved(const gad_graph* g, const void* ws, int L, const int32_t* dims, gad_dtype dtype, const void* X,
-                   const float* slope = nullptr) {
+                   const float* slope = nullptr, bool for_backward = false, bool* consumed = nullptr) {
   std::lock_guard<std::mutex> lk(g_saved_mu);
   auto it = g_saved.find(ws);
   bool ok = it != g_saved.end() && it->second.g == g && it->second.L == L && it->second.dtype == dtype &&
             (X == nullptr || it->second.X == X) && (slope == nullptr || it->second.slope == *slope);
   if (ok)
     for (int l = 0; l <= L; ++l) ok = ok && it->second.dims[l] == dims[l];
+  if (ok && for_backward) {
+    if (it->second.grads_consumed) {
+      if (consumed) *consumed = true;
+      return false;
+    }
+    it->second.grads_consumed = true;
+  }
   return ok;
 }
 
 inline void* at(void* ws, size_t off) { return static_cast<char*>(ws) + off; }
+
+// Measurement aid (gad_gcn_layer_events): events the forward and backward passes of this thread record at their
+// layer boundaries.  Empty = off.
+thread_local std::vector<hipEvent_t> g_layer_events;
+
+inline bool layer_events_on(int L) { return (int)g_layer_events.size() >= 2 * L + 3; }
 
 // The weight-gradient products of the backward pass are bound by the matrix cores, the sparse products next to them
 // by memory, and neither needs the other's result: dW_l runs on a side stream while the main stream goes on with
@@ -270,6 +310,11 @@ static int forward_impl(const gad_graph* g, const void* X, gad_dtype dtype, int 
     return set_error(GAD_ERR_SHAPE, "negative_slope must lie in [0, 1)");
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int64_t n = g->n;
+  // A~ X of the first layer is still in the workspace when the last forward on it had this graph, X and model
+  const bool have_first = reuse_first && p.agg_first[0] && forward_saved(g, workspace, L, dims, dtype, X);
+  forget_workspace(workspace);                           // from here on the workspace holds no complete forward
+  const bool marks = layer_events_on(L);
+  if (marks) GAD_HIP(hipEventRecord(g_layer_events[0], s));
 
   const void* h = X;
   int64_t ldh = dims[0];
@@ -289,8 +334,7 @@ static int forward_impl(const gad_graph* g, const void* X, gad_dtype dtype, int 
     if (p.agg_first[l]) {
       void* m = at(workspace, p.agg[l]);
       const int64_t ldm = pad_ld(dims[l]);
-      // A~ X of the first layer is still in the workspace when the last forward on it had this graph, X and model
-      const bool have = l == 0 && reuse_first && forward_saved(g, workspace, L, dims, dtype, X);
+      const bool have = l == 0 && have_first;
       if (!have && (st = spmm(g, h, ldh, dtype, m, ldm, dtype, dims[l], none, psum, s)) != GAD_OK) return st;
       if ((st = gemm_w(m, ldm, dtype, W[l], dims[l], dims[l + 1], false, dst, ldd, t_dst, n, act, wsc, s)) != GAD_OK)
         return st;
@@ -302,6 +346,7 @@ static int forward_impl(const gad_graph* g, const void* X, gad_dtype dtype, int 
     }
     h = dst;
     ldh = ldd;
+    if (marks) GAD_HIP(hipEventRecord(g_layer_events[l + 1], s));
   }
   const int C = dims[L];
   const int64_t ldz = pad_ld(C);
@@ -310,10 +355,22 @@ static int forward_impl(const gad_graph* g, const void* X, gad_dtype dtype, int 
                     static_cast<double*>(at(workspace, p.sm)), loss_out, s);
   if (st != GAD_OK) return st;
   if (logits_out && (st = copy_rows(Z, ldz, GAD_F32, logits_out, C, n, C, s)) != GAD_OK) return st;
-  {
-    std::lock_guard<std::mutex> lk(g_saved_mu);
-    g_saved[workspace] = Saved{g, L, std::vector<int32_t>(dims, dims + L + 1), dtype, X, negative_slope};
-  }
+  if (marks) GAD_HIP(hipEventRecord(g_layer_events[L + 1], s));
+  remember_forward(workspace, g, L, dims, dtype, X, negative_slope);
+  return GAD_OK;
+}
+
+int gad_gcn_layer_events(void* const* events, int count) {
+  if (count < 0 || (count > 0 && !events)) return set_error(GAD_ERR_NULL, "count < 0, or events is NULL");
+  for (int i = 0; i < count; ++i)
+    if (!events[i]) return set_error(GAD_ERR_NULL, "events[%d] is NULL", i);
+  g_layer_events.assign(reinterpret_cast<const hipEvent_t*>(events), reinterpret_cast<const hipEvent_t*>(events) + count);
+  return GAD_OK;
+}
+
+int gad_workspace_forget(const void* workspace) {
+  if (!workspace) return set_error(GAD_ERR_NULL, "workspace is NULL");
+  forget_workspace(workspace);
   return GAD_OK;
 }
 
@@ -344,8 +401,10 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
   if (!dW) return set_error(GAD_ERR_NULL, "dW is NULL");
   for (int l = 0; l < L; ++l)
     if (!dW[l]) return set_error(GAD_ERR_NULL, "dW[%d] is NULL", l);
-  if (!forward_saved(g, workspace, L, dims, dtype, X, &negative_slope))
-    return set_error(GAD_ERR_STATE, "workspace holds no forward pass matching this graph / model / X / slope");
+  bool consumed = false;
+  if (!forward_saved(g, workspace, L, dims, dtype, X, &negative_slope, true, &consumed))
+    return set_error(GAD_ERR_STATE, consumed ? "a backward pass has already used this forward pass: run the forward again"
+                                             : "workspace holds no forward pass matching this graph / model / X / slope");
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int64_t n = g->n;
   void* gcur = at(workspace, p.g_a);
@@ -381,6 +440,8 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
     side_busy = false;
     return GAD_OK;
   };
+  const bool marks = layer_events_on(L);
+  if (marks) GAD_HIP(hipEventRecord(g_layer_events[L + 2], s));
   for (int l = L - 1; l >= 0; --l) {
     const int fin = dims[l], fout = dims[l + 1];
     const int64_t ldg = pad_ld(fout);        // G_l, S_l
@@ -414,6 +475,13 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
     void* t = gcur;
     gcur = gnext;
     gnext = t;
+    if (marks) {                                         // a layer's time includes its weight gradient: join first
+      if ((st = join()) != GAD_OK) break;
+      if (hipEventRecord(g_layer_events[L + 3 + (L - 1 - l)], s) != hipSuccess) {
+        st = set_error(GAD_ERR_HIP, "hipEventRecord failed on a layer event");
+        break;
+      }
+    }
   }
   const int stj = join();                                // also on an error path: the side stream never outlives the call
   return st != GAD_OK ? st : stj;

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libgad.so")
 
 F32, BF16 = 0, 1
 SYMBOLS = ["gad_last_error", "gad_build_subgraph", "gad_graph_info", "gad_graph_destroy", "gad_graph_concat", "gad_augment_subgraph",
-           "gad_gcn_workspace_bytes", "gad_gcn_forward", "gad_gcn_forward_cached", "gad_gcn_backward", "gad_gcn_activation", "gad_spmm_workspace_bytes", "gad_spmm",
+           "gad_gcn_workspace_bytes", "gad_workspace_forget", "gad_gcn_forward", "gad_gcn_forward_cached", "gad_gcn_backward", "gad_gcn_layer_events", "gad_gcn_activation", "gad_spmm_workspace_bytes", "gad_spmm",
            "gad_gemm_workspace_bytes", "gad_gemm_w", "gad_gemm_tn",
            "gad_subgraph_variance", "gad_subgraph_variance_static", "gad_pair_importance_workspace_bytes", "gad_pair_importance",
            "gad_weighted_consensus", "gad_consensus_update", "gad_train_round", "gad_train_round_batched"]
@@ -161,6 +161,11 @@ def alloc_workspace(g: Graph, dims: Sequence[int], dtype: int = F32) -> torch.Te
     return torch.empty(gcn_workspace_bytes(g, dims, dtype), dtype=torch.uint8, device="cuda")
 
 
+def workspace_forget(workspace: torch.Tensor) -> None:
+    """Call before the memory of a workspace is freed or reused for anything else."""
+    _check(lib().gad_workspace_forget(_ptr(workspace)))
+
+
 def gcn_forward(g: Graph, X: torch.Tensor, dims: Sequence[int], W: List[torch.Tensor], labels: torch.Tensor,
                 mask: Optional[torch.Tensor], loss_scale: float, workspace: torch.Tensor,
                 logits_out: Optional[torch.Tensor] = None, loss_out: Optional[torch.Tensor] = None,
@@ -197,6 +202,12 @@ def gcn_backward(g: Graph, X: torch.Tensor, dims: Sequence[int], W: List[torch.T
     _check(lib().gad_gcn_backward(g.handle, _ptr(X), C.c_int(dtype), C.c_int(len(dims) - 1), _dims(dims), _ptr_array(W),
                                   C.c_float(negative_slope), _ptr(workspace), C.c_size_t(workspace.numel()), _ptr_array(dW),
                                   gp, _stream()))
+
+
+def gcn_layer_events(events: Sequence[int]) -> None:
+    """events: hipEvent_t handles (integers) for the layer boundaries of this thread's passes; empty = off."""
+    arr = (C.c_void_p * max(len(events), 1))(*events)
+    _check(lib().gad_gcn_layer_events(arr, C.c_int(len(events))))
 
 
 def gcn_activation(g: Graph, workspace: torch.Tensor, dims: Sequence[int], layer: int, out: torch.Tensor,

@@ -411,6 +411,51 @@ def test_gcn_errors(gad):
     assert all(torch.isfinite(d).all() for d in dW)
 
 
+def test_workspace_state(gad):
+    """One backward per forward (the backward overwrites the forward's seed gradient: a second one must be refused,
+    not answered wrongly); a forgotten workspace holds nothing: the backward is refused and the cached forward
+    computes the first aggregate again instead of reading whatever lies at that address."""
+    cfg = wl.CONFIGS["tiny"]
+    g, ref = build_both(gad, wl.make_graph(cfg))
+    dims = (24, 40, 32, 9)                                   # three layers: the backward swaps both gradient buffers
+    X, Ws = wl.make_features(cfg.n, dims[0]), wl.make_weights(dims)
+    y, mask = wl.make_labels(cfg.n, dims[-1]), wl.make_mask(cfg)
+    Xd, Wd, yd, md, c = dev(X), [dev(w) for w in Ws], dev(y), dev(mask), 1.0 / mask.sum()
+    f = T1.forward(ref, X, Ws, y, mask, c)
+    ws = gad.alloc_workspace(g, dims)
+    logits = torch.empty((g.n, dims[-1]), device="cuda")
+    dW = [torch.empty_like(w) for w in Wd]
+    gad.gcn_forward(g, Xd, dims, Wd, yd, md, c, ws, logits)
+    gad.gcn_backward(g, Xd, dims, Wd, ws, dW)
+    with pytest.raises(gad.GadError) as e:
+        gad.gcn_backward(g, Xd, dims, Wd, ws, dW)
+    assert e.value.status == -9
+    h1 = torch.empty((g.n, dims[1]), device="cuda")
+    gad.gcn_activation(g, ws, dims, 1, h1)                   # the activations of that forward are still readable
+    assert rel_err(h1.cpu().numpy(), f["H"][1]) < TOL
+    gad.gcn_forward(g, Xd, dims, Wd, yd, md, c, ws, logits, x_unchanged=True)      # and its first aggregate reusable
+    gad.gcn_backward(g, Xd, dims, Wd, ws, dW)
+    torch.cuda.synchronize()
+    d_first = [d.clone() for d in dW]
+    # the caller frees the workspace and a new buffer comes back at the same address: modelled by forgetting it
+    # and overwriting the memory
+    gad.workspace_forget(ws)
+    ws.view(torch.float32).fill_(float("nan"))
+    with pytest.raises(gad.GadError) as e:
+        gad.gcn_backward(g, Xd, dims, Wd, ws, dW)
+    assert e.value.status == -9
+    with pytest.raises(gad.GadError) as e:
+        gad.gcn_activation(g, ws, dims, 1, h1)
+    assert e.value.status == -9
+    gad.gcn_forward(g, Xd, dims, Wd, yd, md, c, ws, logits, x_unchanged=True)      # must run the full forward
+    gad.gcn_backward(g, Xd, dims, Wd, ws, dW)
+    torch.cuda.synchronize()
+    assert rel_err(logits.cpu().numpy(), f["Z"]) < TOL
+    assert all(torch.equal(a, b) for a, b in zip(dW, d_first))
+    gad.workspace_forget(ws)                                 # forgetting twice is fine
+    gad.workspace_forget(ws)
+
+
 # ------------------------------------------------------------------------------------------ GAD-Optimizer
 
 @pytest.mark.parametrize("name,F", [("tiny", 128), ("products_small", 100), ("products_small", 47), ("tiny", 1),
