@@ -81,6 +81,8 @@ CONFIGS: Dict[str, Workload] = {
     # down-scaled variants used by parity tests that need the full oracle
     "rmat16": Workload("rmat16", "rmat", 1 << 16, 0, (128, 512, 512, 512, 64), dtype="bf16",
                        rmat_scale=16, rmat_edge_factor=32),
+    "rmat18": Workload("rmat18", "rmat", 1 << 18, 0, (128, 512, 512, 512, 64), dtype="bf16",
+                       rmat_scale=18, rmat_edge_factor=32),
     "products_small": Workload("products_small", "chung_lu", 20_000, 3_000, (100, 256, 256, 47),
                                avg_degree=50.0, max_degree=2_000, global_factor=2, extra_edge_frac=0.10,
                                consensus_k=4),

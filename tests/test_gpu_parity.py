@@ -195,22 +195,42 @@ def run_gpu_step(gad, g, X, Ws, y, mask, c, dims, dtype=0, slope=0.0):
     return logits.cpu().numpy(), loss.item(), [d.cpu().numpy() for d in dW], Hs, [t.cpu().numpy() for t in Gout]
 
 
-def relu_decisions(f, Ws, Hs_gpu, band=1e-5):
-    """ReLU decisions for the oracle's backward: its own [P_l > 0], except where |P_l| is below float32
-    rounding of the sum that forms it -- there the decision is the kernel's (read off its activation).
-    Returns the decisions and the number of entries taken from the kernel."""
-    out, taken = [], 0
+# Band inside which a ReLU decision is two-valued at the rounding level of the storage type, relative to the sum of
+# the absolute terms that form the pre-activation P_l = (A~ H_{l-1}) W_l.
+#   float32: accumulation error of the sparse and dense sums, a few 2^-24 per term -> 1e-5.
+#   bfloat16: the aggregate is stored in bfloat16 (unit roundoff 2^-9) and W is rounded to bfloat16 for the product
+#   (2^-9 again), so a term is off by up to 2^-8 = 3.9e-3 of itself: band 4e-3.  (Observed on the test workloads:
+#   at most 1.7e-3, also on the third hidden layer, whose input carries the roundings of two layers before it.)
+RELU_BAND_F32 = 1e-5
+RELU_BAND_BF16 = 4e-3
+# Share of a layer's entries whose decision may be taken from the kernel: observed none in float32 and 0.7e-3 to
+# 1.13e-3 in bfloat16 (every layer of every case, R-MAT scale 18 included); caps with a margin over that.
+RELU_TAKEN_F32 = 1e-6
+RELU_TAKEN_BF16 = 2.5e-3
+
+
+def relu_decisions(f, Ws, Hs_gpu, bf16=False, label=""):
+    """ReLU decisions for the oracle's backward: its own [P_l > 0], except where |P_l| lies inside the rounding band
+    of the sum that forms it -- there the decision is the kernel's (read off its activation).  Asserts that every
+    differing entry lies inside the band and that their share stays below the cap; prints the count per layer."""
+    out = []
     for l, h in enumerate(Hs_gpu):
         P = f["P"][l]
         on = P > 0
         differ = on != (h > 0)
-        if differ.any():
+        taken, worst = int(differ.sum()), 0.0
+        band = RELU_BAND_BF16 if bf16 else RELU_BAND_F32
+        if taken:
             bound = np.abs(f["AH"][l]) @ np.abs(np.asarray(Ws[l], dtype=np.float64))    # sum of |terms| of P_l
-            assert np.all(np.abs(P[differ]) <= band * bound[differ]), "activation sign differs beyond rounding"
+            worst = float((np.abs(P[differ]) / bound[differ]).max())
+            assert worst <= band, f"layer {l + 1}: activation sign differs beyond rounding ({worst:.2e} > {band:.1e})"
             on = np.where(differ, h > 0, on)
-            taken += int(differ.sum())
+        cap = (RELU_TAKEN_BF16 if bf16 else RELU_TAKEN_F32) * h.size + 2
+        print(f"relu decisions {label} layer {l + 1}: {taken} of {h.size} taken from the kernel "
+              f"({taken / h.size:.2e}), largest |P| / sum|terms| among them {worst:.2e} (band {band:.1e})", flush=True)
+        assert taken <= cap, f"layer {l + 1}: {taken} decisions taken from the kernel, cap {cap:.0f}"
         out.append(on)
-    return out, taken
+    return out
 
 
 def check_step(gad, g, ref, X, Ws, y, mask, c, dims, bf16=False, slope=0.0):
@@ -228,8 +248,7 @@ def check_step(gad, g, ref, X, Ws, y, mask, c, dims, bf16=False, slope=0.0):
     for l, h in enumerate(Hs):
         assert rel_err(h, f["H"][l + 1]) < tol, f"H[{l + 1}]"
     # ReLU decisions inside the rounding band of the storage type are the kernel's (see relu_decisions)
-    relu_on, taken = relu_decisions(f, Ws, Hs, band=1e-2 if bf16 else 1e-5)
-    assert taken <= (3e-2 if bf16 else 1e-6) * sum(h.size for h in Hs) + 2
+    relu_on = relu_decisions(f, Ws, Hs, bf16, label=f"n={g.n} dims={tuple(dims)}")
     d_ref, G_ref = T1.backward(ref, Ws, f, y, m, c, relu_on=relu_on, slope=slope)
     for l in range(len(dW)):
         assert rel_err(Gs[l], G_ref[l]) < tol, f"G[{l}]"
@@ -252,8 +271,8 @@ def test_gcn_step_matches_oracle(gad, name, dims):
     check_step(gad, g, ref, X, Ws, y, mask, 1.0 / mask.sum(), dims)
 
 
-@pytest.mark.parametrize("name,dims", [("rmat16", None), ("products_small", (100, 72, 33, 7)), ("tiny", (128, 64, 16)),
-                                       ("tiny", (20, 24, 9))])
+@pytest.mark.parametrize("name,dims", [("rmat16", None), ("rmat18", None), ("products_small", (100, 72, 33, 7)),
+                                       ("tiny", (128, 64, 16)), ("tiny", (20, 24, 9))])
 def test_gcn_step_bf16_matches_oracle(gad, name, dims):
     """bfloat16 storage of features and activations, float32 accumulation, float32 weights (fifth workload's type)."""
     cfg = wl.CONFIGS[name]
@@ -315,7 +334,8 @@ def test_gcn_step_sum_loss_no_mask_and_dense_oracle(gad):
     At = T0.normalized_adjacency(T0.adjacency_dense(**gr))
     ones = np.ones(cfg.n, dtype=np.uint8)
     f = T0.forward(At, X, Ws, y, ones, 1.0)
-    relu_on = [np.where(np.abs(f["P"][0]) < 1e-6, Hs[0] > 0, f["P"][0] > 0)]
+    f["AH"] = [At @ np.asarray(X, dtype=np.float64)]           # the aggregate of the first layer, for the band
+    relu_on = relu_decisions(f, Ws, Hs, False, label="dense oracle")
     d_ref, _ = T0.backward(At, Ws, f, y, ones, 1.0, relu_on=relu_on)
     assert rel_err(logits, f["Z"]) < TOL
     assert abs(loss - f["loss"]) <= TOL * abs(f["loss"])
