@@ -44,6 +44,43 @@ class HipEvents:
         return float(t.value)
 
 
+def gather_sweep(args) -> int:
+    """Uniform random graphs: no hub rows, so nearly every gathered row is a miss of whatever cache is smaller than
+    the source matrix.  The rate over the gather-model bytes is then the ceiling of that level for 1 KB gathers."""
+    import dataclasses
+    import numpy as np
+    import torch
+    from paper_2110_02987_amd import gad, workloads as wl
+    torch.cuda.set_device(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    w, out = 256, []
+    for n in (2048, 16384, 65536, 131072, 262144, 690000, 2000000):
+        cfg = dataclasses.replace(wl.CONFIGS["tiny"], name=f"er{n}", n_local=n, avg_degree=50.0)
+        gr = wl.make_graph(cfg)
+        g = gad.build_subgraph(dev(gr["src"]), dev(gr["dst"]), gr["n_global"], dev(gr["local_ids"]), dev(gr["halo_ids"]))
+        T = torch.randn((n, w), device="cuda")
+        O = torch.empty_like(T)
+        sws = gad.spmm_workspace(g, w)
+        for _ in range(3):
+            gad.spmm(g, T, O, w, gad.F32, sws)
+        ts = []
+        for _ in range(args.kernel_reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            gad.spmm(g, T, O, w, gad.F32, sws)
+            b.record()
+            ts.append((a, b))
+        torch.cuda.synchronize()
+        ms = float(np.median([a.elapsed_time(b) for a, b in ts]))
+        gather = g.nnz * (4 + 4 * w) + n * (12 + 4 * w)
+        out.append(dict(n=n, nnz=g.nnz, source_MB=n * w * 4 / 1e6, ms=ms, gather_model_GBps=gather / ms * 1e-6))
+        print(f"uniform random graph n={n:8d} nnz={g.nnz:10d} source matrix {n * w * 4 / 1e6:7.1f} MB: "
+              f"{ms:8.4f} ms  {gather / ms * 1e-6:7.0f} GB/s of gather-model bytes", flush=True)
+        del g, T, O, sws
+    print(json.dumps(dict(gather_sweep=out, width=w)))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +94,10 @@ def main() -> int:
                          "the seeded shuffle")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=20, help="standalone launches of the dominant kernel")
+    ap.add_argument("--gather-sweep", action="store_true",
+                    help="measurement aid: the width-256 SpMM on uniform random graphs (average degree 50) whose source "
+                         "matrix grows from 2 MB (fits one L2) over 268 MB (about the Infinity Cache) to 2 GB (HBM): "
+                         "what random 1 KB row gathers reach at each level of the memory system; prints one line per size")
     ap.add_argument("--kernels-only", action="store_true",
                     help="profiling aid: run only a 1 GiB device copy (counter calibration) and the standalone SpMM "
                          "launches, no training steps, no CPU baseline")
@@ -70,6 +111,8 @@ def main() -> int:
     import torch
     from paper_2110_02987_amd import gad, workloads as wl
 
+    if args.gather_sweep:
+        return gather_sweep(args)
     cfg = wl.CONFIGS[args.workload]
     variant = ""
     if args.storage and args.storage != cfg.dtype:          # a variant of the named workload, reported as such

@@ -204,13 +204,35 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ 
                            p_vec, false);
 }
 
-__global__ void reduce_slabs(const float* __restrict__ P, int n_slabs, int64_t elems, int N, float* __restrict__ C,
-                             int64_t ldc) {
-  const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (e >= elems) return;
-  double s = 0.0;
-  for (int q = 0; q < n_slabs; ++q) s += (double)P[(int64_t)q * elems + e];
-  C[(e / N) * ldc + (e % N)] = (float)s;
+// C = sum over the slabs of P[slab], in float64 and in a fixed order: a block owns 32 output elements; its eight
+// 32-lane groups each add a contiguous run of slabs (four partial sums per thread keep four loads in flight and are
+// combined in a fixed order), then the eight run sums are added in run order.
+__global__ __launch_bounds__(256) void reduce_slabs(const float* __restrict__ P, int n_slabs, int64_t elems, int N,
+                                                    float* __restrict__ C, int64_t ldc) {
+  __shared__ double run_sum[8][32];
+  const int l = threadIdx.x & 31, run = threadIdx.x >> 5;
+  const int64_t e = blockIdx.x * 32ll + l;
+  const int q0 = (int)((int64_t)run * n_slabs / 8), q1 = (int)((int64_t)(run + 1) * n_slabs / 8);
+  double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+  if (e < elems) {
+    const float* p = P + e;
+    int q = q0;
+    for (; q + 4 <= q1; q += 4) {
+      s0 += (double)p[(int64_t)q * elems];
+      s1 += (double)p[(int64_t)(q + 1) * elems];
+      s2 += (double)p[(int64_t)(q + 2) * elems];
+      s3 += (double)p[(int64_t)(q + 3) * elems];
+    }
+    for (; q < q1; ++q) s0 += (double)p[(int64_t)q * elems];
+  }
+  run_sum[run][l] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (run == 0 && e < elems) {
+    double s = run_sum[0][l];
+#pragma unroll
+    for (int r = 1; r < 8; ++r) s += run_sum[r][l];
+    C[(e / N) * ldc + (e % N)] = (float)s;
+  }
 }
 
 __global__ void transpose_kernel(const float* __restrict__ in, int rows, int cols, float* __restrict__ out) {
@@ -298,7 +320,7 @@ int gemm_tn_f32(const float* A, int64_t lda, const float* G, int64_t ldg, float*
                                            vec_ok(G, ldg), pv);
   GAD_LAUNCH_CHECK();
   const int64_t elems = (int64_t)K * N;
-  reduce_slabs<<<(unsigned)ceil_div(elems, 256), 256, 0, s>>>(partials, n_slabs, elems, N, C, ldc);
+  reduce_slabs<<<(unsigned)ceil_div(elems, 32), 256, 0, s>>>(partials, n_slabs, elems, N, C, ldc);
   GAD_LAUNCH_CHECK();
   return GAD_OK;
 }
@@ -344,7 +366,7 @@ int gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, gad_dtype t,
   int st = gemm_tn_bf16(A, lda, G, ldg, partials, M, K, N, n_slabs, slab_rows, full_rows, s);
   if (st != GAD_OK) return st;
   const int64_t elems = (int64_t)K * N;
-  reduce_slabs<<<(unsigned)ceil_div(elems, 256), 256, 0, s>>>(partials, n_slabs, elems, N, C, ldc);
+  reduce_slabs<<<(unsigned)ceil_div(elems, 32), 256, 0, s>>>(partials, n_slabs, elems, N, C, ldc);
   GAD_LAUNCH_CHECK();
   return GAD_OK;
 }

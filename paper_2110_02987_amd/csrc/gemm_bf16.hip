@@ -19,6 +19,8 @@
 // tile (NT) or two tiles (TN) are on their way from global memory into registers while the current one is
 // multiplied (double-buffered LDS, one barrier per tile).  Blocks are renumbered so that the blocks sharing an operand tile run on the same XCD
 // (consecutive workgroup ids go to different XCDs, each with an L2 of its own).
+#include <stdlib.h>
+
 #include <atomic>
 
 #include "dtype.h"
@@ -155,8 +157,8 @@ __device__ __forceinline__ void store_acc(const v16f (&acc)[TM][TN], TC* __restr
 // 64-byte row pieces (bfloat16).  Each wave instead passes its 32 x (32 TN) accumulator blocks through its own
 // region of LDS and writes whole row pieces with 16-byte stores; the mask operand is read the same way.
 // Must be entered by all four waves, after the last read of the operand tiles (the barriers are block wide).
-template <int EPI, int TN, typename TC>
-__device__ __forceinline__ void store_rows(const v16f (&acc)[2][TN], float* __restrict__ lds, TC* __restrict__ C,
+template <int EPI, int TM, int TN, typename TC>
+__device__ __forceinline__ void store_rows(const v16f (&acc)[TM][TN], float* __restrict__ lds, TC* __restrict__ C,
                                            int64_t ldc, int64_t row0, int col0, int64_t M, int N, bool c_vec,
                                            float slope, const bf16_t* __restrict__ aux, int64_t ldaux, bool aux_vec) {
   constexpr int W = 32 * TN;          // columns of the wave's block
@@ -166,7 +168,7 @@ __device__ __forceinline__ void store_rows(const v16f (&acc)[2][TN], float* __re
   const int lane = threadIdx.x & 63;
   float* mine = lds + (threadIdx.x >> 6) * (32 * LD);
 #pragma unroll
-  for (int tm = 0; tm < 2; ++tm) {
+  for (int tm = 0; tm < TM; ++tm) {
     __syncthreads();
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
@@ -223,31 +225,36 @@ __device__ __forceinline__ void store_rows(const v16f (&acc)[2][TN], float* __re
 }
 
 // ---- NT ----------------------------------------------------------------------------------------
-// Block tile 128 x (64 TN); work item = (row tile, column tile) with the column tile fastest, so the blocks
+// WM x WN waves per block, each owning TM x TN accumulator blocks of 32 x 32: block tile BM x BN =
+// (32 WM TM) x (32 WN TN).  Work item = (row tile, column tile) with the column tile fastest, so the blocks
 // that share a row tile of A follow each other on one XCD.  Bt has ldb = K rounded up to BK, zero filled.
+// Two shapes are used: 2 x 2 waves of 64 x (32 TN) for outputs up to 255 columns (two or three blocks per CU), and
+// 2 x 4 waves of 128 x 64 (a 256 x 256 block, one per CU) for wider outputs: per matrix instruction it reads
+// 40 % fewer operand bytes from LDS and stages a third fewer, and a wave runs 32 (64-deep tiles) matrix
+// instructions between barriers instead of 16.
 // FAST: A may be fetched in aligned 16-byte pieces (16-byte aligned rows; a piece that straddles column K reads
 // padding inside the row, which the caller must have declared readable).  Its loads are unconditional (a piece outside the matrix is fetched from the matrix's
 // first bytes; what lies outside is zeroed when the piece is staged), so the compiler can count the loads in
 // flight and wait only for the oldest tile; the general path waits for all of them.
-template <int BK, int TN, int EPI, typename TC, bool FAST>
-__global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const bf16_t* __restrict__ A, int64_t lda,
-                                                      const bf16_t* __restrict__ Bt, int64_t ldb,
-                                                      TC* __restrict__ C, int64_t ldc, int64_t M, int N, int K,
-                                                      bool a_vec, bool c_vec, float slope,
-                                                      const bf16_t* __restrict__ aux, int64_t ldaux, bool aux_vec,
-                                                      int tiles_n, int64_t total) {
+template <int BK, int WM, int WN, int TM, int TN, int EPI, typename TC, bool FAST>
+__global__ __launch_bounds__(64 * WM * WN, WM * WN == 4 ? 2 : 1) void gemm_nt_kernel(
+    const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ Bt, int64_t ldb, TC* __restrict__ C,
+    int64_t ldc, int64_t M, int N, int K, bool a_vec, bool c_vec, float slope, const bf16_t* __restrict__ aux,
+    int64_t ldaux, bool aux_vec, int tiles_n, int64_t total) {
   constexpr int MODE = BK == 32 ? kSwz32 : kPadded;
-  constexpr int BM = 128, BN = 64 * TN, LDK = tile_ld<BK, MODE>(), CH = BK / 8;
-  constexpr int PA = BM * CH / 256, PB = BN * CH / 256;      // 16-byte pieces per thread and tile
+  constexpr int NT = 64 * WM * WN;                           // threads per block
+  constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN, LDK = tile_ld<BK, MODE>(), CH = BK / 8;
+  constexpr int PA = BM * CH / NT, PB = BN * CH / NT;        // 16-byte pieces per thread and tile
+  static_assert(BM * CH % NT == 0 && BN * CH % NT == 0, "whole pieces per thread");
   constexpr int TILE = (BM + BN) * LDK;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);        // [2][TILE]: rows 0..BM-1 = A, then BN rows of Bt
-  const int t = threadIdx.x, w = t >> 6, wm = w >> 1, wn = w & 1;
+  const int t = threadIdx.x, w = t >> 6, wm = w / WN, wn = w % WN;
   const int64_t item = xcd_order(blockIdx.x, total);
   const int64_t row0 = (item / tiles_n) * BM;
   const int col0 = (int)(item % tiles_n) * BN;
-  v16f acc[2][TN];
-  zero_acc<2, TN>(acc);
+  v16f acc[TM][TN];
+  zero_acc<TM, TN>(acc);
 
   constexpr int kDepth = nt_depth<TN>();
   // kDepth tiles are in flight in registers (tile j in slot j % kDepth).
@@ -255,7 +262,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const bf16_t* __restric
   auto fetch = [&](uint4 (&a)[PA], uint4 (&b)[PB], int k1) {
 #pragma unroll
     for (int j = 0; j < PA; ++j) {
-      const int p = t + 256 * j;
+      const int p = t + NT * j;
       const int64_t row = row0 + p / CH;
       const int col = k1 + (p % CH) * 8;
       if (FAST) {
@@ -267,7 +274,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const bf16_t* __restric
     }
 #pragma unroll
     for (int j = 0; j < PB; ++j) {                     // Bt is zero padded to whole tiles along k: inside for k1 < K
-      const int p = t + 256 * j;
+      const int p = t + NT * j;
       const int r = col0 + p / CH;
       b[j] = *reinterpret_cast<const uint4*>(Bt + (r < N && k1 < K ? (int64_t)r * ldb + k1 + (p % CH) * 8 : 0));
     }
@@ -275,13 +282,13 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const bf16_t* __restric
   auto stage = [&](const uint4 (&a)[PA], const uint4 (&b)[PB], bf16_t* tile, int k1) {
 #pragma unroll
     for (int j = 0; j < PA; ++j) {
-      const int p = t + 256 * j;
+      const int p = t + NT * j;
       const int n_valid = !FAST ? 8 : (row0 + p / CH < M ? K - (k1 + (p % CH) * 8) : 0);
       *reinterpret_cast<uint4*>(tile + tile_off<LDK, MODE>(p / CH, p % CH)) = keep_first(a[j], n_valid);
     }
 #pragma unroll
     for (int j = 0; j < PB; ++j) {
-      const int p = t + 256 * j;
+      const int p = t + NT * j;
       *reinterpret_cast<uint4*>(tile + BM * LDK + tile_off<LDK, MODE>(p / CH, p % CH)) = keep_if(col0 + p / CH < N, b[j]);
     }
   };
@@ -300,7 +307,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const bf16_t* __restric
       const int kt = kt0 + d;
       bf16_t* cur = smem + (kt & 1) * TILE;
       bf16_t* nxt = smem + ((kt & 1) ^ 1) * TILE;
-      mma_tile<BK, 2, TN, MODE>(cur, cur + BM * LDK, wm * 64, wn * 32 * TN, acc);
+      mma_tile<BK, TM, TN, MODE>(cur, cur + BM * LDK, wm * 32 * TM, wn * 32 * TN, acc);
       const int slot = (d + 1) % kDepth;                     // tile kt + 1
       stage(ra[slot], rb[slot], nxt, (kt + 1) * BK);
       fetch(ra[slot], rb[slot], (kt + 1 + kDepth) * BK);
@@ -312,8 +319,8 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const bf16_t* __restric
     }
     if (done) break;
   }
-  store_rows<EPI, TN, TC>(acc, reinterpret_cast<float*>(smem_raw), C, ldc, row0 + wm * 64, col0 + wn * 32 * TN, M, N,
-                          c_vec, slope, aux, ldaux, aux_vec);
+  store_rows<EPI, TM, TN, TC>(acc, reinterpret_cast<float*>(smem_raw), C, ldc, row0 + wm * 32 * TM, col0 + wn * 32 * TN,
+                              M, N, c_vec, slope, aux, ldaux, aux_vec);
 }
 
 // ---- TN ----------------------------------------------------------------------------------------
@@ -438,16 +445,17 @@ bool vec_ok(const bf16_t* p, int64_t ld) { return (ld % 8 == 0) && ((reinterpret
 
 constexpr int kNtBKmax = 64;
 
-template <int kNtBK, int TN, typename TC>
+template <int kNtBK, int WM, int WN, int TM, int TN, typename TC>
 int launch_nt(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
               const Epi& e, hipStream_t s) {
-  constexpr int BN = 64 * TN;
-  constexpr size_t tiles_bytes = 2u * (128 + BN) * (kNtBK == 32 ? 32 : kNtBK + 8) * sizeof(bf16_t);   // two operand tiles
-  constexpr size_t stage_bytes = 4u * 32 * (32 * TN + 8) * sizeof(float);            // epilogue staging, reuses them
+  constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN, NT = 64 * WM * WN;
+  constexpr size_t tiles_bytes = 2u * (BM + BN) * (kNtBK == 32 ? 32 : kNtBK + 8) * sizeof(bf16_t);   // two operand tiles
+  constexpr size_t stage_bytes = (size_t)(WM * WN) * 32 * (32 * TN + 8) * sizeof(float);    // epilogue staging, reuses them
   constexpr size_t smem = tiles_bytes > stage_bytes ? tiles_bytes : stage_bytes;
+  static_assert(smem <= 160 * 1024, "one block's tiles fit the CU's LDS");
   const int tiles_n = (int)ceil_div(N, BN);
-  const int64_t total = ceil_div(M, 128) * tiles_n;
-  GAD_GRID_CHECK(total, 256);
+  const int64_t total = ceil_div(M, BM) * tiles_n;
+  GAD_GRID_CHECK(total, NT);
   const bf16_t* aux = static_cast<const bf16_t*>(e.aux);
   const bool av = vec_ok(A, lda);
   const bool fast = av && (e.full_rows || K % 8 == 0);      // no 16-byte piece may reach past the end of a row
@@ -455,15 +463,16 @@ int launch_nt(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C
   const bool xv = aux != nullptr && vec_ok(aux, e.ldaux);
 #define GAD_NT_LAUNCH(EPI)                                                                                          \
   {                                                                                                                 \
-    auto kern = fast ? gemm_nt_kernel<kNtBK, TN, EPI, TC, true> : gemm_nt_kernel<kNtBK, TN, EPI, TC, false>;        \
+    auto kern = fast ? gemm_nt_kernel<kNtBK, WM, WN, TM, TN, EPI, TC, true>                                         \
+                     : gemm_nt_kernel<kNtBK, WM, WN, TM, TN, EPI, TC, false>;                                       \
     static std::atomic<bool> attr_set[2];          /* set once per kernel; setting it twice is harmless */          \
     if (!attr_set[fast].load(std::memory_order_acquire)) {                                                          \
       GAD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,  \
                                   (int)smem));                                                                      \
       attr_set[fast].store(true, std::memory_order_release);                                                        \
     }                                                                                                               \
-    kern<<<(unsigned)total, 256, smem, s>>>(A, lda, Bt, ldb, C, ldc, M, N, K, av, cv, e.slope, aux, e.ldaux, xv,    \
-                                            tiles_n, total);                                                        \
+    kern<<<(unsigned)total, NT, smem, s>>>(A, lda, Bt, ldb, C, ldc, M, N, K, av, cv, e.slope, aux, e.ldaux, xv,     \
+                                           tiles_n, total);                                                         \
   }
   switch (e.kind) {
     case EPI_NONE: GAD_NT_LAUNCH(EPI_NONE) break;
@@ -476,15 +485,27 @@ int launch_nt(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C
   return GAD_OK;
 }
 
+// GAD_NT_WIDE in the environment picks the kernel for outputs of 256 columns or more: 0 = 128 x 256 blocks of four
+// waves with 32-deep tiles, 1 (default) = 256 x 256 blocks of eight waves with 64-deep tiles, 2 = the same with
+// 32-deep tiles.
+int nt_wide_variant() {
+  static const int v = [] {
+    const char* e = getenv("GAD_NT_WIDE");
+    return e ? atoi(e) : 1;
+  }();
+  return v;
+}
+
 template <typename TC>
 int nt_typed(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
              const Epi& e, hipStream_t s) {
-  // Narrow outputs: 64-deep tiles, two or three blocks per CU.  Wide outputs: 256 columns per block (the A tile is
-  // fetched for fewer column tiles) with 32-deep tiles, which keeps two blocks per CU in LDS; measured on
-  // 4.2 M x 512 x 512: 3.7 ms against 5.3 ms with 64-deep tiles at one block per CU.
-  if (N <= 64) return launch_nt<64, 1, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
-  if (N <= 128) return launch_nt<64, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
-  return launch_nt<32, 4, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+  // Narrow outputs: 64-deep tiles, two or three blocks per CU.
+  if (N <= 64) return launch_nt<64, 2, 2, 2, 1, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+  if (N <= 128) return launch_nt<64, 2, 2, 2, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+  const int v = N >= 256 ? nt_wide_variant() : 0;
+  if (v == 1) return launch_nt<64, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+  if (v == 2) return launch_nt<32, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+  return launch_nt<32, 2, 2, 2, 4, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
 }
 
 }  // namespace
