@@ -53,6 +53,8 @@ __device__ __forceinline__ void store_acc(const v16f (&acc)[2][TNW], float* __re
   const int rl = lane / LPR, cl = (lane % LPR) * 4;
   const int col = col0 + wn * W + cl;
   const bool full = col + 4 <= N;
+  __syncthreads();                     // every wave is done with the operand tiles; from here on a wave uses only its
+                                       // own staging block, and the LDS operations of one wave complete in order
 #pragma unroll
   for (int tm = 0; tm < 2; ++tm) {
     const int64_t rbase = row0 + wm * 64 + tm * 32 + rl;
@@ -70,12 +72,14 @@ __device__ __forceinline__ void store_acc(const v16f (&acc)[2][TNW], float* __re
         }
       }
     }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // the staging writes stay behind the previous pass's reads
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int tn = 0; tn < TNW; ++tn)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mine[acc_row(r, lane) * LD + tn * 32 + (lane & 31)] = acc[tm][tn][r];
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // and ahead of this pass's reads
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int64_t row = rbase + i * RPI;

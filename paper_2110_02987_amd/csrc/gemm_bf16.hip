@@ -156,7 +156,9 @@ __device__ __forceinline__ void store_acc(const v16f (&acc)[TM][TN], TC* __restr
 // Epilogue of the NT kernel.  A lane's accumulator values sit in one column, so writing them directly gives
 // 64-byte row pieces (bfloat16).  Each wave instead passes its 32 x (32 TN) accumulator blocks through its own
 // region of LDS and writes whole row pieces with 16-byte stores; the mask operand is read the same way.
-// Must be entered by all four waves, after the last read of the operand tiles (the barriers are block wide).
+// Must be entered by all waves of the block, after the last read of the operand tiles: one block-wide barrier
+// separates those reads from the staging writes.  After it a wave touches only its own region, and the LDS
+// operations of one wave complete in order, so the passes need no further barrier.
 template <int EPI, int TM, int TN, typename TC>
 __device__ __forceinline__ void store_rows(const v16f (&acc)[TM][TN], float* __restrict__ lds, TC* __restrict__ C,
                                            int64_t ldc, int64_t row0, int col0, int64_t M, int N, bool c_vec,
@@ -167,14 +169,15 @@ __device__ __forceinline__ void store_rows(const v16f (&acc)[TM][TN], float* __r
   constexpr int CH = W / E;           // 16-byte pieces per row
   const int lane = threadIdx.x & 63;
   float* mine = lds + (threadIdx.x >> 6) * (32 * LD);
+  __syncthreads();
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
-    __syncthreads();
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mine[acc_row(r, lane) * LD + tn * 32 + (lane & 31)] = acc[tm][tn][r];
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // keeps the compiler from moving the reads above the writes
+    __builtin_amdgcn_wave_barrier();
     static_assert((32 * CH) % 64 == 0, "whole wave passes");
 #pragma unroll
     for (int it = 0; it < 32 * CH / 64; ++it) {
@@ -221,6 +224,8 @@ __device__ __forceinline__ void store_rows(const v16f (&acc)[TM][TN], float* __r
           if (col + q < N) cp[q] = from_f32<TC>(v[q]);
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // the next pass writes what this one read
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
@@ -319,6 +324,83 @@ __global__ __launch_bounds__(64 * WM * WN, WM * WN == 4 ? 2 : 1) void gemm_nt_ke
     }
     if (done) break;
   }
+  store_rows<EPI, TM, TN, TC>(acc, reinterpret_cast<float*>(smem_raw), C, ldc, row0 + wm * 32 * TM, col0 + wn * 32 * TN,
+                              M, N, c_vec, slope, aux, ldaux, aux_vec);
+}
+
+// ---- NT, wide outputs: operand tiles straight from global memory into LDS ------------------------------------
+// Block tile 128 x 256, 2 x 2 waves of 64 x 128, 32-deep tiles in the swizzled layout kSwz32, THREE tiles in LDS.
+// The tiles are filled by global_load_lds_dwordx4: a wave instruction moves 64 16-byte pieces from 64 global
+// addresses into 1 KB of LDS (piece of lane l at byte 16 l of the region), without passing through registers.
+// Region r of a tile holds tile rows 16 r .. 16 r + 15; slot 4 (row % 16) + pos of the region holds chunk
+// pos ^ ((row >> 2) & 3) of that row -- the swizzle is applied to the address a lane fetches from.  A tile is 24
+// regions (8 of A, 16 of Bt); wave w moves regions w, w + 4, .., w + 20 (two of A, four of Bt per tile).
+// Two tiles are in flight while one is multiplied: at the top of step kt a wave waits until at most one tile's
+// worth of its own loads (6) is outstanding -- tile kt has landed -- then the block barrier makes every wave's
+// share of tile kt visible and shows that everyone is done with tile kt - 1, whose memory tile kt + 2 then
+// overwrites.  The compiler does not order LDS reads behind these loads; the explicit wait counts do.
+// Steps past the last tile fetch tile 0 again into memory nobody reads, so every step issues the same six loads.
+// Conditions (checked by the launcher): K a multiple of 32, 16-byte aligned rows of A and Bt, N >= 256.
+// Rows of A past M and rows of Bt past N are fetched from the last valid row; their products land in
+// accumulators that the epilogue does not store.
+constexpr int kDmaBK = 32;
+constexpr int kDmaStages = 3;
+
+template <int WM, int WN, int TM, int TN, int EPI, typename TC>
+__global__ __launch_bounds__(64 * WM * WN, WM * WN == 4 ? 2 : 1) void gemm_nt_dma_kernel(
+    const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ Bt, int64_t ldb, TC* __restrict__ C,
+    int64_t ldc, int64_t M, int N, int K, bool c_vec, float slope, const bf16_t* __restrict__ aux, int64_t ldaux,
+    bool aux_vec, int tiles_n, int64_t total) {
+  constexpr int NW = WM * WN, BM = 32 * WM * TM, BN = 32 * WN * TN;
+  constexpr int RA = BM / 16, RB = BN / 16;                   // 1 KB regions of a tile's A part and Bt part
+  constexpr int LA = RA / NW, LB = RB / NW;                  // regions (= loads) per wave and tile
+  static_assert(RA % NW == 0 && RB % NW == 0, "whole regions per wave");
+  constexpr int TILE = (BM + BN) * kDmaBK;                   // elements of one tile
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);        // [3][TILE]: rows 0..BM-1 = A, then BN rows of Bt
+  const int t = threadIdx.x, w = t >> 6, lane = t & 63, wm = w / WN, wn = w % WN;
+  const int64_t item = xcd_order(blockIdx.x, total);
+  const int64_t row0 = (item / tiles_n) * BM;
+  const int col0 = (int)(item % tiles_n) * BN;
+  v16f acc[TM][TN];
+  zero_acc<TM, TN>(acc);
+
+  // the global addresses this lane fetches from at k = 0: regions w, w + NW, .. of the A part, then of the Bt part
+  const bf16_t* src[LA + LB];
+#pragma unroll
+  for (int j = 0; j < LA + LB; ++j) {
+    const bool is_a = j < LA;
+    const int row = ((is_a ? j : j - LA) * NW + w) * 16 + (lane >> 2);      // tile row inside its part
+    const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+    if (is_a) {
+      const int64_t r = row0 + row < M ? row0 + row : M - 1;
+      src[j] = A + r * lda + chunk * 8;
+    } else {
+      const int r = col0 + row < N ? col0 + row : N - 1;
+      src[j] = Bt + (int64_t)r * ldb + chunk * 8;
+    }
+  }
+  const int n_kt = K / kDmaBK;
+  auto issue = [&](int tile) {
+    const int koff = (tile < n_kt ? tile : 0) * kDmaBK;
+    unsigned char* dst = smem_raw + (tile % kDmaStages) * (TILE * 2) + w * 1024;
+#pragma unroll
+    for (int j = 0; j < LA + LB; ++j) {
+      const int region = j < LA ? j * NW : RA + (j - LA) * NW;       // + w, already in dst
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + koff),
+                                       (__attribute__((address_space(3))) void*)(dst + region * 1024), 16, 0, 0);
+    }
+  };
+  issue(0);
+  issue(1);
+  for (int kt = 0; kt < n_kt; ++kt) {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (LA + LB));          // vmcnt(LA + LB): this wave's share of tile kt is in LDS
+    __builtin_amdgcn_s_barrier();
+    issue(kt + 2);
+    const bf16_t* cur = smem + (kt % kDmaStages) * TILE;
+    mma_tile<kDmaBK, TM, TN, kSwz32>(cur, cur + BM * kDmaBK, wm * 32 * TM, wn * 32 * TN, acc);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);                        // vmcnt(0): the two trailing fetches have landed too
   store_rows<EPI, TM, TN, TC>(acc, reinterpret_cast<float*>(smem_raw), C, ldc, row0 + wm * 32 * TM, col0 + wn * 32 * TN,
                               M, N, c_vec, slope, aux, ldaux, aux_vec);
 }
@@ -485,13 +567,51 @@ int launch_nt(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C
   return GAD_OK;
 }
 
-// GAD_NT_WIDE in the environment picks the kernel for outputs of 256 columns or more: 0 = 128 x 256 blocks of four
-// waves with 32-deep tiles, 1 (default) = 256 x 256 blocks of eight waves with 64-deep tiles, 2 = the same with
-// 32-deep tiles.
+template <int WM, int WN, int TM, int TN, typename TC>
+int launch_nt_dma(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
+                  const Epi& e, hipStream_t s) {
+  constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN, NT = 64 * WM * WN;
+  constexpr size_t tiles_bytes = (size_t)kDmaStages * (BM + BN) * kDmaBK * sizeof(bf16_t);
+  constexpr size_t stage_bytes = (size_t)(WM * WN) * 32 * (32 * TN + 8) * sizeof(float);
+  constexpr size_t smem = tiles_bytes > stage_bytes ? tiles_bytes : stage_bytes;
+  static_assert((WM * WN == 4 ? 2 : 1) * smem <= 160 * 1024, "the blocks of a CU fit its LDS");
+  const int tiles_n = (int)ceil_div(N, BN);
+  const int64_t total = ceil_div(M, BM) * tiles_n;
+  GAD_GRID_CHECK(total, NT);
+  const bf16_t* aux = static_cast<const bf16_t*>(e.aux);
+  const bool cv = (ldc % (16 / (int)sizeof(TC)) == 0) && ((reinterpret_cast<uintptr_t>(C) & 15u) == 0);
+  const bool xv = aux != nullptr && vec_ok(aux, e.ldaux);
+#define GAD_DMA_LAUNCH(EPI)                                                                                         \
+  {                                                                                                                 \
+    auto kern = gemm_nt_dma_kernel<WM, WN, TM, TN, EPI, TC>;                                                        \
+    static std::atomic<bool> attr_set;                                                                              \
+    if (!attr_set.load(std::memory_order_acquire)) {                                                                \
+      GAD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,  \
+                                  (int)smem));                                                                      \
+      attr_set.store(true, std::memory_order_release);                                                              \
+    }                                                                                                               \
+    kern<<<(unsigned)total, NT, smem, s>>>(A, lda, Bt, ldb, C, ldc, M, N, K, cv, e.slope, aux, e.ldaux, xv,         \
+                                           tiles_n, total);                                                         \
+  }
+  switch (e.kind) {
+    case EPI_NONE: GAD_DMA_LAUNCH(EPI_NONE) break;
+    case EPI_RELU: GAD_DMA_LAUNCH(EPI_RELU) break;
+    case EPI_MASK: GAD_DMA_LAUNCH(EPI_MASK) break;
+    default: return set_error(GAD_ERR_UNSUPPORTED, "unknown epilogue %d", e.kind);
+  }
+#undef GAD_DMA_LAUNCH
+  GAD_LAUNCH_CHECK();
+  return GAD_OK;
+}
+
+// GAD_NT_WIDE in the environment picks the kernel for outputs of 256 columns or more.  Tiles staged through
+// registers: 0 = 128 x 256 blocks of four waves, 32-deep tiles; 1 = 256 x 256 blocks of eight waves, 64-deep tiles;
+// 2 = the same with 32-deep tiles.  Tiles loaded straight into LDS (K a multiple of 32, aligned rows; else 0 is
+// used): 3 = 128 x 256 blocks of four waves, 4 (default) = 256 x 256 blocks of eight waves.
 int nt_wide_variant() {
   static const int v = [] {
     const char* e = getenv("GAD_NT_WIDE");
-    return e ? atoi(e) : 1;
+    return e ? atoi(e) : 4;
   }();
   return v;
 }
@@ -503,6 +623,10 @@ int nt_typed(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C,
   if (N <= 64) return launch_nt<64, 2, 2, 2, 1, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   if (N <= 128) return launch_nt<64, 2, 2, 2, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   const int v = N >= 256 ? nt_wide_variant() : 0;
+  if (v >= 3 && M >= 1 && K % kDmaBK == 0 && vec_ok(A, lda) && vec_ok(Bt, ldb)) {
+    if (v == 4) return launch_nt_dma<2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+    return launch_nt_dma<2, 2, 2, 4, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+  }
   if (v == 1) return launch_nt<64, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   if (v == 2) return launch_nt<32, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   return launch_nt<32, 2, 2, 2, 4, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
