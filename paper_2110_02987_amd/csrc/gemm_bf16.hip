@@ -84,14 +84,15 @@ __device__ __forceinline__ uint4 keep_first(uint4 v, int n_valid) {
 //   kSwz32    32-deep tiles without padding (64-byte rows), chunk c of row r at position c ^ ((r >> 2) & 3): the
 //             16-byte reads of 16 consecutive rows and the staging writes of 4 consecutive rows each cover 16
 //             different 16-byte slots of a 256-byte window (the padded 80-byte stride made the writes collide).
-enum Layout : int { kPadded = 0, kSwzTn = 1, kSwz32 = 2 };
+enum Layout : int { kPadded = 0, kSwzTn = 1, kSwz32 = 2, kSwz64 = 3 };   // kSwz64: unpadded 128-byte rows, chunk ^ (row & 7)
 template <int BK, int MODE>
-constexpr int tile_ld() { return MODE == kSwz32 ? BK : BK + 8; }
+constexpr int tile_ld() { return MODE == kSwz32 || MODE == kSwz64 ? BK : BK + 8; }
 
 // Offset (in elements) of 16-byte chunk `chunk` of tile row `row`; LDK = row stride.
 template <int LDK, int MODE>
 __device__ __forceinline__ int tile_off(int row, int chunk) {
-  const int c = MODE == kSwzTn ? (chunk ^ ((row >> 4) & 7)) : MODE == kSwz32 ? (chunk ^ ((row >> 2) & 3)) : chunk;
+  const int c = MODE == kSwzTn ? (chunk ^ ((row >> 4) & 7)) : MODE == kSwz32 ? (chunk ^ ((row >> 2) & 3))
+                : MODE == kSwz64 ? (chunk ^ (row & 7)) : chunk;
   return row * LDK + (c << 3);
 }
 
@@ -329,30 +330,34 @@ __global__ __launch_bounds__(64 * WM * WN, WM * WN == 4 ? 2 : 1) void gemm_nt_ke
 }
 
 // ---- NT, wide outputs: operand tiles straight from global memory into LDS ------------------------------------
-// Block tile 128 x 256, 2 x 2 waves of 64 x 128, 32-deep tiles in the swizzled layout kSwz32, THREE tiles in LDS.
 // The tiles are filled by global_load_lds_dwordx4: a wave instruction moves 64 16-byte pieces from 64 global
-// addresses into 1 KB of LDS (piece of lane l at byte 16 l of the region), without passing through registers.
-// Region r of a tile holds tile rows 16 r .. 16 r + 15; slot 4 (row % 16) + pos of the region holds chunk
-// pos ^ ((row >> 2) & 3) of that row -- the swizzle is applied to the address a lane fetches from.  A tile is 24
-// regions (8 of A, 16 of Bt); wave w moves regions w, w + 4, .., w + 20 (two of A, four of Bt per tile).
-// Two tiles are in flight while one is multiplied: at the top of step kt a wave waits until at most one tile's
-// worth of its own loads (6) is outstanding -- tile kt has landed -- then the block barrier makes every wave's
-// share of tile kt visible and shows that everyone is done with tile kt - 1, whose memory tile kt + 2 then
-// overwrites.  The compiler does not order LDS reads behind these loads; the explicit wait counts do.
-// Steps past the last tile fetch tile 0 again into memory nobody reads, so every step issues the same six loads.
-// Conditions (checked by the launcher): K a multiple of 32, 16-byte aligned rows of A and Bt, N >= 256.
+// addresses into 1 KB of LDS (the piece of lane l lands at byte 16 l of the region), without passing through
+// registers.  A 1 KB region holds 16 tile rows of a 32-deep tile (64-byte rows, layout kSwz32) or 8 rows of a
+// 64-deep tile (128-byte rows, whole cache lines, layout kSwz64); the swizzle is applied to the address a lane
+// fetches from: the slot at position pos of a row holds chunk pos ^ ((row >> 2) & 3), or pos ^ (row & 7).
+// A tile is (BM + BN) / 16 (or / 8) regions, the A part first; wave w moves regions w, w + NW, .. of each part.
+// kDmaStages tiles live in LDS; all but one are in flight while one is multiplied: at the top of step kt a wave
+// waits until at most stages - 2 tiles' worth of its own loads are outstanding -- tile kt has landed -- then the
+// block barrier makes every wave's share of tile kt visible and shows that everyone is done with tile kt - 1,
+// whose memory the tile requested next overwrites.  The compiler does not order LDS reads behind these loads; the
+// explicit wait counts do.  Steps past the last tile fetch tile 0 again into memory nobody reads, so every step
+// issues the same number of loads.
+// Conditions (checked by the launcher): K a multiple of the tile depth, 16-byte aligned rows of A and Bt, N >= 256.
 // Rows of A past M and rows of Bt past N are fetched from the last valid row; their products land in
 // accumulators that the epilogue does not store.
-constexpr int kDmaBK = 32;
-constexpr int kDmaStages = 3;
-
-template <int WM, int WN, int TM, int TN, int EPI, typename TC>
+// Measured on 4.2 M x 512 x 512 (forward): 256 x 256 blocks of eight waves with two 64-deep tiles 2.95 ms, with
+// three 32-deep tiles 3.07 ms, 128 x 256 blocks of four waves (two per CU) with three 32-deep tiles 3.17 ms; the
+// register-staged kernel above 3.45 ms.
+template <int kDmaBK, int kDmaStages, int WM, int WN, int TM, int TN, int EPI, typename TC>
 __global__ __launch_bounds__(64 * WM * WN, WM * WN == 4 ? 2 : 1) void gemm_nt_dma_kernel(
     const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ Bt, int64_t ldb, TC* __restrict__ C,
     int64_t ldc, int64_t M, int N, int K, bool c_vec, float slope, const bf16_t* __restrict__ aux, int64_t ldaux,
     bool aux_vec, int tiles_n, int64_t total) {
   constexpr int NW = WM * WN, BM = 32 * WM * TM, BN = 32 * WN * TN;
-  constexpr int RA = BM / 16, RB = BN / 16;                   // 1 KB regions of a tile's A part and Bt part
+  constexpr int MODE = kDmaBK == 32 ? kSwz32 : kSwz64;
+  constexpr int RR = 512 / kDmaBK;                           // tile rows per 1 KB region (16 or 8)
+  constexpr int CPR = kDmaBK / 8;                            // 16-byte chunks per tile row (4 or 8)
+  constexpr int RA = BM / RR, RB = BN / RR;                  // 1 KB regions of a tile's A part and Bt part
   constexpr int LA = RA / NW, LB = RB / NW;                  // regions (= loads) per wave and tile
   static_assert(RA % NW == 0 && RB % NW == 0, "whole regions per wave");
   constexpr int TILE = (BM + BN) * kDmaBK;                   // elements of one tile
@@ -370,8 +375,8 @@ __global__ __launch_bounds__(64 * WM * WN, WM * WN == 4 ? 2 : 1) void gemm_nt_dm
 #pragma unroll
   for (int j = 0; j < LA + LB; ++j) {
     const bool is_a = j < LA;
-    const int row = ((is_a ? j : j - LA) * NW + w) * 16 + (lane >> 2);      // tile row inside its part
-    const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+    const int row = ((is_a ? j : j - LA) * NW + w) * RR + lane / CPR;       // tile row inside its part
+    const int chunk = kDmaBK == 32 ? (lane & 3) ^ ((row >> 2) & 3) : (lane & 7) ^ (row & 7);
     if (is_a) {
       const int64_t r = row0 + row < M ? row0 + row : M - 1;
       src[j] = A + r * lda + chunk * 8;
@@ -391,14 +396,15 @@ __global__ __launch_bounds__(64 * WM * WN, WM * WN == 4 ? 2 : 1) void gemm_nt_dm
                                        (__attribute__((address_space(3))) void*)(dst + region * 1024), 16, 0, 0);
     }
   };
-  issue(0);
-  issue(1);
+#pragma unroll
+  for (int d = 0; d < kDmaStages - 1; ++d) issue(d);
   for (int kt = 0; kt < n_kt; ++kt) {
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (LA + LB));          // vmcnt(LA + LB): this wave's share of tile kt is in LDS
+    // vmcnt((stages - 2) tiles): this wave's share of tile kt is in LDS
+    __builtin_amdgcn_s_waitcnt(0x0F70 | ((kDmaStages - 2) * (LA + LB)));
     __builtin_amdgcn_s_barrier();
-    issue(kt + 2);
+    issue(kt + kDmaStages - 1);
     const bf16_t* cur = smem + (kt % kDmaStages) * TILE;
-    mma_tile<kDmaBK, TM, TN, kSwz32>(cur, cur + BM * kDmaBK, wm * 32 * TM, wn * 32 * TN, acc);
+    mma_tile<kDmaBK, TM, TN, MODE>(cur, cur + BM * kDmaBK, wm * 32 * TM, wn * 32 * TN, acc);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);                        // vmcnt(0): the two trailing fetches have landed too
   store_rows<EPI, TM, TN, TC>(acc, reinterpret_cast<float*>(smem_raw), C, ldc, row0 + wm * 32 * TM, col0 + wn * 32 * TN,
@@ -567,7 +573,7 @@ int launch_nt(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C
   return GAD_OK;
 }
 
-template <int WM, int WN, int TM, int TN, typename TC>
+template <int kDmaBK, int kDmaStages, int WM, int WN, int TM, int TN, typename TC>
 int launch_nt_dma(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
                   const Epi& e, hipStream_t s) {
   constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN, NT = 64 * WM * WN;
@@ -583,7 +589,7 @@ int launch_nt_dma(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, T
   const bool xv = aux != nullptr && vec_ok(aux, e.ldaux);
 #define GAD_DMA_LAUNCH(EPI)                                                                                         \
   {                                                                                                                 \
-    auto kern = gemm_nt_dma_kernel<WM, WN, TM, TN, EPI, TC>;                                                        \
+    auto kern = gemm_nt_dma_kernel<kDmaBK, kDmaStages, WM, WN, TM, TN, EPI, TC>;                                                        \
     static std::atomic<bool> attr_set;                                                                              \
     if (!attr_set.load(std::memory_order_acquire)) {                                                                \
       GAD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,  \
@@ -606,12 +612,13 @@ int launch_nt_dma(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, T
 
 // GAD_NT_WIDE in the environment picks the kernel for outputs of 256 columns or more.  Tiles staged through
 // registers: 0 = 128 x 256 blocks of four waves, 32-deep tiles; 1 = 256 x 256 blocks of eight waves, 64-deep tiles;
-// 2 = the same with 32-deep tiles.  Tiles loaded straight into LDS (K a multiple of 32, aligned rows; else 0 is
-// used): 3 = 128 x 256 blocks of four waves, 4 (default) = 256 x 256 blocks of eight waves.
+// 2 = the same with 32-deep tiles.  Tiles loaded straight into LDS (aligned rows, K a multiple of the tile depth;
+// else the next variant that fits is used): 3 = 128 x 256 blocks of four waves, three 32-deep tiles; 4 = 256 x 256
+// blocks of eight waves, three 32-deep tiles; 6 (default) = 256 x 256 blocks, two 64-deep tiles.
 int nt_wide_variant() {
   static const int v = [] {
     const char* e = getenv("GAD_NT_WIDE");
-    return e ? atoi(e) : 4;
+    return e ? atoi(e) : 6;
   }();
   return v;
 }
@@ -623,9 +630,10 @@ int nt_typed(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C,
   if (N <= 64) return launch_nt<64, 2, 2, 2, 1, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   if (N <= 128) return launch_nt<64, 2, 2, 2, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   const int v = N >= 256 ? nt_wide_variant() : 0;
-  if (v >= 3 && M >= 1 && K % kDmaBK == 0 && vec_ok(A, lda) && vec_ok(Bt, ldb)) {
-    if (v == 4) return launch_nt_dma<2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
-    return launch_nt_dma<2, 2, 2, 4, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+  if (v >= 3 && M >= 1 && K % 32 == 0 && vec_ok(A, lda) && vec_ok(Bt, ldb)) {
+    if (v == 6 && K % 64 == 0) return launch_nt_dma<64, 2, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+    if (v >= 4) return launch_nt_dma<32, 3, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+    return launch_nt_dma<32, 3, 2, 2, 2, 4, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   }
   if (v == 1) return launch_nt<64, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   if (v == 2) return launch_nt<32, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
