@@ -39,6 +39,7 @@ SHAPES_W = [  # M, K, N, lda, ldc
     (640, 64, 600, 72, 600), (300, 4096, 64, 4096, 64), (200, 48, 4096, 48, 4096),      # the widest K and N accepted
     (300_001, 100, 256, 112, 256), (270_003, 47, 200, 48, 208),                        # tall enough for the 256-row tile
     (1000, 96, 300, 96, 304), (100_003, 512, 512, 512, 512), (77, 32, 256, 40, 256),   # wide outputs, K in whole 32-deep tiles
+    (1, 64, 256, 64, 256), (500, 64, 301, 64, 301), (255, 128, 4096, 128, 4096),       # one row; unaligned output rows; widest
 ]
 
 

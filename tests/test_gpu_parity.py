@@ -476,6 +476,61 @@ def test_workspace_state(gad):
     gad.workspace_forget(ws)
 
 
+def test_layer_events_and_workspace_table_bound(gad):
+    """gad_gcn_layer_events: the passes record the caller's events at their layer boundaries (in order, all of them,
+    and nothing once switched off).  The table of remembered forwards is bounded: after more than 1024 other
+    workspaces the oldest forward is forgotten (its backward is refused), the newest still there."""
+    import ctypes as C
+    hip = C.CDLL("libamdhip64.so")
+    cfg = wl.CONFIGS["tiny"]
+    g, _ = build_both(gad, wl.make_graph(cfg))
+    dims = (16, 24, 8, 5)
+    L = len(dims) - 1
+    Xd = dev(wl.make_features(cfg.n, dims[0]))
+    Wd = [dev(w) for w in wl.make_weights(dims)]
+    yd = dev(wl.make_labels(cfg.n, dims[-1]))
+    ws = gad.alloc_workspace(g, dims)
+    dW = [torch.empty_like(w) for w in Wd]
+    ev = []
+    for _ in range(2 * L + 3):
+        e = C.c_void_p()
+        assert hip.hipEventCreate(C.byref(e)) == 0
+        ev.append(e)
+    gad.gcn_layer_events([e.value for e in ev])
+    gad.gcn_forward(g, Xd, dims, Wd, yd, None, 1.0, ws)
+    gad.gcn_backward(g, Xd, dims, Wd, ws, dW)
+    torch.cuda.synchronize()
+    ms = C.c_float()
+    for i in list(range(0, L + 1)) + list(range(L + 2, 2 * L + 2)):          # consecutive marks of one pass
+        assert hip.hipEventElapsedTime(C.byref(ms), ev[i], ev[i + 1]) == 0 and ms.value >= 0.0
+    assert hip.hipEventElapsedTime(C.byref(ms), ev[0], ev[2 * L + 2]) == 0 and ms.value > 0.0
+    gad.gcn_layer_events([])                                                  # off: a fresh event stays unrecorded
+    fresh = C.c_void_p()
+    assert hip.hipEventCreate(C.byref(fresh)) == 0
+    gad.gcn_forward(g, Xd, dims, Wd, yd, None, 1.0, ws)
+    torch.cuda.synchronize()
+    assert hip.hipEventQuery(fresh) == 0                                      # never recorded: reports "complete"
+    for e in ev + [fresh]:
+        hip.hipEventDestroy(e)
+    # table bound
+    small = (4, 3)
+    Xs, Ws = dev(wl.make_features(cfg.n, 4)), [dev(wl.make_weights(small)[0])]
+    ys = dev(wl.make_labels(cfg.n, 3))
+    nbytes = gad.gcn_workspace_bytes(g, small)
+    pool = torch.empty((1030, (nbytes + 255) // 256 * 256), dtype=torch.uint8, device="cuda")
+    for k in range(1030):
+        gad.gcn_forward(g, Xs, small, Ws, ys, None, 1.0, pool[k])
+    dWs = [torch.empty_like(Ws[0])]
+    with pytest.raises(gad.GadError) as e:
+        gad.gcn_backward(g, Xs, small, Ws, pool[0], dWs)
+    assert e.value.status == -9
+    gad.gcn_backward(g, Xs, small, Ws, pool[1029], dWs)
+    torch.cuda.synchronize()
+    assert torch.isfinite(dWs[0]).all()
+    for k in range(1030):
+        gad.workspace_forget(pool[k])
+
+
 # ------------------------------------------------------------------------------------------ GAD-Optimizer
 
 @pytest.mark.parametrize("name,F", [("tiny", 128), ("products_small", 100), ("products_small", 47), ("tiny", 1),
