@@ -234,10 +234,8 @@ __device__ __forceinline__ void store_rows(const v16f (&acc)[TM][TN], float* __r
 // WM x WN waves per block, each owning TM x TN accumulator blocks of 32 x 32: block tile BM x BN =
 // (32 WM TM) x (32 WN TN).  Work item = (row tile, column tile) with the column tile fastest, so the blocks
 // that share a row tile of A follow each other on one XCD.  Bt has ldb = K rounded up to BK, zero filled.
-// Two shapes are used: 2 x 2 waves of 64 x (32 TN) for outputs up to 255 columns (two or three blocks per CU), and
-// 2 x 4 waves of 128 x 64 (a 256 x 256 block, one per CU) for wider outputs: per matrix instruction it reads
-// 40 % fewer operand bytes from LDS and stages a third fewer, and a wave runs 32 (64-deep tiles) matrix
-// instructions between barriers instead of 16.
+// Used with 2 x 2 waves of 64 x (32 TN): two or three blocks per CU.  (A 256 x 256 block of 2 x 4 waves on this
+// kernel was measured, too: not faster than 128 x 256; the wide outputs have a kernel of their own below.)
 // FAST: A may be fetched in aligned 16-byte pieces (16-byte aligned rows; a piece that straddles column K reads
 // padding inside the row, which the caller must have declared readable).  Its loads are unconditional (a piece outside the matrix is fetched from the matrix's
 // first bytes; what lies outside is zeroed when the piece is staged), so the compiler can count the loads in
@@ -345,9 +343,9 @@ __global__ __launch_bounds__(64 * WM * WN, WM * WN == 4 ? 2 : 1) void gemm_nt_ke
 // Conditions (checked by the launcher): K a multiple of the tile depth, 16-byte aligned rows of A and Bt, N >= 256.
 // Rows of A past M and rows of Bt past N are fetched from the last valid row; their products land in
 // accumulators that the epilogue does not store.
-// Measured on 4.2 M x 512 x 512 (forward): 256 x 256 blocks of eight waves with two 64-deep tiles 2.95 ms, with
-// three 32-deep tiles 3.07 ms, 128 x 256 blocks of four waves (two per CU) with three 32-deep tiles 3.17 ms; the
-// register-staged kernel above 3.45 ms.
+// Used with 256 x 256 blocks of eight waves (2 x 4 waves of 128 x 64).  Measured on 4.2 M x 512 x 512 (forward):
+// two 64-deep tiles 2.95 ms, three 32-deep tiles 3.07 ms, 128 x 256 blocks of four waves (two per CU) with three
+// 32-deep tiles 3.17 ms; the register-staged kernel above 3.45 ms.
 template <int kDmaBK, int kDmaStages, int WM, int WN, int TM, int TN, int EPI, typename TC>
 __global__ __launch_bounds__(64 * WM * WN, WM * WN == 4 ? 2 : 1) void gemm_nt_dma_kernel(
     const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ Bt, int64_t ldb, TC* __restrict__ C,
@@ -610,33 +608,27 @@ int launch_nt_dma(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, T
   return GAD_OK;
 }
 
-// GAD_NT_WIDE in the environment picks the kernel for outputs of 256 columns or more.  Tiles staged through
-// registers: 0 = 128 x 256 blocks of four waves, 32-deep tiles; 1 = 256 x 256 blocks of eight waves, 64-deep tiles;
-// 2 = the same with 32-deep tiles.  Tiles loaded straight into LDS (aligned rows, K a multiple of the tile depth;
-// else the next variant that fits is used): 3 = 128 x 256 blocks of four waves, three 32-deep tiles; 4 = 256 x 256
-// blocks of eight waves, three 32-deep tiles; 6 (default) = 256 x 256 blocks, two 64-deep tiles.
-int nt_wide_variant() {
-  static const int v = [] {
+// GAD_NT_WIDE=0 in the environment keeps outputs of 256 columns or more on the register-staged kernel.
+bool nt_wide_direct() {
+  static const bool on = [] {
     const char* e = getenv("GAD_NT_WIDE");
-    return e ? atoi(e) : 6;
+    return !(e && e[0] == '0');
   }();
-  return v;
+  return on;
 }
 
 template <typename TC>
 int nt_typed(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C, int64_t ldc, int64_t M, int N, int K,
              const Epi& e, hipStream_t s) {
-  // Narrow outputs: 64-deep tiles, two or three blocks per CU.
+  // Narrow outputs: 64-deep tiles staged through registers, two or three blocks per CU.
   if (N <= 64) return launch_nt<64, 2, 2, 2, 1, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   if (N <= 128) return launch_nt<64, 2, 2, 2, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
-  const int v = N >= 256 ? nt_wide_variant() : 0;
-  if (v >= 3 && M >= 1 && K % 32 == 0 && vec_ok(A, lda) && vec_ok(Bt, ldb)) {
-    if (v == 6 && K % 64 == 0) return launch_nt_dma<64, 2, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
-    if (v >= 4) return launch_nt_dma<32, 3, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
-    return launch_nt_dma<32, 3, 2, 2, 2, 4, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+  // Wide outputs: 256 x 256 blocks, tiles loaded straight into LDS -- two 64-deep tiles when K allows, else three
+  // 32-deep ones; unaligned rows or a ragged K stay on the register-staged kernel (128 x 256 blocks, 32-deep tiles).
+  if (N >= 256 && nt_wide_direct() && M >= 1 && K % 32 == 0 && vec_ok(A, lda) && vec_ok(Bt, ldb)) {
+    if (K % 64 == 0) return launch_nt_dma<64, 2, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+    return launch_nt_dma<32, 3, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   }
-  if (v == 1) return launch_nt<64, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
-  if (v == 2) return launch_nt<32, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   return launch_nt<32, 2, 2, 2, 4, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
 }
 
