@@ -208,6 +208,12 @@ bool overlap_enabled() {
 
 using namespace gad;
 
+// The launch checks of the library read the runtime's last-error slot, which keeps an error of ANY earlier HIP call
+// on the thread until somebody reads it -- also one that the caller's framework handled itself (an allocator that
+// ran out of memory, freed its cache and tried again).  Every entry point that launches work empties the slot first,
+// so that what it reports is its own.
+#define GAD_ENTER() (void)hipGetLastError()
+
 extern "C" {
 
 const char* gad_last_error(void) { return g_error; }
@@ -215,6 +221,7 @@ const char* gad_last_error(void) { return g_error; }
 int gad_build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges_in, int64_t n_global,
                        const int64_t* local_ids, int64_t n_local, const int64_t* halo_ids, int64_t n_halo,
                        void* hip_stream, gad_graph** out) {
+  GAD_ENTER();
   if (!out) return set_error(GAD_ERR_NULL, "out is NULL");
   *out = nullptr;
   if (n_edges_in < 0 || n_local < 0 || n_halo < 0 || n_global < 1)
@@ -245,6 +252,7 @@ int gad_graph_info(const gad_graph* g, int64_t* n, int64_t* n_local, int64_t* nn
 }
 
 int gad_graph_concat(const gad_graph* const* graphs, int K, void* hip_stream, gad_graph** out) {
+  GAD_ENTER();
   if (!out) return set_error(GAD_ERR_NULL, "out is NULL");
   *out = nullptr;
   if (!graphs) return set_error(GAD_ERR_NULL, "graphs is NULL");
@@ -273,6 +281,7 @@ int gad_graph_destroy(gad_graph* g) {
 int gad_augment_subgraph(const gad_graph* G, const int64_t* part_rows, int64_t n_part, int32_t walk_len, int64_t budget,
                          uint64_t seed, int64_t max_walks, int64_t* halo_rows_out, int64_t* n_halo_out,
                          int64_t* n_walks_out, void* hip_stream) {
+  GAD_ENTER();
   if (!G || !n_halo_out) return set_error(GAD_ERR_NULL, "graph or n_halo_out is NULL");
   *n_halo_out = 0;
   if (n_part < 1 || n_part > G->n) return set_error(GAD_ERR_SHAPE, "n_part = %lld outside [1, n]", (long long)n_part);
@@ -299,6 +308,7 @@ static int forward_impl(const gad_graph* g, const void* X, gad_dtype dtype, int 
                         const float* const* W, const int32_t* labels, const uint8_t* mask, float loss_scale,
                         const float* row_scale, float negative_slope, void* workspace, size_t workspace_bytes,
                         float* logits_out, double* loss_out, void* hip_stream, bool reuse_first) {
+  GAD_ENTER();
   Plan p;
   int st = make_plan(g, L, dims, dtype, &p);
   if (st != GAD_OK) return st;
@@ -393,6 +403,7 @@ int gad_gcn_forward_cached(const gad_graph* g, const void* X, gad_dtype dtype, i
 int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, const int32_t* dims,
                      const float* const* W, float negative_slope, void* workspace, size_t workspace_bytes,
                      float* const* dW, float* const* G_out, void* hip_stream) {
+  GAD_ENTER();
   Plan p;
   int st = make_plan(g, L, dims, dtype, &p);
   if (st != GAD_OK) return st;
@@ -489,6 +500,7 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
 
 int gad_gcn_activation(const gad_graph* g, const void* workspace, size_t workspace_bytes, int L,
                        const int32_t* dims, gad_dtype dtype, int layer, float* out, void* hip_stream) {
+  GAD_ENTER();
   Plan p;
   int st = make_plan(g, L, dims, dtype, &p);
   if (st != GAD_OK) return st;
@@ -510,6 +522,7 @@ int gad_spmm_workspace_bytes(const gad_graph* g, int32_t width, size_t* bytes) {
 
 int gad_spmm(const gad_graph* g, const void* T, int64_t ldt, void* out, int64_t ldo, int32_t width, gad_dtype dtype,
              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  GAD_ENTER();
   if (!g || !T || !out) return set_error(GAD_ERR_NULL, "graph, T or out is NULL");
   if (width < 1 || width > kMaxWidth || ldt < width || ldo < width)
     return set_error(GAD_ERR_SHAPE, "width outside [1, %d] or a leading dimension < width", kMaxWidth);
@@ -540,6 +553,7 @@ int gad_gemm_workspace_bytes(int64_t M, int32_t K, int32_t N, size_t* bytes) {
 
 int gad_gemm_w(const void* A, int64_t lda, const float* W, int32_t w_rows, int32_t w_cols, int transpose_w, void* C,
                int64_t ldc, int64_t M, gad_dtype dtype, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  GAD_ENTER();
   const int32_t K = transpose_w ? w_cols : w_rows, N = transpose_w ? w_rows : w_cols;
   int st = gemm_args(M, K, N, dtype);
   if (st != GAD_OK) return st;
@@ -553,6 +567,7 @@ int gad_gemm_w(const void* A, int64_t lda, const float* W, int32_t w_rows, int32
 
 int gad_gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, float* C, int64_t M, int32_t K, int32_t N,
                 gad_dtype dtype, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  GAD_ENTER();
   int st = gemm_args(M, K, N, dtype);
   if (st != GAD_OK) return st;
   if (!A || !G || !C || !workspace) return set_error(GAD_ERR_NULL, "A, G, C or workspace is NULL");
@@ -567,6 +582,7 @@ int gad_gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, float* C
 
 int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta, double* out3,
                           float* per_node_out, void* hip_stream) {
+  GAD_ENTER();
   if (!g || !V || !out3) return set_error(GAD_ERR_NULL, "graph, V or out3 is NULL");
   if (F < 1 || F > kMaxWidth) return set_error(GAD_ERR_SHAPE, "F = %d outside [1, %d]", F, kMaxWidth);
   if (!(beta > 0.0) || !isfinite(beta)) return set_error(GAD_ERR_SHAPE, "beta must be positive and finite");
@@ -576,6 +592,7 @@ int gad_subgraph_variance(const gad_graph* g, const void* V, int32_t F, gad_dtyp
 
 int gad_subgraph_variance_static(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta, double* out3,
                                  float* per_node_out, void* hip_stream) {
+  GAD_ENTER();
   if (!g || !V || !out3) return set_error(GAD_ERR_NULL, "graph, V or out3 is NULL");
   if (F < 1) return set_error(GAD_ERR_SHAPE, "F = %d must be positive", F);
   if (!(beta > 0.0) || !isfinite(beta)) return set_error(GAD_ERR_SHAPE, "beta must be positive and finite");
@@ -592,6 +609,7 @@ int gad_pair_importance_workspace_bytes(const gad_graph* g, int32_t F, size_t* b
 
 int gad_pair_importance(const gad_graph* g, const void* V, int32_t F, gad_dtype dtype, double beta, double* out2,
                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+  GAD_ENTER();
   if (!g || !V || !out2 || !workspace) return set_error(GAD_ERR_NULL, "graph, V, out2 or workspace is NULL");
   if (F < 1 || F > kMaxWidth) return set_error(GAD_ERR_SHAPE, "F = %d outside [1, %d]", F, kMaxWidth);
   if (!(beta > 0.0) || !isfinite(beta)) return set_error(GAD_ERR_SHAPE, "beta must be positive and finite");
@@ -622,6 +640,7 @@ static int consensus_weights(const float* const* bufs, int K, const double* zeta
 
 int gad_weighted_consensus(const float* const* bufs, int K, const double* zeta, int64_t n_elems, float* out,
                            void* hip_stream) {
+  GAD_ENTER();
   if (!out) return set_error(GAD_ERR_NULL, "out is NULL");
   double w[kMaxConsensus];
   int st = consensus_weights(bufs, K, zeta, n_elems, w);
@@ -631,6 +650,7 @@ int gad_weighted_consensus(const float* const* bufs, int K, const double* zeta, 
 
 int gad_consensus_update(const float* const* grads, int K, const double* zeta, int64_t n_elems, float eta,
                          float* params, float* avg_out, void* hip_stream) {
+  GAD_ENTER();
   if (!params) return set_error(GAD_ERR_NULL, "params is NULL");
   if (!isfinite(eta)) return set_error(GAD_ERR_SHAPE, "eta is not finite");
   double w[kMaxConsensus];
@@ -646,6 +666,7 @@ int gad_train_round(int K, const gad_graph* const* graphs, const void* const* X,
                     const float* loss_scales, float negative_slope, void* const* workspaces,
                     const size_t* workspace_bytes, float* grads, const double* zeta, float eta, double* losses,
                     int x_unchanged, void* hip_stream) {
+  GAD_ENTER();
   if (K < 1 || K > kMaxConsensus) return set_error(GAD_ERR_SHAPE, "K = %d outside [1, %d]", K, kMaxConsensus);
   if (!graphs || !X || !dims || !params || !labels || !loss_scales || !workspaces || !workspace_bytes || !grads || !zeta)
     return set_error(GAD_ERR_NULL, "a required argument is NULL");
@@ -683,6 +704,7 @@ int gad_train_round_batched(const gad_graph* g, const void* X, gad_dtype dtype, 
                             const int32_t* labels, const uint8_t* mask, const float* row_scale, float negative_slope,
                             void* workspace, size_t workspace_bytes, float* grad, float eta, double* loss,
                             int x_unchanged, void* hip_stream) {
+  GAD_ENTER();
   if (!dims || !params || !grad) return set_error(GAD_ERR_NULL, "dims, params or grad is NULL");
   if (L < 1 || L > kMaxLayers) return set_error(GAD_ERR_SHAPE, "L = %d outside [1, %d]", L, kMaxLayers);
   if (!isfinite(eta)) return set_error(GAD_ERR_SHAPE, "eta is not finite");

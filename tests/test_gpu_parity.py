@@ -476,6 +476,30 @@ def test_workspace_state(gad):
     gad.workspace_forget(ws)
 
 
+def test_foreign_hip_error_is_not_reported_as_ours(gad):
+    """An error of somebody else's HIP call that was handled there (here: an allocation request far beyond the
+    device, refused by the runtime) stays in the runtime's last-error slot; the library's launch checks must not
+    take it for a failure of their own."""
+    import ctypes as C
+    hip = C.CDLL("libamdhip64.so")
+    cfg = wl.CONFIGS["tiny"]
+    g, ref = build_both(gad, wl.make_graph(cfg))
+    T = wl.make_features(cfg.n, 24)
+    Td, out = dev(T), torch.empty((cfg.n, 24), device="cuda")
+    out3 = torch.zeros(3, dtype=torch.float64, device="cuda")
+    sws = gad.spmm_workspace(g, 24)
+    torch.cuda.synchronize()
+    p = C.c_void_p()
+    assert hip.hipMalloc(C.byref(p), C.c_size_t(1 << 60)) != 0          # refused; nothing was allocated
+    gad.spmm(g, Td, out, workspace=sws)                                 # (torch's own next launch would trip over it)
+    torch.cuda.synchronize()
+    assert rel_err(out.cpu().numpy(), T1.spmm(ref, T.astype(np.float64))) < TOL
+    assert hip.hipMalloc(C.byref(p), C.c_size_t(1 << 60)) != 0
+    gad.subgraph_variance(g, Td, 1.0, out3)
+    torch.cuda.synchronize()
+    assert out3[0].item() > 0
+
+
 def test_layer_events_and_workspace_table_bound(gad):
     """gad_gcn_layer_events: the passes record the caller's events at their layer boundaries (in order, all of them,
     and nothing once switched off).  The table of remembered forwards is bounded: after more than 1024 other
