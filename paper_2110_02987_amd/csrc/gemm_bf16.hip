@@ -15,10 +15,14 @@
 // these writes are conflict free as well.  Because the same order of the contraction index is used for both
 // operands, the result does not depend on which 8 indices a lane holds.
 //
-// Four wave64s per block in a 2 x 2 arrangement; a wave owns TM x TN accumulators of 32 x 32.  The next
-// tile (NT) or two tiles (TN) are on their way from global memory into registers while the current one is
-// multiplied (double-buffered LDS, one barrier per tile).  Blocks are renumbered so that the blocks sharing an operand tile run on the same XCD
-// (consecutive workgroup ids go to different XCDs, each with an L2 of its own).
+// Three kernels.  gemm_nt_kernel (outputs below 256 columns, and any shape whose rows are not 16-byte aligned or
+// whose K is not a multiple of 32) and gemm_tn_kernel: four wave64s per block in a 2 x 2 arrangement, a wave owns
+// TM x TN accumulators of 32 x 32; the next tile (NT) or two tiles (TN) are on their way from global memory into
+// registers while the current one is multiplied (double-buffered LDS, one barrier per tile).  gemm_nt_dma_kernel
+// (outputs of 256 columns or more): 256 x 256 blocks of eight waves whose operand tiles go from global memory
+// straight into LDS, all tiles but the one being multiplied in flight.  Blocks are renumbered so that the blocks
+// sharing an operand tile run on the same XCD (consecutive workgroup ids go to different XCDs, each with an L2 of
+// its own).
 #include <stdlib.h>
 
 #include <atomic>
