@@ -344,9 +344,11 @@ __global__ __launch_bounds__(64 * WM * WN, WM * WN == 4 ? 2 : 1) void gemm_nt_ke
 // whose memory the tile requested next overwrites.  The compiler does not order LDS reads behind these loads; the
 // explicit wait counts do.  Steps past the last tile fetch tile 0 again into memory nobody reads, so every step
 // issues the same number of loads.
-// Conditions (checked by the launcher): K a multiple of the tile depth, 16-byte aligned rows of A and Bt, N >= 256.
+// Conditions (checked by the launcher): K a whole number of 16-byte chunks, 16-byte aligned rows of A and Bt, N >= 256.
 // Rows of A past M and rows of Bt past N are fetched from the last valid row; their products land in
-// accumulators that the epilogue does not store.
+// accumulators that the epilogue does not store.  K need not be a whole number of tiles: Bt is zero filled up to
+// whole tiles, and a lane whose chunk of A lies past column K fetches the row's first chunk instead (finite data
+// times zero).
 // Used with 256 x 256 blocks of eight waves (2 x 4 waves of 128 x 64).  Measured on 4.2 M x 512 x 512 (forward):
 // two 64-deep tiles 2.95 ms, three 32-deep tiles 3.07 ms, 128 x 256 blocks of four waves (two per CU) with three
 // 32-deep tiles 3.17 ms; the register-staged kernel above 3.45 ms.
@@ -372,29 +374,33 @@ __global__ __launch_bounds__(64 * WM * WN, WM * WN == 4 ? 2 : 1) void gemm_nt_dm
   v16f acc[TM][TN];
   zero_acc<TM, TN>(acc);
 
-  // the global addresses this lane fetches from at k = 0: regions w, w + NW, .. of the A part, then of the Bt part
+  // the rows this lane fetches from (regions w, w + NW, .. of the A part, then of the Bt part) and its chunk in them
   const bf16_t* src[LA + LB];
+  int coff[LA + LB];
 #pragma unroll
   for (int j = 0; j < LA + LB; ++j) {
     const bool is_a = j < LA;
     const int row = ((is_a ? j : j - LA) * NW + w) * RR + lane / CPR;       // tile row inside its part
     const int chunk = kDmaBK == 32 ? (lane & 3) ^ ((row >> 2) & 3) : (lane & 7) ^ (row & 7);
+    coff[j] = chunk * 8;
     if (is_a) {
       const int64_t r = row0 + row < M ? row0 + row : M - 1;
-      src[j] = A + r * lda + chunk * 8;
+      src[j] = A + r * lda;
     } else {
       const int r = col0 + row < N ? col0 + row : N - 1;
-      src[j] = Bt + (int64_t)r * ldb + chunk * 8;
+      src[j] = Bt + (int64_t)r * ldb;
     }
   }
-  const int n_kt = K / kDmaBK;
+  const int n_kt = (K + kDmaBK - 1) / kDmaBK;
   auto issue = [&](int tile) {
     const int koff = (tile < n_kt ? tile : 0) * kDmaBK;
     unsigned char* dst = smem_raw + (tile % kDmaStages) * (TILE * 2) + w * 1024;
 #pragma unroll
     for (int j = 0; j < LA + LB; ++j) {
       const int region = j < LA ? j * NW : RA + (j - LA) * NW;       // + w, already in dst
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + koff),
+      int col = koff + coff[j];
+      if (j < LA && col >= K) col = 0;                               // past the end of A's rows: see above
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + col),
                                        (__attribute__((address_space(3))) void*)(dst + region * 1024), 16, 0, 0);
     }
   };
@@ -627,10 +633,11 @@ int nt_typed(const bf16_t* A, int64_t lda, const bf16_t* Bt, int64_t ldb, TC* C,
   // Narrow outputs: 64-deep tiles staged through registers, two or three blocks per CU.
   if (N <= 64) return launch_nt<64, 2, 2, 2, 1, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   if (N <= 128) return launch_nt<64, 2, 2, 2, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
-  // Wide outputs: 256 x 256 blocks, tiles loaded straight into LDS -- two 64-deep tiles when K allows, else three
-  // 32-deep ones; unaligned rows or a ragged K stay on the register-staged kernel (128 x 256 blocks, 32-deep tiles).
-  if (N >= 256 && nt_wide_direct() && M >= 1 && K % 32 == 0 && vec_ok(A, lda) && vec_ok(Bt, ldb)) {
-    if (K % 64 == 0) return launch_nt_dma<64, 2, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
+  // Wide outputs: 256 x 256 blocks, tiles loaded straight into LDS -- two 64-deep tiles (three 32-deep ones for
+  // K <= 32); unaligned rows, or a K that is not a whole number of 16-byte chunks, stay on the register-staged kernel
+  // (128 x 256 blocks, 32-deep tiles).  Bt is zero filled up to a multiple of 64, which covers either tile depth.
+  if (N >= 256 && nt_wide_direct() && M >= 1 && K % 8 == 0 && vec_ok(A, lda) && vec_ok(Bt, ldb)) {
+    if (K > 32) return launch_nt_dma<64, 2, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
     return launch_nt_dma<32, 3, 2, 4, 4, 2, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);
   }
   return launch_nt<32, 2, 2, 2, 4, TC>(A, lda, Bt, ldb, C, ldc, M, N, K, e, s);

@@ -40,6 +40,7 @@ SHAPES_W = [  # M, K, N, lda, ldc
     (300_001, 100, 256, 112, 256), (270_003, 47, 200, 48, 208),                        # tall enough for the 256-row tile
     (1000, 96, 300, 96, 304), (100_003, 512, 512, 512, 512), (77, 32, 256, 40, 256),   # wide outputs, K in whole 32-deep tiles
     (1, 64, 256, 64, 256), (500, 64, 301, 64, 301), (255, 128, 4096, 128, 4096),       # one row; unaligned output rows; widest
+    (300, 40, 256, 40, 256), (300, 8, 256, 8, 256), (515, 200, 260, 200, 264),         # K not in whole tiles on the wide path
 ]
 
 
