@@ -145,35 +145,63 @@ __global__ void assign_rows(const int64_t* __restrict__ local_ids, int64_t n_loc
 }
 
 // keys[0..n) = self loops; kept pairs are appended behind them (two keys each) through counter[0].
+// A block takes kEmitItems * kThreads consecutive pairs and reserves the room for all its keys with ONE atomic add
+// (an add per wave made the single counter the bottleneck: 2 M serialised atomics for 134 M pairs).  Where a pair's
+// keys land depends on the order of those adds; the sort that follows makes the result independent of it.
+constexpr int kEmitItems = 8;
+
 __global__ __launch_bounds__(kThreads) void emit_keys(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
                                                      int64_t n_edges, int64_t n_global,
                                                      const int32_t* __restrict__ lut, int64_t n, int bits,
                                                      uint64_t* __restrict__ keys, uint32_t* __restrict__ counter) {
-  const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (e < n) keys[e] = ((uint64_t)e << bits) | (uint64_t)e;
-  bool valid = false;
-  uint64_t r = 0, c = 0;
-  if (e < n_edges) {
-    int64_t a = src[e], b = dst[e];
-    if (a >= 0 && a < n_global && b >= 0 && b < n_global) {
-      int32_t ra = lut[a], rb = lut[b];
-      valid = ra >= 0 && rb >= 0 && ra != rb;
-      r = (uint64_t)(uint32_t)ra;
-      c = (uint64_t)(uint32_t)rb;
+  static_assert(kThreads == 256, "four waves per block");
+  __shared__ uint32_t wave_count[kEmitItems][4];
+  __shared__ uint32_t block_base;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t first = (int64_t)blockIdx.x * (kEmitItems * kThreads);
+  uint64_t r[kEmitItems], c[kEmitItems];
+  uint32_t rank[kEmitItems];                 // position among the kept pairs of this wave and item
+  bool valid[kEmitItems];
+#pragma unroll
+  for (int i = 0; i < kEmitItems; ++i) {
+    const int64_t e = first + (int64_t)i * kThreads + threadIdx.x;
+    if (e < n) keys[e] = ((uint64_t)e << bits) | (uint64_t)e;
+    valid[i] = false;
+    r[i] = c[i] = 0;
+    if (e < n_edges) {
+      const int64_t a = src[e], b = dst[e];
+      if (a >= 0 && a < n_global && b >= 0 && b < n_global) {
+        const int32_t ra = lut[a], rb = lut[b];
+        valid[i] = ra >= 0 && rb >= 0 && ra != rb;
+        r[i] = (uint64_t)(uint32_t)ra;
+        c[i] = (uint64_t)(uint32_t)rb;
+      }
     }
+    const uint64_t m = __ballot(valid[i]);
+    rank[i] = (uint32_t)__popcll(m & lanemask_lt());
+    if (lane == 0) wave_count[i][wave] = (uint32_t)__popcll(m);
   }
-  const uint64_t m = __ballot(valid);
-  if (m == 0) return;
-  const int lane = threadIdx.x & 63;
-  const int leader = __ffsll((unsigned long long)m) - 1;
-  uint32_t base = 0;
-  if (lane == leader) base = atomicAdd(counter, 2u * (uint32_t)__popcll(m));
-  base = __shfl(base, leader, 64);
-  if (valid) {
-    const uint32_t rank = (uint32_t)__popcll(m & lanemask_lt());
-    uint64_t* o = keys + n + base + 2u * rank;
-    o[0] = (r << bits) | c;
-    o[1] = (c << bits) | r;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t total = 0;
+#pragma unroll
+    for (int i = 0; i < kEmitItems; ++i)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t cnt = wave_count[i][w];
+        wave_count[i][w] = total;            // exclusive offset of (item, wave) inside the block
+        total += cnt;
+      }
+    block_base = total ? atomicAdd(counter, 2u * total) : 0u;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kEmitItems; ++i) {
+    if (valid[i]) {
+      uint64_t* o = keys + n + block_base + 2u * (wave_count[i][wave] + rank[i]);
+      o[0] = (r[i] << bits) | c[i];
+      o[1] = (c[i] << bits) | r[i];
+    }
   }
 }
 
@@ -551,7 +579,7 @@ int build_subgraph(const int64_t* src, const int64_t* dst, int64_t n_edges, int6
   GAD_HIP(scratch.alloc(&keys_b, (size_t)max_keys));
   {
     const int64_t work = n_edges > n ? n_edges : n;
-    emit_keys<<<(unsigned)ceil_div(work, kThreads), kThreads, 0, s>>>(src, dst, n_edges, n_global, lut, n, bits, keys_a,
+    emit_keys<<<(unsigned)ceil_div(work, kEmitItems * kThreads), kThreads, 0, s>>>(src, dst, n_edges, n_global, lut, n, bits, keys_a,
                                                                       flags + 2);
     GAD_LAUNCH_CHECK();
   }
