@@ -36,7 +36,23 @@ def _step(gad, name, bf16=False):
     mask = wl.make_mask(cfg)
     f = check_step(gad, g, ref, X, Ws, y, mask, 1.0 / mask.sum(), dims, bf16=bf16)
     progress(f"[{name}] step parity ok in {time.time() - t0:.1f}s, loss={f['loss']:.6f}, bf16={bf16}")
+    spmm_fixed_point(gad, g, max(dims[1:-1]), bf16)
+    progress(f"[{name}] standalone SpMM fixed point ok at width {max(dims[1:-1])}")
     return cfg, g, ref, X, f
+
+
+def spmm_fixed_point(gad, g, width, bf16):
+    """The standalone sparse product (the launch bench.py times, at the width it times): sqrt(1 + deg) is an
+    eigenvector of A~ with eigenvalue 1, so a matrix whose columns are multiples of it must come back unchanged --
+    a property of the definition that needs no oracle and holds at any size."""
+    d = torch.sqrt(g.deg().to(torch.float64) + 1.0)
+    T = (d[:, None] * (1.0 + torch.arange(width, device="cuda", dtype=torch.float64) / width)[None, :])
+    Td = T.to(torch.bfloat16 if bf16 else torch.float32).contiguous()
+    out = torch.empty_like(Td)
+    gad.spmm(g, Td, out, width, 1 if bf16 else 0)
+    torch.cuda.synchronize()
+    err = ((out.to(torch.float64) - T).abs() / T).max().item()
+    assert err < (1e-2 if bf16 else 1e-5), err
 
 
 def test_reddit_shaped_partition(gad):
@@ -207,4 +223,5 @@ def test_rmat22_skew_stress_bf16(gad):
             assert rel_err(G_prev[rows], exp) < TOL_BF16, f"G[{l - 1}]"
             G_l = G_prev
             progress(f"[{name}] backward rows of layer {l} ok")
-    progress(f"[{name}] done in {time.time() - t0:.1f}s")
+    spmm_fixed_point(gad, g, 512, True)
+    progress(f"[{name}] standalone SpMM fixed point ok at width 512; done in {time.time() - t0:.1f}s")
