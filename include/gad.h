@@ -14,6 +14,9 @@
  *    gad_graph objects (create / destroy pair) and scratch memory that lives inside one call.
  *    The calls that allocate or free device memory (gad_build_subgraph, gad_graph_concat, gad_augment_subgraph,
  *    gad_graph_destroy) must not run while a stream of the process is being captured into a HIP graph.
+ *    Everything else only enqueues kernels and may be captured, after ONE un-captured call of the same kind and
+ *    shapes on the device: the first use of a kernel sets its attributes and the first backward creates the
+ *    library's side stream and events, which does not belong inside a capture.
  *    A graph is read-only to every call except gad_subgraph_variance, which uses a reduction buffer inside
  *    the graph: variance calls on ONE graph from different streams must not overlap.
  *  - All calls enqueue work on `hip_stream` (a hipStream_t, NULL = default stream) and return
