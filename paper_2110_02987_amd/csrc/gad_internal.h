@@ -126,8 +126,12 @@ int gemm_w(const void* A, int64_t lda, gad_dtype ta, const float* W, int w_rows,
 size_t bf16_weight_elems(int n_out, int k);      // elements of the bfloat16 copy of an [n_out x k] right operand
 int gemm_w_bf16(const void* A, int64_t lda, const float* W, int w_rows, int w_cols, bool trans_w, void* C, int64_t ldc,
                 gad_dtype tc, int64_t M, const Epi& epi, void* scratch, hipStream_t s);
+// Output shapes for which the 256 x 256 weight-gradient tiles are worth their padding; ..._wide_ok adds the alignment
+// conditions of that kernel.  `wide` selects it; the slabs must then come from the wide split.
+inline bool tn_wide_shape(int K, int N) { return K >= 192 && N >= 192; }
+bool gemm_tn_bf16_wide_ok(const void* A, int64_t lda, const void* G, int64_t ldg, int K, int N, bool full_rows);
 int gemm_tn_bf16(const void* A, int64_t lda, const void* G, int64_t ldg, float* partials, int64_t M, int K, int N,
-                 int n_slabs, int64_t slab_rows, bool full_rows, hipStream_t s);
+                 int n_slabs, int64_t slab_rows, bool full_rows, bool wide, hipStream_t s);
 // C[K x N] (ldc) = A[M x K]^T * G[M x N]; `partials` must hold gemm_tn_partial_floats(M, K, N) floats.
 size_t gemm_tn_partial_floats(int64_t M, int K, int N);
 int gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, gad_dtype t, float* C, int64_t ldc, int64_t M,

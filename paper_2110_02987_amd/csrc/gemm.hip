@@ -260,13 +260,14 @@ bool vec_ok(const T* p, int64_t ld) {
 // instructions on padding), else 128.
 inline int block_cols(int N) { return N <= 64 ? 64 : 128; }
 
-void tn_split(int64_t M, int K, int N, int* n_slabs, int64_t* slab_rows) {
-  const int64_t tiles = ceil_div(K, BM) * ceil_div(N, block_cols(N));
-  int64_t want = ceil_div(512, tiles);                // ~2 blocks per CU over the whole grid
+// wide: the bfloat16 kernel with 256 x 256 output tiles, one block per CU.
+void tn_split(int64_t M, int K, int N, bool wide, int* n_slabs, int64_t* slab_rows) {
+  const int64_t tiles = wide ? ceil_div(K, 256) * ceil_div(N, 256) : ceil_div(K, BM) * ceil_div(N, block_cols(N));
+  int64_t want = ceil_div(wide ? 256 : 512, tiles);   // one block (wide) or ~2 blocks per CU over the whole grid
   const int64_t max_slabs = ceil_div(M, 512);         // at least 512 reduction rows per slab
   if (want > max_slabs) want = max_slabs;
   if (want < 1) want = 1;
-  *slab_rows = round_up(ceil_div(M, want), 64);       // whole tiles of either kernel (16 or 64 rows)
+  *slab_rows = round_up(ceil_div(M, want), 64);       // whole tiles of every kernel (16 or 64 rows)
   *n_slabs = (int)ceil_div(M, *slab_rows);
 }
 
@@ -311,7 +312,7 @@ int gemm_tn_f32(const float* A, int64_t lda, const float* G, int64_t ldg, float*
                 float* partials, hipStream_t s) {
   int n_slabs;
   int64_t slab_rows;
-  tn_split(M, K, N, &n_slabs, &slab_rows);
+  tn_split(M, K, N, false, &n_slabs, &slab_rows);
   const int tiles_n = (int)ceil_div(N, block_cols(N));
   const dim3 grid((unsigned)(ceil_div(K, BM) * tiles_n), (unsigned)n_slabs);
   // every slab of the partial products starts on a 16-byte boundary when K N is a multiple of 4
@@ -354,20 +355,22 @@ int gemm_w(const void* A, int64_t lda, gad_dtype ta, const float* W, int w_rows,
 }
 
 size_t gemm_tn_partial_floats(int64_t M, int K, int N) {
-  int n_slabs;
+  int n_slabs, n_wide = 0;
   int64_t slab_rows;
-  tn_split(M, K, N, &n_slabs, &slab_rows);
-  return (size_t)n_slabs * (size_t)K * (size_t)N;
+  tn_split(M, K, N, false, &n_slabs, &slab_rows);
+  if (tn_wide_shape(K, N)) tn_split(M, K, N, true, &n_wide, &slab_rows);   // whichever kernel ends up running
+  return (size_t)(n_slabs > n_wide ? n_slabs : n_wide) * (size_t)K * (size_t)N;
 }
 
 int gemm_tn(const void* A, int64_t lda, const void* G, int64_t ldg, gad_dtype t, float* C, int64_t ldc, int64_t M,
             int K, int N, float* partials, bool full_rows, hipStream_t s) {
   if (K == 0 || N == 0) return GAD_OK;
   if (t == GAD_F32) return gemm_tn_f32((const float*)A, lda, (const float*)G, ldg, C, ldc, M, K, N, partials, s);
+  const bool wide = gemm_tn_bf16_wide_ok(A, lda, G, ldg, K, N, full_rows);
   int n_slabs;
   int64_t slab_rows;
-  tn_split(M, K, N, &n_slabs, &slab_rows);
-  int st = gemm_tn_bf16(A, lda, G, ldg, partials, M, K, N, n_slabs, slab_rows, full_rows, s);
+  tn_split(M, K, N, wide, &n_slabs, &slab_rows);
+  int st = gemm_tn_bf16(A, lda, G, ldg, partials, M, K, N, n_slabs, slab_rows, full_rows, wide, s);
   if (st != GAD_OK) return st;
   const int64_t elems = (int64_t)K * N;
   reduce_slabs<<<(unsigned)ceil_div(elems, 32), 256, 0, s>>>(partials, n_slabs, elems, N, C, ldc);

@@ -525,6 +525,124 @@ __global__ __launch_bounds__(256, 2) void gemm_tn_kernel(const bf16_t* __restric
   store_acc<EPI_NONE, 2, 2, float>(acc, Pslab, N, k0 + wm * 64, n0 + wn * 64, K, N, 0.f, nullptr, 0);
 }
 
+// ---- TN, tiles loaded straight into LDS -----------------------------------------------------------
+// Output tile 256 x 256 of K x N by eight waves (2 x 4 of 128 x 64), so that a block reads each row of A and G once
+// per 256 output columns / rows instead of once per 128.  A tile is kTwBK rows of A and of G, 256 columns each,
+// row-major as in memory: 512-byte rows, the A part first; a 1 KB region is two tile rows, wave w moves regions w,
+// w + 8, .. of each part, and kTwStages tiles live in LDS (all but one in flight while that one is multiplied; waits
+// as in the NT kernel).  The matrix instruction wants, per lane, 8 consecutive reduction rows of one column; the transposing LDS
+// read delivers exactly that from a row-major tile: within 16 lanes, lane t points at the 8 bytes of row t / 4, columns
+// 4 (t % 4) .. + 3, and lane i receives column i of those four rows.  Two such reads make one operand.
+// Bank conflicts: the 64 lanes of one read touch 4 rows x 2 (reduction halves) x 32 columns, and rows are 512 bytes
+// apart, so the 16-byte chunk c of tile row r is kept at position c ^ (4 (r & 3) + 16 ((r >> 3) & 1)) -- applied, as
+// in the NT kernel, to the address a lane fetches from; the read then covers all 32 slots of a 512-byte window once.
+// Conditions (checked by the launcher): 16-byte aligned rows of A and G, no 16-byte piece reaching past the end of an
+// allocated row, slabs of whole tiles.  Rows past the end of the last slab are fetched from row M - 1 and zeroed in
+// LDS before they are multiplied; column chunks past K or N are fetched from column 0 and feed only accumulators that
+// are not stored.
+// Measured on 4.2 M x 512 x 512 (the 128 x 128 kernel above: 4.12 ms): tiles of 64 rows, two in LDS 2.71 ms; tiles of
+// 32 rows, two, three or four in LDS 3.01 - 3.03 ms (the number in flight does not matter, the barriers per row do);
+// twice as many slabs (two blocks' worth of work per CU instead of one) 2.74 ms.
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8 read_tr8(const unsigned char* p) {
+  // rows r .. r + 3 and r + 4 .. r + 7 of the lane's column: two transposing reads 4 tile rows (2 KB) apart
+  const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(p));
+  const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(p + 4 * 512));
+  typedef short v8s __attribute__((ext_vector_type(8)));
+  const v8s both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+template <int kTwBK, int kTwStages>
+__global__ __launch_bounds__(512, 1) void gemm_tn_dma_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                            const bf16_t* __restrict__ G, int64_t ldg,
+                                                            float* __restrict__ P, int64_t M, int K, int N,
+                                                            int64_t slab_rows, int tiles_n, int tiles, int64_t total,
+                                                            bool p_vec) {
+  constexpr int kTwPart = kTwBK * 256;                       // elements of a tile's A part (and of its G part)
+  constexpr int NW = 8, TM = 4, TN = 2, LP = kTwBK / 16;     // LP: regions (= loads) per wave, part and tile
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int t = threadIdx.x, w = t >> 6, lane = t & 63, wm = w >> 2, wn = w & 3;
+  const int64_t item = xcd_order(blockIdx.x, total);
+  const int tile = (int)(item % tiles);
+  const int64_t slab = item / tiles;
+  const int k0 = (tile / tiles_n) * 256;    // output row block (columns of A)
+  const int n0 = (tile % tiles_n) * 256;    // output column block (columns of G)
+  const int64_t m_begin = slab * slab_rows;
+  const int64_t m_end = m_begin + slab_rows < M ? m_begin + slab_rows : M;
+  const int n_mt = (int)((m_end - m_begin + kTwBK - 1) / kTwBK);
+  v16f acc[TM][TN];
+  zero_acc<TM, TN>(acc);
+
+  // what this lane fetches: tile row 2 (w + 8 j) + lane / 32 of each part, the chunk that belongs in slot lane % 32
+  const int frow = 2 * w + (lane >> 5);                      // its tile row in load j is frow + 16 j
+  const int fchunk = (lane & 31) ^ (((frow & 3) << 2) | (((frow >> 3) & 1) << 4));
+  int col_a = k0 + fchunk * 8, col_g = n0 + fchunk * 8;
+  if (col_a >= K) col_a = 0;
+  if (col_g >= N) col_g = 0;
+  auto issue = [&](int mt) {
+    const int64_t m0 = m_begin + (int64_t)(mt < n_mt ? mt : 0) * kTwBK + frow;
+    unsigned char* dst = smem_raw + (mt % kTwStages) * (2 * kTwPart * 2) + w * 1024;
+#pragma unroll
+    for (int j = 0; j < 2 * LP; ++j) {
+      const bool is_a = j < LP;
+      int64_t row = m0 + 16 * (is_a ? j : j - LP);
+      row = row < M ? row : M - 1;
+      const bf16_t* src = is_a ? A + row * lda + col_a : G + row * ldg + col_g;
+      const int region = is_a ? j * NW : kTwBK / 2 + (j - LP) * NW;   // + w, already in dst
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)(dst + region * 1024), 16, 0, 0);
+    }
+  };
+
+  // what this lane reads: see above; g16 = which 16 columns of the 32, kg = which 8 of the 16 reduction rows
+  const int t16 = lane & 15, g16 = (lane >> 4) & 1, kg = lane >> 5;
+  const int swz = ((t16 >> 2) << 2) | (kg << 4);             // of tile rows 8 kg + t16 / 4 (+ 4, + 16 ks)
+  const int low = (2 * g16 + ((t16 & 3) >> 1)) * 16 + (t16 & 1) * 8 + (8 * kg + (t16 >> 2)) * 512;
+  int off_a[TM], off_g[TN];                                  // byte offsets inside a part, reduction row 0
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) off_a[tm] = (((wm * 128 + tm * 32) >> 3) ^ swz) * 16 + low;
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn) off_g[tn] = (((wn * 64 + tn * 32) >> 3) ^ swz) * 16 + low + kTwPart * 2;
+
+#pragma unroll
+  for (int d = 0; d < kTwStages - 1; ++d) issue(d);
+  for (int mt = 0; mt < n_mt; ++mt) {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | ((kTwStages - 2) * 2 * LP));   // this wave's share of tile mt is in LDS
+    __builtin_amdgcn_s_barrier();
+    unsigned char* cur = smem_raw + (mt % kTwStages) * (2 * kTwPart * 2);
+    const int64_t valid = m_end - (m_begin + (int64_t)mt * kTwBK);
+    if (valid < kTwBK) {                                     // the same for every thread; only a slab's last tile
+      const int first = (int)valid;                          // rows first .. 63 of both parts
+      for (int p = t; p < (kTwBK - first) * 32; p += 512) {
+        *reinterpret_cast<uint4*>(cur + first * 512 + p * 16) = make_uint4(0u, 0u, 0u, 0u);
+        *reinterpret_cast<uint4*>(cur + kTwPart * 2 + first * 512 + p * 16) = make_uint4(0u, 0u, 0u, 0u);
+      }
+      __syncthreads();
+    }
+    issue(mt + kTwStages - 1);
+#pragma unroll
+    for (int ks = 0; ks < kTwBK / 16; ++ks) {
+      bf16x8 a[TM], b[TN];
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm) a[tm] = read_tr8(cur + off_a[tm] + ks * 16 * 512);
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) b[tn] = read_tr8(cur + off_g[tn] + ks * 16 * 512);
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);                        // the trailing fetch has landed before LDS is reused
+  float* Pslab = P + slab * (int64_t)K * N;
+  store_rows<EPI_NONE, TM, TN, float>(acc, reinterpret_cast<float*>(smem_raw), Pslab, N, k0 + wm * 128, n0 + wn * 64, K,
+                                      N, p_vec, 0.f, nullptr, 0, false);
+}
+
 // out[r][c] (leading dimension ld_out) = transpose ? W[c][r] : W[r][c], rounded to bfloat16; zero for
 // out_cols <= c < ld_out.  W is row-major with w_cols columns.
 __global__ void weights_to_bf16(const float* __restrict__ W, int w_cols, bool transpose, bf16_t* __restrict__ out,
@@ -661,11 +779,46 @@ int gemm_w_bf16(const void* A, int64_t lda, const float* W, int w_rows, int w_co
   return nt_typed<float>(a, lda, Bt, ldb, static_cast<float*>(C), ldc, M, N, K, e, s);
 }
 
+bool gemm_tn_bf16_wide_ok(const void* A, int64_t lda, const void* G, int64_t ldg, int K, int N, bool full_rows) {
+  static const bool on = [] {                                // GAD_TN_WIDE=0 keeps every shape on the 128 x 128 kernel
+    const char* e = getenv("GAD_TN_WIDE");
+    return !(e && e[0] == '0');
+  }();
+  return on && tn_wide_shape(K, N) && vec_ok(static_cast<const bf16_t*>(A), lda) &&
+         vec_ok(static_cast<const bf16_t*>(G), ldg) && (full_rows || (K % 8 == 0 && N % 8 == 0));
+}
+
 int gemm_tn_bf16(const void* A, int64_t lda, const void* G, int64_t ldg, float* partials, int64_t M, int K, int N,
-                 int n_slabs, int64_t slab_rows, bool full_rows, hipStream_t s) {
-  constexpr size_t smem = 2u * 2u * 128u * TLDK * sizeof(bf16_t);
+                 int n_slabs, int64_t slab_rows, bool full_rows, bool wide, hipStream_t s) {
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* g = static_cast<const bf16_t*>(G);
+  if (wide) {
+    constexpr int kTwBK = 64, kTwStages = 2;
+    constexpr size_t tiles_bytes = (size_t)kTwStages * 2 * kTwBK * 256 * sizeof(bf16_t);
+    constexpr size_t stage_bytes = (size_t)8 * 32 * (32 * 2 + 8) * sizeof(float);           // epilogue staging, reuses them
+    constexpr size_t kTwSmem = tiles_bytes > stage_bytes ? tiles_bytes : stage_bytes;
+    static_assert(kTwSmem <= 160 * 1024, "one block's tiles fit the CU's LDS");
+    if (!gemm_tn_bf16_wide_ok(A, lda, G, ldg, K, N, full_rows) || slab_rows % kTwBK != 0 || M < 1)
+      return set_error(GAD_ERR_UNSUPPORTED, "the 256 x 256 weight-gradient kernel does not take these operands");
+    auto kern = gemm_tn_dma_kernel<kTwBK, kTwStages>;
+    static std::atomic<bool> wide_attr_set;          // set once; setting it twice is harmless
+    if (!wide_attr_set.load(std::memory_order_acquire)) {
+      GAD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)kTwSmem));
+      wide_attr_set.store(true, std::memory_order_release);
+    }
+    const int tiles_n = (int)ceil_div(N, 256);
+    const int tiles = (int)ceil_div(K, 256) * tiles_n;
+    const int64_t total = (int64_t)tiles * n_slabs;
+    GAD_GRID_CHECK(total, 512);
+    // every slab of the partial products starts on a 16-byte boundary when K N is a multiple of 4
+    const bool pv = N % 4 == 0 && (reinterpret_cast<uintptr_t>(partials) & 15u) == 0 && ((int64_t)K * N) % 4 == 0;
+    kern<<<(unsigned)total, 512, kTwSmem, s>>>(a, lda, g, ldg, partials, M, K, N, slab_rows, tiles_n,
+                                                             tiles, total, pv);
+    GAD_LAUNCH_CHECK();
+    return GAD_OK;
+  }
+  constexpr size_t smem = 2u * 2u * 128u * TLDK * sizeof(bf16_t);
   const bool av = vec_ok(a, lda), gv = vec_ok(g, ldg);
   const bool fast = av && gv && (full_rows || (K % 8 == 0 && N % 8 == 0));   // no piece may reach past a row's end
   auto kern = fast ? gemm_tn_kernel<true> : gemm_tn_kernel<false>;

@@ -82,6 +82,13 @@ def test_gemm_w_bf16_is_float32_accumulation(gad):
     Gd, _ = bf16_dev(G)
     gad.gemm_tn(Ad, Gd, out, workspace=ws)
     assert np.array_equal(out.cpu().numpy(), A.T @ G)
+    # the same on the 256 x 256 output tiles, with a ragged last tile of rows and of columns
+    M2, K2, N2 = 1000, 264, 320
+    A2 = rng.integers(-8, 9, (M2, K2)).astype(np.float32)
+    G2 = rng.integers(-8, 9, (M2, N2)).astype(np.float32)
+    out2 = torch.empty((K2, N2), device="cuda")
+    gad.gemm_tn(bf16_dev(A2)[0], bf16_dev(G2)[0], out2)
+    assert np.array_equal(out2.cpu().numpy(), A2.T @ G2)
     # gad_gemm_w writes bfloat16: the exact integer product rounded once
     outb = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
     gad.gemm_w(Ad, dev(W), outb, False, ws)
@@ -93,6 +100,9 @@ SHAPES_TN = [  # M, K, N, lda, ldg
     (1, 1, 1, 1, 1), (63, 5, 3, 5, 3), (1000, 47, 65, 48, 80), (70_000, 100, 256, 112, 256), (33_333, 256, 47, 256, 48),
     (5000, 602, 41, 608, 48), (20_000, 128, 512, 128, 512), (9001, 130, 129, 130, 129), (150_000, 64, 16, 64, 16),
     (3000, 4096, 24, 4096, 24), (3000, 24, 4096, 24, 4096),                                # the widest K and N accepted
+    # both K and N of 192 or more: 256 x 256 output tiles (bfloat16); one short slab, ragged tiles, many slabs
+    (70, 256, 256, 256, 256), (1000, 192, 200, 192, 200), (100_003, 512, 512, 512, 512), (20_000, 320, 448, 328, 456),
+    (4097, 264, 1032, 264, 1032), (5000, 250, 256, 256, 256), (5000, 256, 252, 264, 252),  # last two: not in whole chunks
 ]
 
 
