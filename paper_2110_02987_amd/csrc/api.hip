@@ -475,6 +475,7 @@ int gad_gcn_backward(const gad_graph* g, const void* X, gad_dtype dtype, int L, 
       // product (memory) rather than beside another dense product
       if (l > 0 && (st = gemm_w(gcur, ldg, dtype, W[l], fin, fout, true, tmp, ldi, dtype, n, none, wsc, s)) != GAD_OK) break;
       if ((st = weight_grad(at(workspace, p.agg[l]), ldi, gcur, ldg, l)) != GAD_OK) break;
+      dact.shares_gpu = side_busy;
       if (l > 0 && (st = spmm(g, tmp, ldi, dtype, gnext, ldi, dtype, fin, dact, psum, s)) != GAD_OK) break;
     } else {
       if ((st = spmm(g, gcur, ldg, dtype, tmp, ldg, dtype, fout, none, psum, s)) != GAD_OK) break;

@@ -50,6 +50,7 @@ struct Epi {
   const void* aux = nullptr;   // storage type of the kernel's node-matrix input
   int64_t ldaux = 0;
   bool full_rows = false;      // every row of the node-matrix input can be read up to its leading dimension
+  bool shares_gpu = false;     // another kernel runs beside this one (a weight gradient on the side stream)
 };
 
 // Rows longer than this many non-zeros are split into chunks of this size; each chunk is summed by

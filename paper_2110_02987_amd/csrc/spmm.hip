@@ -202,6 +202,8 @@ __global__ __launch_bounds__(256) void spmm_reduce_many(const int64_t* __restric
   }
 }
 
+constexpr unsigned kCapLdsBytes = 32000;      // five blocks (20 waves) per CU out of 160 KB
+
 template <int LPR, int V, typename TI, typename TO>
 int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, int width, const Epi& e, float* partial,
            hipStream_t s) {
@@ -211,7 +213,14 @@ int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, i
   const unsigned row_blocks = (unsigned)ceil_div(g->n_short, 4);
   const unsigned chunk_blocks = (unsigned)ceil_div(g->n_chunks, 4);
   const dim3 grid(chunk_blocks + row_blocks, (unsigned)ceil_div(width, LPR * V));
-  spmm_kernel<LPR, V, TI, TO><<<grid, 256, 0, s>>>(g->rowptr, g->colidx, g->dinv, T, ldt, out, ldo, width, g->n_short,
+  // float32 rows of 129 - 256 columns (1 KB per gathered row): 20 waves per CU finish sooner than the 32 that fit,
+  // presumably because fewer rows in flight push each other out of L2 less often (products_part 4.33 -> 4.21 ms,
+  // whole_graph 16.68 -> 16.50, reddit_part 0.322 -> 0.312; 16 waves: 4.30, 12 waves: 4.62).  Narrower rows need every
+  // slot (width 100: 2.12 -> 2.21 ms at 20 waves), bfloat16 rows of 1 KB gain nothing (30.3 -> 30.9 ms), and two
+  // column slabs lose 0.5 %.  The cap is a reservation of LDS the kernel never touches; it is left off when another
+  // kernel that needs LDS shares the GPU (the weight gradient beside a backward product would have to wait).
+  const unsigned cap_lds = sizeof(TI) == 4 && LPR == 64 && width <= 256 && !e.shares_gpu ? kCapLdsBytes : 0u;
+  spmm_kernel<LPR, V, TI, TO><<<grid, 256, cap_lds, s>>>(g->rowptr, g->colidx, g->dinv, T, ldt, out, ldo, width, g->n_short,
                                                    g->row_order, e.kind, e.slope, aux, e.ldaux, (int)chunk_blocks,
                                                    g->chunk_perm, g->chunk_row, g->chunk_begin, g->n_chunks, partial,
                                                    ldp);
