@@ -526,10 +526,10 @@ __global__ __launch_bounds__(256, 2) void gemm_tn_kernel(const bf16_t* __restric
 }
 
 // ---- TN, tiles loaded straight into LDS -----------------------------------------------------------
-// Output tile 256 x 256 of K x N by eight waves (2 x 4 of 128 x 64), so that a block reads each row of A and G once
+// Output tile 256 x 256 of K x N by WM x WN waves (used: 2 x 4 of 128 x 64), so that a block reads each row of A and G once
 // per 256 output columns / rows instead of once per 128.  A tile is kTwBK rows of A and of G, 256 columns each,
 // row-major as in memory: 512-byte rows, the A part first; a 1 KB region is two tile rows, wave w moves regions w,
-// w + 8, .. of each part, and kTwStages tiles live in LDS (all but one in flight while that one is multiplied; waits
+// w + NW, .. of each part, and kTwStages tiles live in LDS (all but one in flight while that one is multiplied; waits
 // as in the NT kernel).  The matrix instruction wants, per lane, 8 consecutive reduction rows of one column; the transposing LDS
 // read delivers exactly that from a row-major tile: within 16 lanes, lane t points at the 8 bytes of row t / 4, columns
 // 4 (t % 4) .. + 3, and lane i receives column i of those four rows.  Two such reads make one operand.
@@ -542,7 +542,9 @@ __global__ __launch_bounds__(256, 2) void gemm_tn_kernel(const bf16_t* __restric
 // are not stored.
 // Measured on 4.2 M x 512 x 512 (the 128 x 128 kernel above: 4.12 ms): tiles of 64 rows, two in LDS 2.71 ms; tiles of
 // 32 rows, two, three or four in LDS 3.01 - 3.03 ms (the number in flight does not matter, the barriers per row do);
-// twice as many slabs (two blocks' worth of work per CU instead of one) 2.74 ms.
+// twice as many slabs (two blocks' worth of work per CU instead of one) 2.74 ms; four waves of 128 x 128 (WM = WN = 2:
+// 256 accumulator registers per lane, a third fewer operand reads from LDS per matrix instruction, one wave per
+// SIMD) 2.77 ms against 2.66 for the eight waves of 128 x 64 in the same run.
 
 typedef short v4s __attribute__((ext_vector_type(4)));
 
@@ -555,16 +557,18 @@ __device__ __forceinline__ bf16x8 read_tr8(const unsigned char* p) {
   return __builtin_bit_cast(bf16x8, both);
 }
 
-template <int kTwBK, int kTwStages>
-__global__ __launch_bounds__(512, 1) void gemm_tn_dma_kernel(const bf16_t* __restrict__ A, int64_t lda,
-                                                            const bf16_t* __restrict__ G, int64_t ldg,
-                                                            float* __restrict__ P, int64_t M, int K, int N,
-                                                            int64_t slab_rows, int tiles_n, int tiles, int64_t total,
-                                                            bool p_vec) {
+template <int kTwBK, int kTwStages, int WM, int WN>
+__global__ __launch_bounds__(64 * WM * WN, 1) void gemm_tn_dma_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                                      const bf16_t* __restrict__ G, int64_t ldg,
+                                                                      float* __restrict__ P, int64_t M, int K, int N,
+                                                                      int64_t slab_rows, int tiles_n, int tiles,
+                                                                      int64_t total, bool p_vec) {
   constexpr int kTwPart = kTwBK * 256;                       // elements of a tile's A part (and of its G part)
-  constexpr int NW = 8, TM = 4, TN = 2, LP = kTwBK / 16;     // LP: regions (= loads) per wave, part and tile
+  constexpr int NW = WM * WN, TM = 8 / WM, TN = 8 / WN;      // waves; 32 x 32 accumulator blocks per wave
+  constexpr int LP = kTwBK / 2 / NW;                         // regions (= loads) per wave, part and tile
+  static_assert(LP * NW * 2 == kTwBK, "whole regions per wave");
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const int t = threadIdx.x, w = t >> 6, lane = t & 63, wm = w >> 2, wn = w & 3;
+  const int t = threadIdx.x, w = t >> 6, lane = t & 63, wm = w / WN, wn = w % WN;
   const int64_t item = xcd_order(blockIdx.x, total);
   const int tile = (int)(item % tiles);
   const int64_t slab = item / tiles;
@@ -576,22 +580,23 @@ __global__ __launch_bounds__(512, 1) void gemm_tn_dma_kernel(const bf16_t* __res
   v16f acc[TM][TN];
   zero_acc<TM, TN>(acc);
 
-  // what this lane fetches: tile row 2 (w + 8 j) + lane / 32 of each part, the chunk that belongs in slot lane % 32
-  const int frow = 2 * w + (lane >> 5);                      // its tile row in load j is frow + 16 j
-  const int fchunk = (lane & 31) ^ (((frow & 3) << 2) | (((frow >> 3) & 1) << 4));
-  int col_a = k0 + fchunk * 8, col_g = n0 + fchunk * 8;
-  if (col_a >= K) col_a = 0;
-  if (col_g >= N) col_g = 0;
+  // what this lane fetches in load j of a part: tile row 2 (w + NW j) + lane / 32, the chunk that belongs in slot
+  // lane % 32 of that row
   auto issue = [&](int mt) {
-    const int64_t m0 = m_begin + (int64_t)(mt < n_mt ? mt : 0) * kTwBK + frow;
+    const int64_t m0 = m_begin + (int64_t)(mt < n_mt ? mt : 0) * kTwBK;
     unsigned char* dst = smem_raw + (mt % kTwStages) * (2 * kTwPart * 2) + w * 1024;
 #pragma unroll
     for (int j = 0; j < 2 * LP; ++j) {
       const bool is_a = j < LP;
-      int64_t row = m0 + 16 * (is_a ? j : j - LP);
+      const int jj = is_a ? j : j - LP;
+      const int frow = 2 * (jj * NW + w) + (lane >> 5);
+      const int fchunk = (lane & 31) ^ (((frow & 3) << 2) | (((frow >> 3) & 1) << 4));
+      int col = (is_a ? k0 : n0) + fchunk * 8;
+      if (col >= (is_a ? K : N)) col = 0;
+      int64_t row = m0 + frow;
       row = row < M ? row : M - 1;
-      const bf16_t* src = is_a ? A + row * lda + col_a : G + row * ldg + col_g;
-      const int region = is_a ? j * NW : kTwBK / 2 + (j - LP) * NW;   // + w, already in dst
+      const bf16_t* src = is_a ? A + row * lda + col : G + row * ldg + col;
+      const int region = (is_a ? 0 : kTwBK / 2) + jj * NW;            // + w, already in dst
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                        (__attribute__((address_space(3))) void*)(dst + region * 1024), 16, 0, 0);
     }
@@ -603,9 +608,9 @@ __global__ __launch_bounds__(512, 1) void gemm_tn_dma_kernel(const bf16_t* __res
   const int low = (2 * g16 + ((t16 & 3) >> 1)) * 16 + (t16 & 1) * 8 + (8 * kg + (t16 >> 2)) * 512;
   int off_a[TM], off_g[TN];                                  // byte offsets inside a part, reduction row 0
 #pragma unroll
-  for (int tm = 0; tm < TM; ++tm) off_a[tm] = (((wm * 128 + tm * 32) >> 3) ^ swz) * 16 + low;
+  for (int tm = 0; tm < TM; ++tm) off_a[tm] = ((((wm * TM + tm) * 32) >> 3) ^ swz) * 16 + low;
 #pragma unroll
-  for (int tn = 0; tn < TN; ++tn) off_g[tn] = (((wn * 64 + tn * 32) >> 3) ^ swz) * 16 + low + kTwPart * 2;
+  for (int tn = 0; tn < TN; ++tn) off_g[tn] = ((((wn * TN + tn) * 32) >> 3) ^ swz) * 16 + low + kTwPart * 2;
 
 #pragma unroll
   for (int d = 0; d < kTwStages - 1; ++d) issue(d);
@@ -616,31 +621,38 @@ __global__ __launch_bounds__(512, 1) void gemm_tn_dma_kernel(const bf16_t* __res
     const int64_t valid = m_end - (m_begin + (int64_t)mt * kTwBK);
     if (valid < kTwBK) {                                     // the same for every thread; only a slab's last tile
       const int first = (int)valid;                          // rows first .. 63 of both parts
-      for (int p = t; p < (kTwBK - first) * 32; p += 512) {
+      for (int p = t; p < (kTwBK - first) * 32; p += 64 * NW) {
         *reinterpret_cast<uint4*>(cur + first * 512 + p * 16) = make_uint4(0u, 0u, 0u, 0u);
         *reinterpret_cast<uint4*>(cur + kTwPart * 2 + first * 512 + p * 16) = make_uint4(0u, 0u, 0u, 0u);
       }
       __syncthreads();
     }
     issue(mt + kTwStages - 1);
+    // the operands of step ks + 1 are read while the matrix instructions of step ks run
+    bf16x8 a[2][TM], b[2][TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) a[0][tm] = read_tr8(cur + off_a[tm]);
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) b[0][tn] = read_tr8(cur + off_g[tn]);
 #pragma unroll
     for (int ks = 0; ks < kTwBK / 16; ++ks) {
-      bf16x8 a[TM], b[TN];
+      if (ks + 1 < kTwBK / 16) {
 #pragma unroll
-      for (int tm = 0; tm < TM; ++tm) a[tm] = read_tr8(cur + off_a[tm] + ks * 16 * 512);
+        for (int tm = 0; tm < TM; ++tm) a[(ks + 1) & 1][tm] = read_tr8(cur + off_a[tm] + (ks + 1) * 16 * 512);
 #pragma unroll
-      for (int tn = 0; tn < TN; ++tn) b[tn] = read_tr8(cur + off_g[tn] + ks * 16 * 512);
+        for (int tn = 0; tn < TN; ++tn) b[(ks + 1) & 1][tn] = read_tr8(cur + off_g[tn] + (ks + 1) * 16 * 512);
+      }
 #pragma unroll
       for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn)
-          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][tm], b[ks & 1][tn], acc[tm][tn], 0, 0, 0);
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);                        // the trailing fetch has landed before LDS is reused
   float* Pslab = P + slab * (int64_t)K * N;
-  store_rows<EPI_NONE, TM, TN, float>(acc, reinterpret_cast<float*>(smem_raw), Pslab, N, k0 + wm * 128, n0 + wn * 64, K,
-                                      N, p_vec, 0.f, nullptr, 0, false);
+  store_rows<EPI_NONE, TM, TN, float>(acc, reinterpret_cast<float*>(smem_raw), Pslab, N, k0 + wm * 32 * TM,
+                                      n0 + wn * 32 * TN, K, N, p_vec, 0.f, nullptr, 0, false);
 }
 
 // out[r][c] (leading dimension ld_out) = transpose ? W[c][r] : W[r][c], rounded to bfloat16; zero for
@@ -795,12 +807,12 @@ int gemm_tn_bf16(const void* A, int64_t lda, const void* G, int64_t ldg, float* 
   if (wide) {
     constexpr int kTwBK = 64, kTwStages = 2;
     constexpr size_t tiles_bytes = (size_t)kTwStages * 2 * kTwBK * 256 * sizeof(bf16_t);
-    constexpr size_t stage_bytes = (size_t)8 * 32 * (32 * 2 + 8) * sizeof(float);           // epilogue staging, reuses them
-    constexpr size_t kTwSmem = tiles_bytes > stage_bytes ? tiles_bytes : stage_bytes;
-    static_assert(kTwSmem <= 160 * 1024, "one block's tiles fit the CU's LDS");
+    constexpr size_t kTwSmem = tiles_bytes;                  // the epilogue staging (at most 70 KB) reuses them
+    static_assert(kTwSmem <= 160 * 1024 && kTwSmem >= 4u * 32 * (32 * 4 + 8) * sizeof(float), "LDS of one block");
     if (!gemm_tn_bf16_wide_ok(A, lda, G, ldg, K, N, full_rows) || slab_rows % kTwBK != 0 || M < 1)
       return set_error(GAD_ERR_UNSUPPORTED, "the 256 x 256 weight-gradient kernel does not take these operands");
-    auto kern = gemm_tn_dma_kernel<kTwBK, kTwStages>;
+    auto kern = gemm_tn_dma_kernel<kTwBK, kTwStages, 2, 4>;
+    constexpr int threads = 512;
     static std::atomic<bool> wide_attr_set;          // set once; setting it twice is harmless
     if (!wide_attr_set.load(std::memory_order_acquire)) {
       GAD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -810,11 +822,10 @@ int gemm_tn_bf16(const void* A, int64_t lda, const void* G, int64_t ldg, float* 
     const int tiles_n = (int)ceil_div(N, 256);
     const int tiles = (int)ceil_div(K, 256) * tiles_n;
     const int64_t total = (int64_t)tiles * n_slabs;
-    GAD_GRID_CHECK(total, 512);
+    GAD_GRID_CHECK(total, threads);
     // every slab of the partial products starts on a 16-byte boundary when K N is a multiple of 4
     const bool pv = N % 4 == 0 && (reinterpret_cast<uintptr_t>(partials) & 15u) == 0 && ((int64_t)K * N) % 4 == 0;
-    kern<<<(unsigned)total, 512, kTwSmem, s>>>(a, lda, g, ldg, partials, M, K, N, slab_rows, tiles_n,
-                                                             tiles, total, pv);
+    kern<<<(unsigned)total, threads, kTwSmem, s>>>(a, lda, g, ldg, partials, M, K, N, slab_rows, tiles_n, tiles, total, pv);
     GAD_LAUNCH_CHECK();
     return GAD_OK;
   }
