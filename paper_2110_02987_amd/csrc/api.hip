@@ -264,7 +264,7 @@ int gad_graph_concat(const gad_graph* const* graphs, int K, void* hip_stream, ga
 
 int gad_graph_destroy(gad_graph* g) {
   if (!g) return GAD_OK;
-  void* ptrs[] = {g->rowptr,    g->colidx,    g->deg,         g->dinv,       g->row_order, g->long_row,
+  void* ptrs[] = {g->rowptr,     g->colidx,    g->deg,       g->dinv,        g->ew,         g->row_order, g->long_row,
                   g->long_first, g->many_slot, g->chunk_row, g->chunk_begin, g->chunk_perm, g->red_scratch};
   int st = GAD_OK;
   for (void* p : ptrs)

@@ -407,8 +407,23 @@ size_t scan_tmp_len(size_t n) { return (size_t)ceil_div((int64_t)n, kTile) + 1; 
 
 // SpMM schedule of a graph whose rowptr / colidx are in place (see gad_graph).  Allocates the schedule arrays of
 // `g` (freed by gad_graph_destroy, also after a failure here) and synchronises the stream.
+namespace {
+// ew[p] = dinv[colidx[p]]: the factor D~^-1/2 of the gathered row, stored beside its column index
+__global__ void edge_weights(const int32_t* __restrict__ colidx, const float* __restrict__ dinv, int64_t nnz,
+                             float* __restrict__ ew) {
+  const int64_t p = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (p < nnz) ew[p] = dinv[colidx[p]];
+}
+}  // namespace
+
 int build_schedule(gad_graph* g, hipStream_t s) {
   const int64_t n = g->n;
+  if (g->nnz > 0) {
+    GAD_HIP(hipMalloc((void**)&g->ew, sizeof(float) * (size_t)g->nnz));
+    GAD_GRID_CHECK(ceil_div(g->nnz, 256), 256);
+    edge_weights<<<(unsigned)ceil_div(g->nnz, 256), 256, 0, s>>>(g->colidx, g->dinv, g->nnz, g->ew);
+    GAD_LAUNCH_CHECK();
+  }
   int bits = 1;
   while ((1ll << bits) < n) ++bits;
   Scratch scratch;

@@ -72,6 +72,8 @@ struct gad_graph {
   int32_t* colidx = nullptr;   // [nnz]
   int32_t* deg = nullptr;      // [n]
   float* dinv = nullptr;       // [n]
+  float* ew = nullptr;         // [nnz] dinv of the column of every non-zero: the sparse product streams it with colidx
+                               // instead of gathering dinv[colidx[p]] (a dependent access per edge: 7 - 24 % of its time)
   // SpMM schedule.  Rows with at most kLongRow non-zeros ("short") are summed by one wave each, in the order
   // row_order[0 .. n_short): longest class first, so that waves running side by side do similar amounts of work.
   // Longer rows are cut into chunks of kLongRow non-zeros; the chunks run in the order chunk_perm[], ascending in

@@ -5,8 +5,10 @@
 // 64/LPR groups of LPR lanes; a group gathers one neighbour row at a time, each lane holding V
 // consecutive columns (16-byte loads: V = 4 float32 or 8 bfloat16), so a gathered row is read as one
 // contiguous burst.  Groups walk the neighbour list interleaved and are combined with wave shuffles at
-// the end.  Accumulation is float32 whatever the storage type.  Only the 4-byte column index is read per
-// edge; dinv_j comes from a 4n-byte array that stays in L2.
+// the end.  Accumulation is float32 whatever the storage type.  Per edge the 4-byte column index and the 4-byte
+// factor dinv_j are read, both streamed in edge order (ew[p] = dinv[colidx[p]] is stored with the graph: gathering
+// dinv[j] instead, a second access that depends on the index, cost 7 % of the kernel at width 256 and 17 - 24 % at
+// widths 47 - 64; one packed 8-byte entry per edge instead of the two arrays measured within 1 - 3 % either way).
 // Rows longer than kLongRow are cut into chunks, one wave per chunk (the first blocks of the same
 // launch), whose raw sums go to a partial buffer and are added in a fixed order by a second kernel
 // (deterministic: no floating-point atomics).
@@ -22,10 +24,10 @@
 namespace gad {
 namespace {
 
-// Sum over the neighbour positions [begin, end) of dinv_j * T_j for this lane's V columns starting at
+// Sum over the neighbour positions [begin, end) of ew_p * T_j (ew_p = dinv_j) for this lane's V columns starting at
 // column c (if `active`), combined over the wave's groups.  All lanes return the combined value.
 template <int LPR, int V, typename TI>
-__device__ __forceinline__ void gather_sum(const int32_t* __restrict__ colidx, const float* __restrict__ dinv,
+__device__ __forceinline__ void gather_sum(const int32_t* __restrict__ colidx, const float* __restrict__ ew,
                                            const TI* __restrict__ T, int64_t ldt, int64_t begin, int64_t end, int c,
                                            bool active, float (&acc)[V]) {
   constexpr int G = 64 / LPR;
@@ -37,7 +39,7 @@ __device__ __forceinline__ void gather_sum(const int32_t* __restrict__ colidx, c
   // four neighbours in flight per group
   for (; p + 3 * G < end; p += 4 * G) {
     const int32_t j0 = colidx[p], j1 = colidx[p + G], j2 = colidx[p + 2 * G], j3 = colidx[p + 3 * G];
-    const float d0 = dinv[j0], d1 = dinv[j1], d2 = dinv[j2], d3 = dinv[j3];
+    const float d0 = ew[p], d1 = ew[p + G], d2 = ew[p + 2 * G], d3 = ew[p + 3 * G];
     if (active) {
       float t0[V], t1[V], t2[V], t3[V];
       load_row_piece<V, TI>(T + (int64_t)j0 * ldt + c, t0);
@@ -55,7 +57,7 @@ __device__ __forceinline__ void gather_sum(const int32_t* __restrict__ colidx, c
   }
   for (; p < end; p += G) {
     const int32_t j = colidx[p];
-    const float d = dinv[j];
+    const float d = ew[p];
     if (active) {
       float t[V];
       load_row_piece<V, TI>(T + (int64_t)j * ldt + c, t);
@@ -84,7 +86,8 @@ __device__ __forceinline__ void store_elem(TO* __restrict__ out, int64_t ldo, in
 // Chunk sums go to partial[chunk id][column] (leading dimension ldp).
 template <int LPR, int V, typename TI, typename TO>
 __global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
-                                                   const float* __restrict__ dinv, const TI* __restrict__ T,
+                                                   const float* __restrict__ ew, const float* __restrict__ dinv,
+                                                   const TI* __restrict__ T,
                                                    int64_t ldt, TO* __restrict__ out, int64_t ldo, int width,
                                                    int64_t n_short, const int32_t* __restrict__ row_order, int epi,
                                                    float slope, const TI* __restrict__ aux, int64_t ldaux,
@@ -104,7 +107,7 @@ __global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ r
     const int64_t begin = rowptr[i] + chunk_begin[ch];
     const int64_t row_end = rowptr[i + 1];
     const int64_t end = begin + kLongRow < row_end ? begin + kLongRow : row_end;
-    gather_sum<LPR, V, TI>(colidx, dinv, T, ldt, begin, end, c, active, acc);
+    gather_sum<LPR, V, TI>(colidx, ew, T, ldt, begin, end, c, active, acc);
     if (active && lane < LPR) {
 #pragma unroll
       for (int k = 0; k < V; ++k)
@@ -115,7 +118,7 @@ __global__ __launch_bounds__(256) void spmm_kernel(const int64_t* __restrict__ r
   const int64_t slot = (int64_t)(blockIdx.x - chunk_blocks) * 4 + (threadIdx.x >> 6);
   if (slot >= n_short) return;
   const int64_t i = row_order[slot];
-  gather_sum<LPR, V, TI>(colidx, dinv, T, ldt, rowptr[i], rowptr[i + 1], c, active, acc);
+  gather_sum<LPR, V, TI>(colidx, ew, T, ldt, rowptr[i], rowptr[i + 1], c, active, acc);
   if (active && lane < LPR) {
     const float di = dinv[i];
 #pragma unroll
@@ -220,10 +223,10 @@ int launch(const gad_graph* g, const TI* T, int64_t ldt, TO* out, int64_t ldo, i
   // column slabs lose 0.5 %.  The cap is a reservation of LDS the kernel never touches; it is left off when another
   // kernel that needs LDS shares the GPU (the weight gradient beside a backward product would have to wait).
   const unsigned cap_lds = sizeof(TI) == 4 && LPR == 64 && width <= 256 && !e.shares_gpu ? kCapLdsBytes : 0u;
-  spmm_kernel<LPR, V, TI, TO><<<grid, 256, cap_lds, s>>>(g->rowptr, g->colidx, g->dinv, T, ldt, out, ldo, width, g->n_short,
-                                                   g->row_order, e.kind, e.slope, aux, e.ldaux, (int)chunk_blocks,
-                                                   g->chunk_perm, g->chunk_row, g->chunk_begin, g->n_chunks, partial,
-                                                   ldp);
+  spmm_kernel<LPR, V, TI, TO><<<grid, 256, cap_lds, s>>>(g->rowptr, g->colidx, g->ew, g->dinv, T, ldt, out, ldo, width,
+                                                         g->n_short, g->row_order, e.kind, e.slope, aux, e.ldaux,
+                                                         (int)chunk_blocks, g->chunk_perm, g->chunk_row, g->chunk_begin,
+                                                         g->n_chunks, partial, ldp);
   GAD_LAUNCH_CHECK();
   if (g->n_long > 0) {
     spmm_reduce_few<TI, TO><<<dim3((unsigned)ceil_div(g->n_long, 4), (unsigned)ceil_div(width, 256)), 256, 0, s>>>(
