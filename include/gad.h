@@ -81,6 +81,8 @@ const char* gad_last_error(void);
  * Result (bit-exact, deterministic): rowptr int64[n+1], colidx int32[nnz] with strictly ascending
  * columns per row and exactly one self loop per row; deg int32[n] (self loop not counted);
  * dinv float32[n] = (1 + deg)^-1/2 evaluated in float64 and rounded once.
+ * Device memory of a graph: a little over 8 bytes per non-zero (the column index, the factor dinv[column] again
+ * beside it for the sparse product, scheduling data of the rows above 128 non-zeros) and about 24 bytes per row.
  * Errors: NULL pointers (src/dst may be NULL iff n_edges_in = 0, halo_ids iff n_halo = 0),
  * n_local + n_halo = 0 or > 2^31 - 2, 2 * n_edges_in + n >= 2^31, ids out of range, duplicate ids.
  * Synchronises hip_stream (sizes must be read back to allocate the CSR). */
